@@ -1,0 +1,133 @@
+/*
+ * race_attn.h - C ABI of the MI355X (gfx950) RACE Attention library.
+ *
+ * RACE Attention (arXiv 2510.04008) replaces softmax attention by a linear-time estimator
+ * of sharpened angular-kernel attention.  For every head, L independent tables each draw
+ * P Gaussian hyperplanes; a query or key x is softly assigned to the R = 2^P corners of
+ * the hypercube, phi_r(x) = softmax_r(beta * tanh(W x) . v_r)  (Algorithm 1, steps 2-4);
+ * keys and values are accumulated into per-table bucket statistics A = Phi_K^T 1 and
+ * B = Phi_K^T V (step 5); every query reads them back, Num = (1/L) sum_l Phi_Q B,
+ * Den = (1/L) sum_l Phi_Q A, O = Num / Den (steps 7-8).  The causal variant
+ * (Algorithm 2, appendix "Causal RACE Attention") lets query t read the statistics of
+ * keys 1..t only (inclusive: token t is added before it reads).
+ *
+ * Conventions common to all entry points
+ *   - Tensors Q, K, V, O, dO, dQ, dK, dV are DEVICE pointers to (B, H, N, d) arrays,
+ *     row-major with d contiguous, of the element type named by desc->dtype.
+ *     den is a DEVICE pointer to (B, H, N) float.  Buffers must not overlap.
+ *   - proj_seeds is a HOST pointer to H 64-bit seeds, one per head, read during the call.
+ *     W is shared by the batch.  Head h uses the (L*P, d) matrix whose row l*P+t is
+ *     hyperplane t of table l, drawn i.i.d. N(0,1) (Algorithm 1, step 2) by the generator
+ *     documented at race_attn_expand_projection().
+ *   - Corner r of the hypercube has v_{r,t} = +1 iff bit t of r is set (t = 0 is the least
+ *     significant bit and belongs to row l*P+0 of W).
+ *   - sharpening is the temperature beta of Algorithms 1/2.  Q and K are used as given:
+ *     no normalisation and no 1/sqrt(d) scaling happens inside the layer.
+ *   - The caller owns every buffer, including the workspace (device memory, 256-byte
+ *     aligned, at least race_attn_workspace_bytes() bytes; contents are scratch).  The
+ *     library allocates no device memory, never synchronises the stream and launches all
+ *     work on the given stream.  Calls that share a workspace must be stream-ordered.
+ *   - Every argument is checked before anything is launched; on any error status other
+ *     than RACE_ERR_HIP the outputs are untouched.  N == 0 is a valid no-op.
+ *   - Arithmetic: products of bf16 operands are accumulated in fp32; the fp32 element
+ *     type computes in fp32 throughout.
+ */
+#ifndef RACE_ATTN_H
+#define RACE_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    RACE_OK = 0,
+    RACE_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, non-finite beta, bad enum   */
+    RACE_ERR_UNSUPPORTED = 2, /* a valid shape outside what the kernels were built for         */
+    RACE_ERR_WORKSPACE = 3,   /* workspace null, misaligned or smaller than required           */
+    RACE_ERR_HIP = 4          /* a HIP call failed; text from race_attn_last_error()           */
+} race_status_t;
+
+typedef enum { RACE_F32 = 0, RACE_BF16 = 1 } race_dtype_t;
+
+/* ABI-identical to hipStream_t (a pointer to HIP's opaque stream object); 0 = default stream. */
+typedef struct ihipStream_t *race_stream_t;
+
+/* Problem statement of Algorithms 1/2: inputs Q, K, V in R^{N x d}, L tables, P hyperplanes,
+ * temperature beta; batched over (B, H). */
+typedef struct {
+    int32_t B, H;     /* batch, heads (>= 1)                                                   */
+    int64_t N;        /* tokens per sequence (>= 0)                                            */
+    int32_t d;        /* head dimension: multiple of 8, 8 <= d <= 256                          */
+    int32_t L, P;     /* tables (>= 1), hyperplanes per table (1..8); R = 1 << P               */
+    float sharpening; /* beta > 0, finite                                                      */
+    int32_t causal;   /* 0: Algorithm 1 (all keys); 1: Algorithm 2 (keys j <= i)               */
+    int32_t dtype;    /* race_dtype_t of Q, K, V, O, dO, dQ, dK, dV                            */
+    int64_t chunk;    /* tokens per scan segment: the sequence is cut into segments whose
+                         bucket statistics are combined by a prefix scan; 0 = choose           */
+} race_attn_desc_t;
+
+/* Bytes of device workspace that race_attn_fwd / race_attn_bwd / race_attn_debug_buckets need
+ * for this descriptor (one figure covers all three).  Returns 0 for an invalid or unsupported
+ * descriptor (and for N == 0). */
+size_t race_attn_workspace_bytes(const race_attn_desc_t *desc);
+
+/* Forward pass, Algorithm 1 (causal == 0) or Algorithm 2 (causal == 1).
+ * in : Q, K, V (device), proj_seeds (host, H entries)
+ * out: O (device, same type as V), den (device, float (B,H,N)): Den_i including the 1/L of
+ *      Algorithm 1 step 7; the backward pass needs O and den. */
+race_status_t race_attn_fwd(const race_attn_desc_t *desc, const void *Q, const void *K, const void *V,
+                            const uint64_t *proj_seeds, void *O, float *den,
+                            void *workspace, size_t workspace_bytes, race_stream_t stream);
+
+/* Backward pass of the same operator: given dO = d(loss)/dO, O and den from race_attn_fwd on the
+ * same inputs, writes dQ, dK, dV.  The paper trains through the differentiable soft assignment
+ * (Section 3.3) and prints no gradient; the formulas are the chain rule through Algorithms 1/2:
+ * read-out, bucket accumulation (a suffix scan in the causal case), corner softmax, tanh and W.
+ * W is a fixed random matrix and gets no gradient. */
+race_status_t race_attn_bwd(const race_attn_desc_t *desc, const void *Q, const void *K, const void *V,
+                            const void *O, const float *den, const void *dO,
+                            const uint64_t *proj_seeds, void *dQ, void *dK, void *dV,
+                            void *workspace, size_t workspace_bytes, race_stream_t stream);
+
+/* Host-only: expands the seeds into W_host (HOST, float, (H, L*P, d)), the values the kernels
+ * multiply with (Algorithm 1, step 2).  Generator: element e = row*d + col of head h is Gaussian
+ * number (e mod 4) of block e/4 of Philox-4x32-10 with key = (low, high) 32 bits of the head's
+ * seed and counter = (block low, block high, 0, 0); the block's words (x0,x1,x2,x3) give
+ * Box-Muller pairs from (x0,x1) and (x2,x3) with u = (x + 0.5) / 2^32, evaluated in fp64:
+ * sqrt(-2 ln u1) * (cos, sin)(2 pi u2); rounded to fp32 (nearest even), and for RACE_BF16 once
+ * more to bf16 (nearest even, returned widened to float).  Only H, L, P, d, dtype of desc are used. */
+race_status_t race_attn_expand_projection(const race_attn_desc_t *desc, const uint64_t *proj_seeds,
+                                          float *W_host);
+
+/* Debug tap of the projection and soft assignment (Algorithm 1, steps 2-4) of one tensor X (Q or K):
+ * codes (device, uint8 (B,H,N,L)): bit t = [<w_t, x> >= 0], i.e. the hard hash sign(W x) of
+ * Section 3.3, which is also the arg-max corner of phi;  phi (device, float (B,H,N,L,R)) or NULL.
+ * Runs the projection arithmetic of the production kernels.  Needs no workspace beyond
+ * H*L*P*d floats + 256 bytes. */
+race_status_t race_attn_debug_hash(const race_attn_desc_t *desc, const void *X, const uint64_t *proj_seeds,
+                                   uint8_t *codes, float *phi,
+                                   void *workspace, size_t workspace_bytes, race_stream_t stream);
+
+/* Debug tap of the bucket statistics of Algorithm 1, step 5, over all N keys (whatever causal
+ * says): A (device, float (B,H,L,R)) and Bsum (device, float (B,H,L,R,d)). */
+race_status_t race_attn_debug_buckets(const race_attn_desc_t *desc, const void *K, const void *V,
+                                      const uint64_t *proj_seeds, float *A, float *Bsum,
+                                      void *workspace, size_t workspace_bytes, race_stream_t stream);
+
+/* Static, never-null description of a status code. */
+const char *race_status_string(race_status_t status);
+
+/* Text of the most recent HIP failure seen by the calling thread ("" if none). */
+const char *race_attn_last_error(void);
+
+/* Which kernel family a descriptor is served by: 0 = invalid/unsupported, 1 = generic fp32-math
+ * kernels, 2 = bf16 MFMA kernels.  Informational (benchmarks and tests report it). */
+int race_attn_kernel_family(const race_attn_desc_t *desc);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RACE_ATTN_H */

@@ -1,0 +1,194 @@
+"""Thin ctypes binding of librace_attn.so: argument marshalling only.  Every step of the path runs in
+the library's HIP kernels; torch is used for device memory and streams.  Names follow include/race_attn.h.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librace_attn.so")
+
+RACE_OK, RACE_ERR_INVALID_ARG, RACE_ERR_UNSUPPORTED, RACE_ERR_WORKSPACE, RACE_ERR_HIP = range(5)
+RACE_F32, RACE_BF16 = 0, 1
+
+
+class RaceAttnDesc(ctypes.Structure):
+    """race_attn_desc_t"""
+    _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("N", ctypes.c_int64), ("d", ctypes.c_int32),
+                ("L", ctypes.c_int32), ("P", ctypes.c_int32), ("sharpening", ctypes.c_float),
+                ("causal", ctypes.c_int32), ("dtype", ctypes.c_int32), ("chunk", ctypes.c_int64)]
+
+
+class RaceAttnError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        text = lib().race_status_string(status).decode()
+        detail = lib().race_attn_last_error().decode() if status == RACE_ERR_HIP else ""
+        super().__init__("%s: %s%s" % (where, text, (" (" + detail + ")") if detail else ""))
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Loads the shared library; builds it first only if no built library is present."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            from . import build as _build
+            _build.build()
+        L = ctypes.CDLL(LIB_PATH)
+        vp, u64p, fp, u8p = ctypes.c_void_p, ctypes.POINTER(ctypes.c_uint64), ctypes.c_void_p, ctypes.c_void_p
+        dp = ctypes.POINTER(RaceAttnDesc)
+        L.race_attn_workspace_bytes.argtypes = [dp]
+        L.race_attn_workspace_bytes.restype = ctypes.c_size_t
+        L.race_attn_kernel_family.argtypes = [dp]
+        L.race_attn_kernel_family.restype = ctypes.c_int
+        L.race_attn_fwd.argtypes = [dp, vp, vp, vp, u64p, vp, fp, vp, ctypes.c_size_t, vp]
+        L.race_attn_fwd.restype = ctypes.c_int
+        L.race_attn_bwd.argtypes = [dp, vp, vp, vp, vp, fp, vp, u64p, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.race_attn_bwd.restype = ctypes.c_int
+        L.race_attn_expand_projection.argtypes = [dp, u64p, ctypes.POINTER(ctypes.c_float)]
+        L.race_attn_expand_projection.restype = ctypes.c_int
+        L.race_attn_debug_hash.argtypes = [dp, vp, u64p, u8p, fp, vp, ctypes.c_size_t, vp]
+        L.race_attn_debug_hash.restype = ctypes.c_int
+        L.race_attn_debug_buckets.argtypes = [dp, vp, vp, u64p, fp, fp, vp, ctypes.c_size_t, vp]
+        L.race_attn_debug_buckets.restype = ctypes.c_int
+        L.race_status_string.argtypes = [ctypes.c_int]
+        L.race_status_string.restype = ctypes.c_char_p
+        L.race_attn_last_error.argtypes = []
+        L.race_attn_last_error.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def make_desc(B: int, H: int, N: int, d: int, L: int, P: int, sharpening: float, causal: bool,
+              dtype: int, chunk: int = 0) -> RaceAttnDesc:
+    return RaceAttnDesc(B, H, N, d, L, P, float(sharpening), int(bool(causal)), int(dtype), int(chunk))
+
+
+def _seeds(seeds: Sequence[int]):
+    arr = (ctypes.c_uint64 * len(seeds))(*[int(s) & 0xFFFFFFFFFFFFFFFF for s in seeds])
+    return arr
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def _elem_dtype(desc):
+    torch = _torch()
+    return torch.float32 if desc.dtype == RACE_F32 else torch.bfloat16
+
+
+def _check_tensor(t, desc, name, shape=None, dtype=None):
+    shape = shape or (desc.B, desc.H, desc.N, desc.d)
+    dtype = dtype or _elem_dtype(desc)
+    if not t.is_cuda or not t.is_contiguous() or tuple(t.shape) != tuple(shape) or t.dtype != dtype:
+        raise ValueError("%s must be a contiguous device tensor of shape %s and dtype %s" % (name, shape, dtype))
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return _torch().cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _workspace(desc, workspace, device):
+    torch = _torch()
+    need = race_attn_workspace_bytes(desc)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=device)
+    return workspace, workspace.numel()
+
+
+def race_attn_workspace_bytes(desc: RaceAttnDesc) -> int:
+    return int(lib().race_attn_workspace_bytes(ctypes.byref(desc)))
+
+
+def race_attn_kernel_family(desc: RaceAttnDesc) -> int:
+    return int(lib().race_attn_kernel_family(ctypes.byref(desc)))
+
+
+def race_attn_expand_projection(desc: RaceAttnDesc, proj_seeds: Sequence[int]) -> np.ndarray:
+    out = np.empty((desc.H, desc.L * desc.P, desc.d), dtype=np.float32)
+    st = lib().race_attn_expand_projection(ctypes.byref(desc), _seeds(proj_seeds),
+                                           out.ctypes.data_as(ctypes.POINTER(ctypes.c_float)))
+    if st != RACE_OK:
+        raise RaceAttnError(st, "race_attn_expand_projection")
+    return out
+
+
+def race_attn_fwd(desc: RaceAttnDesc, Q, K, V, proj_seeds: Sequence[int], O=None, den=None,
+                  workspace=None, stream=None):
+    torch = _torch()
+    for t, n in ((Q, "Q"), (K, "K"), (V, "V")):
+        _check_tensor(t, desc, n)
+    if O is None:
+        O = torch.empty_like(V)
+    if den is None:
+        den = torch.empty((desc.B, desc.H, desc.N), dtype=torch.float32, device=V.device)
+    _check_tensor(O, desc, "O")
+    _check_tensor(den, desc, "den", (desc.B, desc.H, desc.N), torch.float32)
+    workspace, nbytes = _workspace(desc, workspace, V.device)
+    st = lib().race_attn_fwd(ctypes.byref(desc), Q.data_ptr(), K.data_ptr(), V.data_ptr(), _seeds(proj_seeds),
+                             O.data_ptr(), den.data_ptr(), workspace.data_ptr(), nbytes, _stream(stream))
+    if st != RACE_OK:
+        raise RaceAttnError(st, "race_attn_fwd")
+    return O, den
+
+
+def race_attn_bwd(desc: RaceAttnDesc, Q, K, V, O, den, dO, proj_seeds: Sequence[int], dQ=None, dK=None, dV=None,
+                  workspace=None, stream=None):
+    torch = _torch()
+    for t, n in ((Q, "Q"), (K, "K"), (V, "V"), (O, "O"), (dO, "dO")):
+        _check_tensor(t, desc, n)
+    _check_tensor(den, desc, "den", (desc.B, desc.H, desc.N), torch.float32)
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(K) if dK is None else dK
+    dV = torch.empty_like(V) if dV is None else dV
+    for t, n in ((dQ, "dQ"), (dK, "dK"), (dV, "dV")):
+        _check_tensor(t, desc, n)
+    workspace, nbytes = _workspace(desc, workspace, V.device)
+    st = lib().race_attn_bwd(ctypes.byref(desc), Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(),
+                             den.data_ptr(), dO.data_ptr(), _seeds(proj_seeds), dQ.data_ptr(), dK.data_ptr(),
+                             dV.data_ptr(), workspace.data_ptr(), nbytes, _stream(stream))
+    if st != RACE_OK:
+        raise RaceAttnError(st, "race_attn_bwd")
+    return dQ, dK, dV
+
+
+def race_attn_debug_hash(desc: RaceAttnDesc, X, proj_seeds: Sequence[int], want_phi: bool = False,
+                         workspace=None, stream=None):
+    torch = _torch()
+    _check_tensor(X, desc, "X")
+    codes = torch.empty((desc.B, desc.H, desc.N, desc.L), dtype=torch.uint8, device=X.device)
+    phi = torch.empty((desc.B, desc.H, desc.N, desc.L, 1 << desc.P), dtype=torch.float32,
+                      device=X.device) if want_phi else None
+    workspace, nbytes = _workspace(desc, workspace, X.device)
+    st = lib().race_attn_debug_hash(ctypes.byref(desc), X.data_ptr(), _seeds(proj_seeds), codes.data_ptr(),
+                                    phi.data_ptr() if want_phi else None, workspace.data_ptr(), nbytes,
+                                    _stream(stream))
+    if st != RACE_OK:
+        raise RaceAttnError(st, "race_attn_debug_hash")
+    return codes, phi
+
+
+def race_attn_debug_buckets(desc: RaceAttnDesc, K, V, proj_seeds: Sequence[int], workspace=None, stream=None):
+    torch = _torch()
+    _check_tensor(K, desc, "K")
+    _check_tensor(V, desc, "V")
+    R = 1 << desc.P
+    A = torch.empty((desc.B, desc.H, desc.L, R), dtype=torch.float32, device=K.device)
+    Bsum = torch.empty((desc.B, desc.H, desc.L, R, desc.d), dtype=torch.float32, device=K.device)
+    workspace, nbytes = _workspace(desc, workspace, K.device)
+    st = lib().race_attn_debug_buckets(ctypes.byref(desc), K.data_ptr(), V.data_ptr(), _seeds(proj_seeds),
+                                       A.data_ptr(), Bsum.data_ptr(), workspace.data_ptr(), nbytes, _stream(stream))
+    if st != RACE_OK:
+        raise RaceAttnError(st, "race_attn_debug_buckets")
+    return A, Bsum

@@ -1,0 +1,69 @@
+// Internal declarations shared by the translation units of the library (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "race_attn.h"
+
+namespace race {
+
+constexpr int kFamilyNone = 0;
+constexpr int kFamilySimple = 1;   // generic kernels, fp32 arithmetic on the vector ALUs
+constexpr int kFamilyMfma = 2;     // bf16 MFMA kernels, register-resident bucket state
+
+// Everything the launchers need, derived once from a validated descriptor.
+struct Plan {
+    int B, H, BH, d, L, P, R, LP, LR;
+    int64_t N;
+    float beta;
+    int causal;
+    int dtype;
+    int family;
+    // The sequence is cut into nseg segments of seg_len tokens (the last may be short).  One
+    // workgroup owns one segment; segment totals of the bucket statistics are turned into
+    // segment-start states by an exclusive scan (forward: prefix, backward: suffix).
+    int nseg;
+    int64_t seg_len;
+    // workspace layout, byte offsets (all multiples of 256)
+    size_t off_W;       // projection matrix in the layout of the kernel family
+    size_t bytes_W;
+    size_t off_stateA;  // per-segment bucket statistics, (BH, nseg, ...) fp32
+    size_t off_stateB;  // second set (backward only: cotangent statistics)
+    size_t bytes_state;
+    size_t off_part;    // per-table partial results (simple family only)
+    size_t bytes_part;
+    size_t total;
+};
+
+// Validates desc and fills plan.  Returns RACE_OK, RACE_ERR_INVALID_ARG or RACE_ERR_UNSUPPORTED.
+race_status_t make_plan(const race_attn_desc_t *desc, Plan *plan);
+
+// Host: pinned, immutable image of W for (seeds, L, P, d, dtype) in the layout of `family`.
+// Returns nullptr if pinned memory cannot be allocated.
+const void *projection_image(const Plan &plan, const uint64_t *seeds, size_t *bytes);
+// Host: plain (H, L*P, d) expansion into caller memory.
+void expand_projection_host(int H, int L, int P, int d, int dtype, const uint64_t *seeds, float *out);
+
+// ---- simple family (simple_kernels.hip)
+hipError_t simple_fwd(const Plan &p, const void *Q, const void *K, const void *V, void *O, float *den,
+                      char *ws, hipStream_t st);
+hipError_t simple_bwd(const Plan &p, const void *Q, const void *K, const void *V, const void *O,
+                      const float *den, const void *dO, void *dQ, void *dK, void *dV, char *ws, hipStream_t st);
+hipError_t simple_hash(const Plan &p, const void *X, uint8_t *codes, float *phi, char *ws, hipStream_t st);
+hipError_t simple_buckets(const Plan &p, const void *K, const void *V, float *A, float *Bsum, char *ws,
+                          hipStream_t st);
+
+// ---- MFMA family (mfma_kernels.hip)
+bool mfma_supported(int d, int L, int P);
+size_t mfma_projection_bytes(const Plan &p);
+void mfma_pack_projection(const Plan &p, const float *W, void *image);   // host
+hipError_t mfma_fwd(const Plan &p, const void *Q, const void *K, const void *V, void *O, float *den,
+                    char *ws, hipStream_t st);
+hipError_t mfma_bwd(const Plan &p, const void *Q, const void *K, const void *V, const void *O,
+                    const float *den, const void *dO, void *dQ, void *dK, void *dV, char *ws, hipStream_t st);
+hipError_t mfma_hash(const Plan &p, const void *X, uint8_t *codes, float *phi, char *ws, hipStream_t st);
+hipError_t mfma_buckets(const Plan &p, const void *K, const void *V, float *A, float *Bsum, char *ws,
+                        hipStream_t st);
+
+}  // namespace race

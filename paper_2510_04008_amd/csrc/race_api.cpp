@@ -1,0 +1,348 @@
+// Host side of the C ABI: argument validation, planning (segments, workspace layout), the
+// seed -> W generator with its host cache, and dispatch to the kernel families.
+#include <hip/hip_runtime_api.h>
+
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <map>
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "internal.h"
+
+namespace race {
+
+bool simple_supported(int R, int d, int P);
+
+namespace {
+
+thread_local std::string g_last_error;
+
+size_t align256(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
+
+// ---------------------------------------------------------------- Philox-4x32-10 + Box-Muller
+// Counter-based generator of Salmon et al. (SC'11): ten rounds of two 32x32->64 multiplications,
+// the key bumped by the Weyl constants between rounds.
+struct Philox4 { uint32_t v[4]; };
+
+Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1)
+{
+    for (int round = 0; round < 10; ++round) {
+        if (round) { k0 += 0x9E3779B9u; k1 += 0xBB67AE85u; }
+        const uint64_t a = 0xD2511F53ull * c0, b = 0xCD9E8D57ull * c2;
+        const uint32_t n0 = static_cast<uint32_t>(b >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = static_cast<uint32_t>(a >> 32) ^ c3 ^ k1;
+        c1 = static_cast<uint32_t>(b);
+        c3 = static_cast<uint32_t>(a);
+        c0 = n0;
+        c2 = n2;
+    }
+    return Philox4{{c0, c1, c2, c3}};
+}
+
+void gaussian_pair(uint32_t x0, uint32_t x1, double *g)
+{
+    const double u1 = (static_cast<double>(x0) + 0.5) * (1.0 / 4294967296.0);
+    const double u2 = (static_cast<double>(x1) + 0.5) * (1.0 / 4294967296.0);
+    const double rad = std::sqrt(-2.0 * std::log(u1));
+    const double ang = 2.0 * 3.14159265358979323846 * u2;
+    g[0] = rad * std::cos(ang);
+    g[1] = rad * std::sin(ang);
+}
+
+float round_to_bf16(float x)
+{
+    uint32_t b;
+    std::memcpy(&b, &x, 4);
+    b += 0x7fffu + ((b >> 16) & 1u);
+    b &= 0xffff0000u;
+    std::memcpy(&x, &b, 4);
+    return x;
+}
+
+// ---------------------------------------------------------------- host cache of projection images
+struct CacheKey {
+    int family, dtype, H, L, P, d;
+    std::vector<uint64_t> seeds;
+    bool operator<(const CacheKey &o) const
+    {
+        if (family != o.family) return family < o.family;
+        if (dtype != o.dtype) return dtype < o.dtype;
+        if (H != o.H) return H < o.H;
+        if (L != o.L) return L < o.L;
+        if (P != o.P) return P < o.P;
+        if (d != o.d) return d < o.d;
+        return seeds < o.seeds;
+    }
+};
+struct CacheEntry { void *pinned; size_t bytes; };
+std::mutex g_cache_mutex;
+std::map<CacheKey, CacheEntry> g_cache;
+constexpr size_t kMaxCacheEntries = 64;
+
+}  // namespace
+
+void expand_projection_host(int H, int L, int P, int d, int dtype, const uint64_t *seeds, float *out)
+{
+    const size_t n = static_cast<size_t>(L) * P * d;
+    for (int h = 0; h < H; ++h) {
+        const uint32_t k0 = static_cast<uint32_t>(seeds[h]), k1 = static_cast<uint32_t>(seeds[h] >> 32);
+        float *w = out + static_cast<size_t>(h) * n;
+        for (size_t blk = 0; blk * 4 < n; ++blk) {
+            const Philox4 x = philox4x32_10(static_cast<uint32_t>(blk), static_cast<uint32_t>(blk >> 32), 0, 0, k0, k1);
+            double g[4];
+            gaussian_pair(x.v[0], x.v[1], g);
+            gaussian_pair(x.v[2], x.v[3], g + 2);
+            for (size_t i = 0; i < 4 && blk * 4 + i < n; ++i) {
+                float f = static_cast<float>(g[i]);
+                w[blk * 4 + i] = (dtype == RACE_BF16) ? round_to_bf16(f) : f;
+            }
+        }
+    }
+}
+
+const void *projection_image(const Plan &p, const uint64_t *seeds, size_t *bytes)
+{
+    CacheKey key{p.family, p.dtype, p.H, p.L, p.P, p.d, std::vector<uint64_t>(seeds, seeds + p.H)};
+    std::lock_guard<std::mutex> lock(g_cache_mutex);
+    auto it = g_cache.find(key);
+    if (it == g_cache.end()) {
+        if (g_cache.size() >= kMaxCacheEntries) {
+            // images may still be the source of an asynchronous copy: drain the device first
+            (void)hipDeviceSynchronize();
+            for (auto &e : g_cache) (void)hipHostFree(e.second.pinned);
+            g_cache.clear();
+        }
+        std::vector<float> W(static_cast<size_t>(p.H) * p.LP * p.d);
+        expand_projection_host(p.H, p.L, p.P, p.d, p.dtype, seeds, W.data());
+        CacheEntry e;
+        e.bytes = p.bytes_W;
+        if (hipHostMalloc(&e.pinned, e.bytes, hipHostMallocDefault) != hipSuccess) return nullptr;
+        if (p.family == kFamilyMfma) mfma_pack_projection(p, W.data(), e.pinned);
+        else std::memcpy(e.pinned, W.data(), W.size() * sizeof(float));
+        it = g_cache.emplace(std::move(key), e).first;
+    }
+    *bytes = it->second.bytes;
+    return it->second.pinned;
+}
+
+race_status_t make_plan(const race_attn_desc_t *desc, Plan *pl)
+{
+    if (!desc) return RACE_ERR_INVALID_ARG;
+    if (desc->B < 1 || desc->H < 1 || desc->N < 0 || desc->d < 1 || desc->L < 1 || desc->P < 1)
+        return RACE_ERR_INVALID_ARG;
+    if (!(desc->sharpening > 0.0f) || !std::isfinite(desc->sharpening)) return RACE_ERR_INVALID_ARG;
+    if (desc->causal != 0 && desc->causal != 1) return RACE_ERR_INVALID_ARG;
+    if (desc->dtype != RACE_F32 && desc->dtype != RACE_BF16) return RACE_ERR_INVALID_ARG;
+    if (desc->chunk < 0) return RACE_ERR_INVALID_ARG;
+    if (desc->P > 8 || desc->d > 256 || desc->d % 8 != 0) return RACE_ERR_UNSUPPORTED;
+    if (desc->L > 4096 || static_cast<int64_t>(desc->B) * desc->H > 65535) return RACE_ERR_UNSUPPORTED;
+    if (static_cast<int64_t>(desc->B) * desc->H * desc->L > 65535) return RACE_ERR_UNSUPPORTED;
+    if (desc->N > (static_cast<int64_t>(1) << 40)) return RACE_ERR_UNSUPPORTED;
+
+    Plan p{};
+    p.B = desc->B; p.H = desc->H; p.BH = desc->B * desc->H; p.d = desc->d; p.L = desc->L; p.P = desc->P;
+    p.R = 1 << desc->P; p.LP = p.L * p.P; p.LR = p.L * p.R; p.N = desc->N; p.beta = desc->sharpening;
+    p.causal = desc->causal; p.dtype = desc->dtype;
+
+    const char *force = std::getenv("RACE_ATTN_FORCE_GENERIC");
+    const bool forced = force && force[0] == '1';
+    if (p.dtype == RACE_BF16 && !forced && mfma_supported(p.d, p.L, p.P)) p.family = kFamilyMfma;
+    else if (simple_supported(p.R, p.d, p.P)) p.family = kFamilySimple;
+    else return RACE_ERR_UNSUPPORTED;
+
+    const int64_t n = p.N > 0 ? p.N : 1;
+    if (p.family == kFamilySimple) {
+        // enough workgroups to fill 256 CUs a few times over, segments of at least 64 tokens
+        int64_t want = (2048 + static_cast<int64_t>(p.BH) * p.L - 1) / (static_cast<int64_t>(p.BH) * p.L);
+        int64_t len = desc->chunk > 0 ? desc->chunk : (n + want - 1) / want;
+        if (desc->chunk == 0 && len < 64) len = 64;
+        len = (len + 7) / 8 * 8;
+        p.seg_len = len;
+        p.nseg = static_cast<int>((n + len - 1) / len);
+        if ((n + len - 1) / len > 65535) return RACE_ERR_UNSUPPORTED;
+        p.bytes_W = align256(static_cast<size_t>(p.H) * p.LP * p.d * sizeof(float));
+        p.bytes_state = align256(static_cast<size_t>(p.BH) * p.L * p.nseg * p.R * (p.d + 1) * sizeof(float));
+        const size_t fwd_part = static_cast<size_t>(p.BH) * p.L * n * (p.d + 1) * sizeof(float);
+        const size_t bwd_part = static_cast<size_t>(p.BH) * p.L * n * p.d * sizeof(float) * 3;
+        p.bytes_part = align256(fwd_part > bwd_part ? fwd_part : bwd_part);
+    } else {
+        // two workgroups' worth of segments per CU and head-batch; multiples of the 32-token tile
+        int64_t want = (512 + p.BH - 1) / p.BH;
+        int64_t len = desc->chunk > 0 ? desc->chunk : (n + want - 1) / want;
+        if (desc->chunk == 0 && len < 256) len = 256;
+        len = (len + 31) / 32 * 32;
+        p.seg_len = len;
+        if ((n + len - 1) / len > 65535) return RACE_ERR_UNSUPPORTED;
+        p.nseg = static_cast<int>((n + len - 1) / len);
+        p.bytes_W = align256(mfma_projection_bytes(p));
+        p.bytes_state = align256(static_cast<size_t>(p.BH) * p.nseg * p.LR * (p.d + 1) * sizeof(float));
+        p.bytes_part = 0;
+    }
+    p.off_W = 0;
+    p.off_stateA = p.off_W + p.bytes_W;
+    p.off_stateB = p.off_stateA + p.bytes_state;
+    p.off_part = p.off_stateB + p.bytes_state;
+    p.total = p.off_part + p.bytes_part;
+    *pl = p;
+    return RACE_OK;
+}
+
+namespace {
+
+race_status_t hip_failed(hipError_t e, const char *where)
+{
+    g_last_error = std::string(where) + ": " + hipGetErrorString(e);
+    return RACE_ERR_HIP;
+}
+
+race_status_t check_workspace(const Plan &p, const void *ws, size_t bytes, size_t need)
+{
+    (void)p;
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255) != 0 || bytes < need) return RACE_ERR_WORKSPACE;
+    return RACE_OK;
+}
+
+bool any_equal(std::initializer_list<const void *> outs, std::initializer_list<const void *> all)
+{
+    for (const void *o : outs) {
+        int hits = 0;
+        for (const void *a : all) hits += (a == o);
+        if (hits > 1) return true;
+    }
+    return false;
+}
+
+race_status_t upload_projection(const Plan &p, const uint64_t *seeds, char *ws, hipStream_t st)
+{
+    size_t bytes = 0;
+    const void *img = projection_image(p, seeds, &bytes);
+    if (!img) return hip_failed(hipErrorOutOfMemory, "hipHostMalloc(projection image)");
+    hipError_t e = hipMemcpyAsync(ws + p.off_W, img, bytes, hipMemcpyHostToDevice, st);
+    if (e != hipSuccess) return hip_failed(e, "hipMemcpyAsync(projection image)");
+    return RACE_OK;
+}
+
+}  // namespace
+}  // namespace race
+
+using namespace race;
+
+extern "C" {
+
+size_t race_attn_workspace_bytes(const race_attn_desc_t *desc)
+{
+    Plan p;
+    if (make_plan(desc, &p) != RACE_OK || p.N == 0) return 0;
+    return p.total;
+}
+
+int race_attn_kernel_family(const race_attn_desc_t *desc)
+{
+    Plan p;
+    if (make_plan(desc, &p) != RACE_OK) return kFamilyNone;
+    return p.family;
+}
+
+race_status_t race_attn_fwd(const race_attn_desc_t *desc, const void *Q, const void *K, const void *V,
+                            const uint64_t *proj_seeds, void *O, float *den, void *workspace,
+                            size_t workspace_bytes, race_stream_t stream)
+{
+    Plan p;
+    race_status_t s = make_plan(desc, &p);
+    if (s != RACE_OK) return s;
+    if (!Q || !K || !V || !proj_seeds || !O || !den) return RACE_ERR_INVALID_ARG;
+    if (any_equal({O, den}, {Q, K, V, O, den})) return RACE_ERR_INVALID_ARG;
+    if (p.N == 0) return RACE_OK;
+    if ((s = check_workspace(p, workspace, workspace_bytes, p.total)) != RACE_OK) return s;
+    char *ws = static_cast<char *>(workspace);
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if ((s = upload_projection(p, proj_seeds, ws, st)) != RACE_OK) return s;
+    hipError_t e = (p.family == kFamilyMfma) ? mfma_fwd(p, Q, K, V, O, den, ws, st)
+                                             : simple_fwd(p, Q, K, V, O, den, ws, st);
+    return e == hipSuccess ? RACE_OK : hip_failed(e, "race_attn_fwd launch");
+}
+
+race_status_t race_attn_bwd(const race_attn_desc_t *desc, const void *Q, const void *K, const void *V,
+                            const void *O, const float *den, const void *dO, const uint64_t *proj_seeds,
+                            void *dQ, void *dK, void *dV, void *workspace, size_t workspace_bytes,
+                            race_stream_t stream)
+{
+    Plan p;
+    race_status_t s = make_plan(desc, &p);
+    if (s != RACE_OK) return s;
+    if (!Q || !K || !V || !O || !den || !dO || !proj_seeds || !dQ || !dK || !dV) return RACE_ERR_INVALID_ARG;
+    if (any_equal({dQ, dK, dV}, {Q, K, V, O, den, dO, dQ, dK, dV})) return RACE_ERR_INVALID_ARG;
+    if (p.N == 0) return RACE_OK;
+    if ((s = check_workspace(p, workspace, workspace_bytes, p.total)) != RACE_OK) return s;
+    char *ws = static_cast<char *>(workspace);
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if ((s = upload_projection(p, proj_seeds, ws, st)) != RACE_OK) return s;
+    hipError_t e = (p.family == kFamilyMfma) ? mfma_bwd(p, Q, K, V, O, den, dO, dQ, dK, dV, ws, st)
+                                             : simple_bwd(p, Q, K, V, O, den, dO, dQ, dK, dV, ws, st);
+    return e == hipSuccess ? RACE_OK : hip_failed(e, "race_attn_bwd launch");
+}
+
+race_status_t race_attn_expand_projection(const race_attn_desc_t *desc, const uint64_t *proj_seeds, float *W_host)
+{
+    if (!desc || !proj_seeds || !W_host) return RACE_ERR_INVALID_ARG;
+    if (desc->H < 1 || desc->L < 1 || desc->P < 1 || desc->d < 1) return RACE_ERR_INVALID_ARG;
+    if (desc->dtype != RACE_F32 && desc->dtype != RACE_BF16) return RACE_ERR_INVALID_ARG;
+    if (desc->P > 8 || desc->d > 256 || desc->L > 4096) return RACE_ERR_UNSUPPORTED;
+    expand_projection_host(desc->H, desc->L, desc->P, desc->d, desc->dtype, proj_seeds, W_host);
+    return RACE_OK;
+}
+
+race_status_t race_attn_debug_hash(const race_attn_desc_t *desc, const void *X, const uint64_t *proj_seeds,
+                                   uint8_t *codes, float *phi, void *workspace, size_t workspace_bytes,
+                                   race_stream_t stream)
+{
+    Plan p;
+    race_status_t s = make_plan(desc, &p);
+    if (s != RACE_OK) return s;
+    if (!X || !proj_seeds || !codes) return RACE_ERR_INVALID_ARG;
+    if (p.N == 0) return RACE_OK;
+    if ((s = check_workspace(p, workspace, workspace_bytes, p.off_W + p.bytes_W)) != RACE_OK) return s;
+    char *ws = static_cast<char *>(workspace);
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if ((s = upload_projection(p, proj_seeds, ws, st)) != RACE_OK) return s;
+    hipError_t e = (p.family == kFamilyMfma) ? mfma_hash(p, X, codes, phi, ws, st)
+                                             : simple_hash(p, X, codes, phi, ws, st);
+    return e == hipSuccess ? RACE_OK : hip_failed(e, "race_attn_debug_hash launch");
+}
+
+race_status_t race_attn_debug_buckets(const race_attn_desc_t *desc, const void *K, const void *V,
+                                      const uint64_t *proj_seeds, float *A, float *Bsum, void *workspace,
+                                      size_t workspace_bytes, race_stream_t stream)
+{
+    Plan p;
+    race_status_t s = make_plan(desc, &p);
+    if (s != RACE_OK) return s;
+    if (!K || !V || !proj_seeds || !A || !Bsum) return RACE_ERR_INVALID_ARG;
+    if (p.N == 0) return RACE_OK;
+    if ((s = check_workspace(p, workspace, workspace_bytes, p.total)) != RACE_OK) return s;
+    char *ws = static_cast<char *>(workspace);
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if ((s = upload_projection(p, proj_seeds, ws, st)) != RACE_OK) return s;
+    hipError_t e = (p.family == kFamilyMfma) ? mfma_buckets(p, K, V, A, Bsum, ws, st)
+                                             : simple_buckets(p, K, V, A, Bsum, ws, st);
+    return e == hipSuccess ? RACE_OK : hip_failed(e, "race_attn_debug_buckets launch");
+}
+
+const char *race_status_string(race_status_t status)
+{
+    switch (status) {
+    case RACE_OK: return "ok";
+    case RACE_ERR_INVALID_ARG: return "invalid argument";
+    case RACE_ERR_UNSUPPORTED: return "unsupported shape";
+    case RACE_ERR_WORKSPACE: return "workspace null, misaligned or too small";
+    case RACE_ERR_HIP: return "HIP call failed";
+    }
+    return "unknown status";
+}
+
+const char *race_attn_last_error(void) { return g_last_error.c_str(); }
+
+}  // extern "C"

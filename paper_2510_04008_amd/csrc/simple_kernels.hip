@@ -1,0 +1,622 @@
+// Generic RACE Attention kernels: any (L, P <= 8, d <= 256), fp32 or bf16 tensors, all arithmetic
+// in fp32 on the vector ALUs.  One workgroup owns one (batch*head, table, segment): the table's
+// bucket statistics [R][d+1] (B | A of Algorithm 1, step 5) live in LDS and tokens are taken in
+// the order of Algorithm 2 (update with key/value t, then query t reads).  Per-table partial
+// numerators are written to the workspace and summed over tables in table order by a combine
+// kernel, so results are deterministic.  This family serves the fp32 element type and every bf16
+// shape the MFMA family has no instantiation for; it is written for clarity, not speed.
+#include <hip/hip_runtime.h>
+
+#include "internal.h"
+
+namespace race {
+namespace {
+
+constexpr int kThreads = 256;
+
+// ------------------------------------------------------------------ element access
+struct bf16_t { uint16_t bits; };
+
+__device__ __forceinline__ float load_elem(const float *p, size_t i) { return p[i]; }
+__device__ __forceinline__ float load_elem(const bf16_t *p, size_t i)
+{
+    return __uint_as_float(static_cast<uint32_t>(p[i].bits) << 16);
+}
+__device__ __forceinline__ void store_elem(float *p, size_t i, float v) { p[i] = v; }
+__device__ __forceinline__ void store_elem(bf16_t *p, size_t i, float v)
+{
+    uint32_t b = __float_as_uint(v);
+    if ((b & 0x7fffffffu) > 0x7f800000u) { p[i].bits = 0x7fc0; return; }      // NaN
+    b += 0x7fffu + ((b >> 16) & 1u);                                          // nearest even
+    p[i].bits = static_cast<uint16_t>(b >> 16);
+}
+
+struct Args {
+    int H, L, P, R, d, LP, nseg, causal, TT;
+    int64_t N, seg_len;
+    float beta;
+    const float *W;      // (H, L*P, d)
+};
+
+// ------------------------------------------------------------------ LDS carving
+// S     [R][d+1]   bucket statistics of this table (value sums | mass)
+// xa,xb [TT][d]    rows of the two hashed tensors
+// ya,yb [TT][d+1]  rows of the two accumulated tensors ([V | 1] and [dO/e | -(dO.O)/e])
+// ha,hb            per-token hash data of the two hashed tensors: s, p, q, u [TT][P] each, phi [TT][R]
+// dphi  [R], dz [P]
+struct Smem {
+    float *S, *xa, *xb, *ya, *yb, *ha, *hb, *dphi, *dz;
+    __device__ Smem(float *base, const Args &a)
+    {
+        const int d1 = a.d + 1;
+        S = base;                 base += a.R * d1;
+        xa = base;                base += a.TT * a.d;
+        xb = base;                base += a.TT * a.d;
+        ya = base;                base += a.TT * d1;
+        yb = base;                base += a.TT * d1;
+        ha = base;                base += a.TT * (4 * a.P + a.R);
+        hb = base;                base += a.TT * (4 * a.P + a.R);
+        dphi = base;              base += a.R;
+        dz = base;
+    }
+};
+inline size_t smem_floats(int R, int d, int P, int TT)
+{
+    return static_cast<size_t>(R) * (d + 1) + 2 * TT * d + 2 * TT * (d + 1) + 2 * TT * (4 * P + R) + R + P;
+}
+
+struct HashView {
+    float *s, *p, *q, *u, *phi;     // s = 1 - tanh^2(z), p/q = mass on the +1/-1 side of each bit
+    __device__ HashView(float *h, const Args &a)
+        : s(h), p(h + a.TT * a.P), q(h + 2 * a.TT * a.P), u(h + 3 * a.TT * a.P), phi(h + 4 * a.TT * a.P) {}
+};
+
+// rows [t0, t0+nt) of X -> xs[TT][d]
+template <typename T>
+__device__ void load_rows(const T *X, size_t row0, int nt, int d, float *xs)
+{
+    for (int i = threadIdx.x; i < nt * d; i += kThreads) xs[i] = load_elem(X, row0 * d + i);
+}
+
+// [V | 1] rows
+template <typename T>
+__device__ void load_value_rows(const T *V, size_t row0, int nt, int d, float *ys)
+{
+    for (int i = threadIdx.x; i < nt * (d + 1); i += kThreads) {
+        const int t = i / (d + 1), c = i - t * (d + 1);
+        ys[i] = (c < d) ? load_elem(V, (row0 + t) * d + c) : 1.0f;
+    }
+}
+
+// [dO / e | -(dO . O) / e] rows with e = L * Den: the cotangents of the un-averaged numerator and
+// normaliser of Algorithm 1, step 7.  scratch: [TT][d] floats.
+template <typename T>
+__device__ void load_cotangent_rows(const T *dO, const T *O, const float *den, size_t row0, int nt, int d,
+                                    int L, float *ys, float *scratch)
+{
+    for (int i = threadIdx.x; i < nt * d; i += kThreads) {
+        const int t = i / d, c = i - t * d;
+        const float g = load_elem(dO, (row0 + t) * d + c);
+        ys[t * (d + 1) + c] = g;
+        scratch[i] = g * load_elem(O, (row0 + t) * d + c);
+    }
+    __syncthreads();
+    // 32 threads per token
+    const int t = threadIdx.x >> 5, sub = threadIdx.x & 31;
+    for (int tok = t; tok < nt; tok += kThreads / 32) {
+        float acc = 0.f;
+        for (int c = sub; c < d; c += 32) acc += scratch[tok * d + c];
+        for (int m = 16; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);
+        const float inv = 1.0f / (den[row0 + tok] * static_cast<float>(L));
+        for (int c = sub; c < d; c += 32) ys[tok * (d + 1) + c] *= inv;
+        if (sub == 0) ys[tok * (d + 1) + d] = -acc * inv;
+    }
+    __syncthreads();
+}
+
+// Projection + soft assignment of nt rows (Algorithm 1, steps 2-4).  phi is built from its
+// factorised form phi_r = prod_t sigmoid(2 beta v_{r,t} u_t), u = tanh(W x), which equals the
+// softmax over corners exactly (the softmax denominator is prod_t 2 cosh(beta u_t)).
+__device__ void hash_rows(const Args &a, const float *Wl, const float *xs, int nt, HashView hv)
+{
+    __syncthreads();
+    const int sub = threadIdx.x & 3;
+    for (int pair = threadIdx.x >> 2; pair < nt * a.P; pair += kThreads / 4) {
+        const int tok = pair / a.P, t = pair - tok * a.P;
+        float z = 0.f;
+        for (int c = sub; c < a.d; c += 4) z = fmaf(Wl[t * a.d + c], xs[tok * a.d + c], z);
+        z += __shfl_xor(z, 1, 64);
+        z += __shfl_xor(z, 2, 64);
+        if (sub == 0) {
+            const float u = tanhf(z);
+            const float e = expf(-2.0f * a.beta * fabsf(u));      // in (0, 1]
+            const float big = 1.0f / (1.0f + e), small = e / (1.0f + e);
+            const float e2 = expf(-2.0f * fabsf(z));               // 1 - tanh^2 z = 4 e2 / (1 + e2)^2
+            hv.u[pair] = u;
+            hv.s[pair] = 4.0f * e2 / ((1.0f + e2) * (1.0f + e2));
+            hv.p[pair] = (u >= 0.f) ? big : small;                 // mass on the +1 side of bit t
+            hv.q[pair] = (u >= 0.f) ? small : big;
+        }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < nt * a.R; i += kThreads) {
+        const int tok = i / a.R, r = i - tok * a.R;
+        float f = 1.f;
+        for (int t = 0; t < a.P; ++t) f *= ((r >> t) & 1) ? hv.p[tok * a.P + t] : hv.q[tok * a.P + t];
+        hv.phi[i] = f;
+    }
+    __syncthreads();
+}
+
+// S[:, c] += phi[r] * y[c] for the columns this thread owns (thread-private columns: no barrier).
+__device__ __forceinline__ void accumulate_token(const Args &a, float *S, const float *phi, const float *y)
+{
+    const int d1 = a.d + 1;
+    for (int c = threadIdx.x; c < d1; c += kThreads) {
+        const float yc = y[c];
+        for (int r = 0; r < a.R; ++r) S[r * d1 + c] = fmaf(phi[r], yc, S[r * d1 + c]);
+    }
+}
+
+// Cotangent of phi -> cotangent of z (softmax over corners, corner logits, tanh).  dphi in LDS.
+// Leaves dz[P] in LDS (followed by a barrier).
+__device__ void soft_hash_vjp(const Args &a, const float *phi, const float *sech2, const float *dphi, float *dz)
+{
+    if (threadIdx.x < a.P) {
+        const int t = threadIdx.x;
+        float mean = 0.f;
+        for (int r = 0; r < a.R; ++r) mean = fmaf(phi[r], dphi[r], mean);
+        float du = 0.f;
+        for (int r = 0; r < a.R; ++r) {
+            const float ds = phi[r] * (dphi[r] - mean);
+            du += ((r >> t) & 1) ? ds : -ds;
+        }
+        dz[t] = a.beta * du * sech2[t];
+    }
+    __syncthreads();
+}
+
+__device__ __forceinline__ size_t state_index(const Args &a, int bh, int l, int seg)
+{
+    return ((static_cast<size_t>(bh) * a.L + l) * a.nseg + seg) * a.R * (a.d + 1);
+}
+
+// ------------------------------------------------------------------ kernels
+// Segment totals of the bucket statistics.  SIDE 0: keys/values (A | B of Algorithm 1, step 5).
+// SIDE 1: queries / read-out cotangents (the statistics the key side reads in the backward pass).
+template <typename T, int SIDE>
+__global__ __launch_bounds__(kThreads) void simple_totals(Args a, const T *X, const T *Y, const T *O,
+                                                          const float *den, float *state)
+{
+    extern __shared__ float lds[];
+    Smem sm(lds, a);
+    const int seg = blockIdx.x, l = blockIdx.y, bh = blockIdx.z, h = bh % a.H;
+    const float *Wl = a.W + (static_cast<size_t>(h) * a.LP + l * a.P) * a.d;
+    const int d1 = a.d + 1;
+    for (int i = threadIdx.x; i < a.R * d1; i += kThreads) sm.S[i] = 0.f;
+    const int64_t t_begin = seg * a.seg_len;
+    const int64_t t_end = (t_begin + a.seg_len < a.N) ? t_begin + a.seg_len : a.N;
+    HashView hv(sm.ha, a);
+    for (int64_t t0 = t_begin; t0 < t_end; t0 += a.TT) {
+        const int nt = (t_end - t0 < a.TT) ? static_cast<int>(t_end - t0) : a.TT;
+        const size_t row0 = static_cast<size_t>(bh) * a.N + t0;
+        __syncthreads();
+        load_rows(X, row0, nt, a.d, sm.xa);
+        if (SIDE == 0) load_value_rows(Y, row0, nt, a.d, sm.ya);
+        else load_cotangent_rows(Y, O, den, row0, nt, a.d, a.L, sm.ya, sm.xb);
+        hash_rows(a, Wl, sm.xa, nt, hv);
+        for (int tok = 0; tok < nt; ++tok) accumulate_token(a, sm.S, hv.phi + tok * a.R, sm.ya + tok * d1);
+    }
+    __syncthreads();
+    float *out = state + state_index(a, bh, l, seg);
+    for (int i = threadIdx.x; i < a.R * d1; i += kThreads) out[i] = sm.S[i];
+}
+
+// In-place scan over segments of the per-segment totals.  mode 0: exclusive prefix (state at the
+// start of the segment, forward direction); 1: exclusive suffix; 2: every segment gets the grand total.
+__global__ void simple_scan(float *state, int nseg, size_t elems, int mode)
+{
+    const size_t e = blockIdx.x * static_cast<size_t>(blockDim.x) + threadIdx.x;
+    if (e >= elems) return;
+    float *base = state + static_cast<size_t>(blockIdx.y) * nseg * elems + e;
+    if (mode == 0) {
+        float run = 0.f;
+        for (int s = 0; s < nseg; ++s) { const float v = base[s * elems]; base[s * elems] = run; run += v; }
+    } else if (mode == 1) {
+        float run = 0.f;
+        for (int s = nseg - 1; s >= 0; --s) { const float v = base[s * elems]; base[s * elems] = run; run += v; }
+    } else {
+        float run = 0.f;
+        for (int s = 0; s < nseg; ++s) run += base[s * elems];
+        for (int s = 0; s < nseg; ++s) base[s * elems] = run;
+    }
+}
+
+// Forward replay of one segment of one table: Algorithm 2's loop body (or Algorithm 1's read-out
+// against the all-N statistics).  Writes the table's un-averaged [num | den] rows.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void simple_fwd_replay(Args a, const T *Q, const T *K, const T *V,
+                                                              const float *state, float *part)
+{
+    extern __shared__ float lds[];
+    Smem sm(lds, a);
+    const int seg = blockIdx.x, l = blockIdx.y, bh = blockIdx.z, h = bh % a.H;
+    const float *Wl = a.W + (static_cast<size_t>(h) * a.LP + l * a.P) * a.d;
+    const int d1 = a.d + 1;
+    const float *init = state + state_index(a, bh, l, seg);
+    for (int i = threadIdx.x; i < a.R * d1; i += kThreads) sm.S[i] = init[i];
+    const int64_t t_begin = seg * a.seg_len;
+    const int64_t t_end = (t_begin + a.seg_len < a.N) ? t_begin + a.seg_len : a.N;
+    HashView hk(sm.ha, a), hq(sm.hb, a);
+    float *out = part + (static_cast<size_t>(bh) * a.L + l) * a.N * d1;
+    for (int64_t t0 = t_begin; t0 < t_end; t0 += a.TT) {
+        const int nt = (t_end - t0 < a.TT) ? static_cast<int>(t_end - t0) : a.TT;
+        const size_t row0 = static_cast<size_t>(bh) * a.N + t0;
+        __syncthreads();
+        load_rows(Q, row0, nt, a.d, sm.xb);
+        if (a.causal) {
+            load_rows(K, row0, nt, a.d, sm.xa);
+            load_value_rows(V, row0, nt, a.d, sm.ya);
+            hash_rows(a, Wl, sm.xa, nt, hk);
+        }
+        hash_rows(a, Wl, sm.xb, nt, hq);
+        for (int tok = 0; tok < nt; ++tok) {
+            if (a.causal) accumulate_token(a, sm.S, hk.phi + tok * a.R, sm.ya + tok * d1);
+            const float *phi = hq.phi + tok * a.R;
+            for (int c = threadIdx.x; c < d1; c += kThreads) {
+                float acc = 0.f;
+                for (int r = 0; r < a.R; ++r) acc = fmaf(phi[r], sm.S[r * d1 + c], acc);
+                out[(t0 + tok) * d1 + c] = acc;
+            }
+        }
+    }
+}
+
+// Num = (1/L) sum_l num_l, Den = (1/L) sum_l den_l, O = Num / Den  (Algorithm 1, steps 7-8)
+template <typename T>
+__global__ void simple_fwd_combine(Args a, int BH, const float *part, T *O, float *den)
+{
+    const size_t i = blockIdx.x * static_cast<size_t>(blockDim.x) + threadIdx.x;
+    const size_t total = static_cast<size_t>(BH) * a.N * a.d;
+    if (i >= total) return;
+    const int d1 = a.d + 1;
+    const size_t row = i / a.d;
+    const int c = static_cast<int>(i - row * a.d);
+    const size_t bh = row / a.N, t = row - bh * a.N;
+    float num = 0.f, dn = 0.f;
+    for (int l = 0; l < a.L; ++l) {
+        const float *p = part + ((bh * a.L + l) * a.N + t) * d1;
+        num += p[c];
+        dn += p[a.d];
+    }
+    const float invL = 1.0f / static_cast<float>(a.L);
+    store_elem(O, i, (num * invL) / (dn * invL));
+    if (c == 0) den[row] = dn * invL;
+}
+
+// Backward, query side, one segment of one table, left to right: with the prefix statistics S
+// (after adding key/value i), dphi_Q[r] = S[r,:] . [dO_i/e_i | -(dO_i.O_i)/e_i]; then back through
+// the soft assignment to the table's share of dQ_i.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void simple_bwd_query(Args a, const T *Q, const T *K, const T *V,
+                                                             const T *O, const float *den, const T *dO,
+                                                             const float *state, float *partQ)
+{
+    extern __shared__ float lds[];
+    Smem sm(lds, a);
+    const int seg = blockIdx.x, l = blockIdx.y, bh = blockIdx.z, h = bh % a.H;
+    const float *Wl = a.W + (static_cast<size_t>(h) * a.LP + l * a.P) * a.d;
+    const int d1 = a.d + 1;
+    const float *init = state + state_index(a, bh, l, seg);
+    for (int i = threadIdx.x; i < a.R * d1; i += kThreads) sm.S[i] = init[i];
+    const int64_t t_begin = seg * a.seg_len;
+    const int64_t t_end = (t_begin + a.seg_len < a.N) ? t_begin + a.seg_len : a.N;
+    HashView hk(sm.ha, a), hq(sm.hb, a);
+    float *out = partQ + (static_cast<size_t>(bh) * a.L + l) * a.N * a.d;
+    for (int64_t t0 = t_begin; t0 < t_end; t0 += a.TT) {
+        const int nt = (t_end - t0 < a.TT) ? static_cast<int>(t_end - t0) : a.TT;
+        const size_t row0 = static_cast<size_t>(bh) * a.N + t0;
+        __syncthreads();
+        if (a.causal) {
+            load_rows(K, row0, nt, a.d, sm.xa);
+            load_value_rows(V, row0, nt, a.d, sm.ya);
+            hash_rows(a, Wl, sm.xa, nt, hk);
+        }
+        load_cotangent_rows(dO, O, den, row0, nt, a.d, a.L, sm.yb, sm.xb);
+        load_rows(Q, row0, nt, a.d, sm.xb);
+        hash_rows(a, Wl, sm.xb, nt, hq);
+        for (int tok = 0; tok < nt; ++tok) {
+            if (a.causal) {
+                accumulate_token(a, sm.S, hk.phi + tok * a.R, sm.ya + tok * d1);
+                __syncthreads();
+            }
+            const float *gt = sm.yb + tok * d1;
+            for (int r = threadIdx.x; r < a.R; r += kThreads) {
+                float acc = 0.f;
+                for (int c = 0; c < d1; ++c) acc = fmaf(sm.S[r * d1 + c], gt[c], acc);
+                sm.dphi[r] = acc;
+            }
+            __syncthreads();
+            soft_hash_vjp(a, hq.phi + tok * a.R, hq.s + tok * a.P, sm.dphi, sm.dz);
+            for (int c = threadIdx.x; c < a.d; c += kThreads) {
+                float acc = 0.f;
+                for (int t = 0; t < a.P; ++t) acc = fmaf(sm.dz[t], Wl[t * a.d + c], acc);
+                out[(t0 + tok) * a.d + c] = acc;
+            }
+            __syncthreads();
+        }
+    }
+}
+
+// Backward, key/value side, one segment of one table, right to left: with the suffix statistics
+// dS of the read-out cotangents (after adding query j), dV_j = phi_K(j) . dB,
+// dphi_K[r] = dB[r,:] . V_j + dA[r]; then back through the soft assignment to the share of dK_j.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void simple_bwd_keyvalue(Args a, const T *Q, const T *K, const T *V,
+                                                                const T *O, const float *den, const T *dO,
+                                                                const float *state, float *partK, float *partV)
+{
+    extern __shared__ float lds[];
+    Smem sm(lds, a);
+    const int seg = blockIdx.x, l = blockIdx.y, bh = blockIdx.z, h = bh % a.H;
+    const float *Wl = a.W + (static_cast<size_t>(h) * a.LP + l * a.P) * a.d;
+    const int d1 = a.d + 1;
+    const float *init = state + state_index(a, bh, l, seg);
+    for (int i = threadIdx.x; i < a.R * d1; i += kThreads) sm.S[i] = init[i];
+    const int64_t t_begin = seg * a.seg_len;
+    const int64_t t_end = (t_begin + a.seg_len < a.N) ? t_begin + a.seg_len : a.N;
+    HashView hk(sm.ha, a), hq(sm.hb, a);
+    float *outK = partK + (static_cast<size_t>(bh) * a.L + l) * a.N * a.d;
+    float *outV = partV + (static_cast<size_t>(bh) * a.L + l) * a.N * a.d;
+    const int64_t ntiles = (t_end - t_begin + a.TT - 1) / a.TT;
+    for (int64_t tile = ntiles - 1; tile >= 0; --tile) {
+        const int64_t t0 = t_begin + tile * a.TT;
+        const int nt = (t_end - t0 < a.TT) ? static_cast<int>(t_end - t0) : a.TT;
+        const size_t row0 = static_cast<size_t>(bh) * a.N + t0;
+        __syncthreads();
+        load_rows(K, row0, nt, a.d, sm.xa);
+        load_value_rows(V, row0, nt, a.d, sm.ya);
+        hash_rows(a, Wl, sm.xa, nt, hk);
+        if (a.causal) {
+            load_cotangent_rows(dO, O, den, row0, nt, a.d, a.L, sm.yb, sm.xb);
+            load_rows(Q, row0, nt, a.d, sm.xb);
+            hash_rows(a, Wl, sm.xb, nt, hq);
+        }
+        for (int tok = nt - 1; tok >= 0; --tok) {
+            if (a.causal) accumulate_token(a, sm.S, hq.phi + tok * a.R, sm.yb + tok * d1);
+            const float *phi = hk.phi + tok * a.R;
+            for (int c = threadIdx.x; c < a.d; c += kThreads) {       // same columns as accumulate_token
+                float acc = 0.f;
+                for (int r = 0; r < a.R; ++r) acc = fmaf(phi[r], sm.S[r * d1 + c], acc);
+                outV[(t0 + tok) * a.d + c] = acc;
+            }
+            __syncthreads();
+            const float *vt = sm.ya + tok * d1;
+            for (int r = threadIdx.x; r < a.R; r += kThreads) {
+                float acc = 0.f;
+                for (int c = 0; c < d1; ++c) acc = fmaf(sm.S[r * d1 + c], vt[c], acc);
+                sm.dphi[r] = acc;
+            }
+            __syncthreads();
+            soft_hash_vjp(a, phi, hk.s + tok * a.P, sm.dphi, sm.dz);
+            for (int c = threadIdx.x; c < a.d; c += kThreads) {
+                float acc = 0.f;
+                for (int t = 0; t < a.P; ++t) acc = fmaf(sm.dz[t], Wl[t * a.d + c], acc);
+                outK[(t0 + tok) * a.d + c] = acc;
+            }
+            __syncthreads();
+        }
+    }
+}
+
+template <typename T>
+__global__ void simple_bwd_combine(Args a, int BH, const float *pQ, const float *pK, const float *pV,
+                                   T *dQ, T *dK, T *dV)
+{
+    const size_t i = blockIdx.x * static_cast<size_t>(blockDim.x) + threadIdx.x;
+    const size_t total = static_cast<size_t>(BH) * a.N * a.d;
+    if (i >= total) return;
+    const size_t row = i / a.d;
+    const int c = static_cast<int>(i - row * a.d);
+    const size_t bh = row / a.N, t = row - bh * a.N;
+    float q = 0.f, k = 0.f, v = 0.f;
+    for (int l = 0; l < a.L; ++l) {
+        const size_t j = ((bh * a.L + l) * a.N + t) * a.d + c;
+        q += pQ[j]; k += pK[j]; v += pV[j];
+    }
+    store_elem(dQ, i, q);
+    store_elem(dK, i, k);
+    store_elem(dV, i, v);
+}
+
+// Debug tap: hard codes and phi of every (row, table).
+template <typename T>
+__global__ void simple_hash_tap(Args a, int BH, const T *X, uint8_t *codes, float *phi)
+{
+    const size_t i = blockIdx.x * static_cast<size_t>(blockDim.x) + threadIdx.x;
+    const size_t total = static_cast<size_t>(BH) * a.N * a.L;
+    if (i >= total) return;
+    const size_t row = i / a.L;
+    const int l = static_cast<int>(i - row * a.L);
+    const int h = static_cast<int>((row / a.N) % a.H);
+    const float *Wl = a.W + (static_cast<size_t>(h) * a.LP + l * a.P) * a.d;
+    float p[8], q[8];
+    unsigned code = 0;
+    for (int t = 0; t < a.P; ++t) {
+        float z = 0.f;
+        for (int c = 0; c < a.d; ++c) z = fmaf(Wl[t * a.d + c], load_elem(X, row * a.d + c), z);
+        code |= (z >= 0.f ? 1u : 0u) << t;
+        const float u = tanhf(z);
+        const float e = expf(-2.0f * a.beta * fabsf(u));
+        const float big = 1.0f / (1.0f + e), small = e / (1.0f + e);
+        p[t] = (u >= 0.f) ? big : small;
+        q[t] = (u >= 0.f) ? small : big;
+    }
+    codes[i] = static_cast<uint8_t>(code);
+    if (phi) {
+        for (int r = 0; r < a.R; ++r) {
+            float f = 1.f;
+            for (int t = 0; t < a.P; ++t) f *= ((r >> t) & 1) ? p[t] : q[t];
+            phi[i * a.R + r] = f;
+        }
+    }
+}
+
+// Debug tap: sum the per-segment totals and split them into A and B.
+__global__ void simple_bucket_tap(Args a, int BH, const float *state, float *A, float *Bsum)
+{
+    const size_t i = blockIdx.x * static_cast<size_t>(blockDim.x) + threadIdx.x;
+    const int d1 = a.d + 1;
+    const size_t total = static_cast<size_t>(BH) * a.L * a.R * d1;
+    if (i >= total) return;
+    const size_t bl = i / (static_cast<size_t>(a.R) * d1);
+    const size_t e = i - bl * a.R * d1;
+    float run = 0.f;
+    for (int s = 0; s < a.nseg; ++s) run += state[(bl * a.nseg + s) * a.R * d1 + e];
+    const int r = static_cast<int>(e / d1), c = static_cast<int>(e - static_cast<size_t>(r) * d1);
+    if (c == a.d) A[bl * a.R + r] = run;
+    else Bsum[(bl * a.R + r) * a.d + c] = run;
+}
+
+// ------------------------------------------------------------------ host side
+int pick_tile(int R, int d, int P)
+{
+    for (int tt = 8; tt >= 1; tt >>= 1)
+        if (smem_floats(R, d, P, tt) * sizeof(float) <= 160 * 1024) return tt;
+    return 0;
+}
+
+Args make_args(const Plan &p, const char *ws)
+{
+    Args a;
+    a.H = p.H; a.L = p.L; a.P = p.P; a.R = p.R; a.d = p.d; a.LP = p.LP;
+    a.nseg = p.nseg; a.causal = p.causal; a.TT = pick_tile(p.R, p.d, p.P);
+    a.N = p.N; a.seg_len = p.seg_len; a.beta = p.beta;
+    a.W = reinterpret_cast<const float *>(ws + p.off_W);
+    return a;
+}
+
+template <typename K>
+hipError_t allow_lds(K kernel, size_t bytes)
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(bytes));
+}
+
+#define RACE_TRY(expr)                                   \
+    do {                                                 \
+        hipError_t e_ = (expr);                          \
+        if (e_ != hipSuccess) return e_;                 \
+    } while (0)
+
+unsigned blocks_for(size_t n, unsigned per) { return static_cast<unsigned>((n + per - 1) / per); }
+
+template <typename T>
+hipError_t fwd_impl(const Plan &p, const T *Q, const T *K, const T *V, T *O, float *den, char *ws, hipStream_t st)
+{
+    const Args a = make_args(p, ws);
+    const size_t lds = smem_floats(p.R, p.d, p.P, a.TT) * sizeof(float);
+    float *state = reinterpret_cast<float *>(ws + p.off_stateA);
+    float *part = reinterpret_cast<float *>(ws + p.off_part);
+    const dim3 grid(p.nseg, p.L, p.BH);
+    const size_t elems = static_cast<size_t>(p.R) * (p.d + 1);
+    RACE_TRY(allow_lds(simple_totals<T, 0>, lds));
+    RACE_TRY(allow_lds(simple_fwd_replay<T>, lds));
+    hipLaunchKernelGGL((simple_totals<T, 0>), grid, dim3(kThreads), lds, st, a, K, V,
+                       static_cast<const T *>(nullptr), static_cast<const float *>(nullptr), state);
+    hipLaunchKernelGGL(simple_scan, dim3(blocks_for(elems, 256), p.BH * p.L), dim3(256), 0, st, state, p.nseg,
+                       elems, p.causal ? 0 : 2);
+    hipLaunchKernelGGL((simple_fwd_replay<T>), grid, dim3(kThreads), lds, st, a, Q, K, V, state, part);
+    const size_t total = static_cast<size_t>(p.BH) * p.N * p.d;
+    hipLaunchKernelGGL((simple_fwd_combine<T>), dim3(blocks_for(total, 256)), dim3(256), 0, st, a, p.BH, part, O, den);
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t bwd_impl(const Plan &p, const T *Q, const T *K, const T *V, const T *O, const float *den, const T *dO,
+                    T *dQ, T *dK, T *dV, char *ws, hipStream_t st)
+{
+    const Args a = make_args(p, ws);
+    const size_t lds = smem_floats(p.R, p.d, p.P, a.TT) * sizeof(float);
+    float *stateS = reinterpret_cast<float *>(ws + p.off_stateA);
+    float *stateD = reinterpret_cast<float *>(ws + p.off_stateB);
+    float *pQ = reinterpret_cast<float *>(ws + p.off_part);
+    const size_t per = static_cast<size_t>(p.BH) * p.L * p.N * p.d;
+    float *pK = pQ + per, *pV = pK + per;
+    const dim3 grid(p.nseg, p.L, p.BH);
+    const size_t elems = static_cast<size_t>(p.R) * (p.d + 1);
+    const dim3 sgrid(blocks_for(elems, 256), p.BH * p.L);
+    RACE_TRY(allow_lds(simple_totals<T, 0>, lds));
+    RACE_TRY(allow_lds(simple_totals<T, 1>, lds));
+    RACE_TRY(allow_lds(simple_bwd_query<T>, lds));
+    RACE_TRY(allow_lds(simple_bwd_keyvalue<T>, lds));
+    hipLaunchKernelGGL((simple_totals<T, 0>), grid, dim3(kThreads), lds, st, a, K, V,
+                       static_cast<const T *>(nullptr), static_cast<const float *>(nullptr), stateS);
+    hipLaunchKernelGGL(simple_scan, sgrid, dim3(256), 0, st, stateS, p.nseg, elems, p.causal ? 0 : 2);
+    hipLaunchKernelGGL((simple_totals<T, 1>), grid, dim3(kThreads), lds, st, a, Q, dO, O, den, stateD);
+    hipLaunchKernelGGL(simple_scan, sgrid, dim3(256), 0, st, stateD, p.nseg, elems, p.causal ? 1 : 2);
+    hipLaunchKernelGGL((simple_bwd_query<T>), grid, dim3(kThreads), lds, st, a, Q, K, V, O, den, dO, stateS, pQ);
+    hipLaunchKernelGGL((simple_bwd_keyvalue<T>), grid, dim3(kThreads), lds, st, a, Q, K, V, O, den, dO, stateD, pK, pV);
+    const size_t total = static_cast<size_t>(p.BH) * p.N * p.d;
+    hipLaunchKernelGGL((simple_bwd_combine<T>), dim3(blocks_for(total, 256)), dim3(256), 0, st, a, p.BH, pQ, pK, pV,
+                       dQ, dK, dV);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool simple_supported(int R, int d, int P) { return pick_tile(R, d, P) > 0; }
+
+hipError_t simple_fwd(const Plan &p, const void *Q, const void *K, const void *V, void *O, float *den, char *ws,
+                      hipStream_t st)
+{
+    if (p.dtype == RACE_F32)
+        return fwd_impl<float>(p, (const float *)Q, (const float *)K, (const float *)V, (float *)O, den, ws, st);
+    return fwd_impl<bf16_t>(p, (const bf16_t *)Q, (const bf16_t *)K, (const bf16_t *)V, (bf16_t *)O, den, ws, st);
+}
+
+hipError_t simple_bwd(const Plan &p, const void *Q, const void *K, const void *V, const void *O, const float *den,
+                      const void *dO, void *dQ, void *dK, void *dV, char *ws, hipStream_t st)
+{
+    if (p.dtype == RACE_F32)
+        return bwd_impl<float>(p, (const float *)Q, (const float *)K, (const float *)V, (const float *)O, den,
+                               (const float *)dO, (float *)dQ, (float *)dK, (float *)dV, ws, st);
+    return bwd_impl<bf16_t>(p, (const bf16_t *)Q, (const bf16_t *)K, (const bf16_t *)V, (const bf16_t *)O, den,
+                            (const bf16_t *)dO, (bf16_t *)dQ, (bf16_t *)dK, (bf16_t *)dV, ws, st);
+}
+
+hipError_t simple_hash(const Plan &p, const void *X, uint8_t *codes, float *phi, char *ws, hipStream_t st)
+{
+    const Args a = make_args(p, ws);
+    const size_t total = static_cast<size_t>(p.BH) * p.N * p.L;
+    if (p.dtype == RACE_F32)
+        hipLaunchKernelGGL((simple_hash_tap<float>), dim3(blocks_for(total, 128)), dim3(128), 0, st, a, p.BH,
+                           (const float *)X, codes, phi);
+    else
+        hipLaunchKernelGGL((simple_hash_tap<bf16_t>), dim3(blocks_for(total, 128)), dim3(128), 0, st, a, p.BH,
+                           (const bf16_t *)X, codes, phi);
+    return hipGetLastError();
+}
+
+hipError_t simple_buckets(const Plan &p, const void *K, const void *V, float *A, float *Bsum, char *ws,
+                          hipStream_t st)
+{
+    const Args a = make_args(p, ws);
+    const size_t lds = smem_floats(p.R, p.d, p.P, a.TT) * sizeof(float);
+    float *state = reinterpret_cast<float *>(ws + p.off_stateA);
+    const dim3 grid(p.nseg, p.L, p.BH);
+    if (p.dtype == RACE_F32) {
+        RACE_TRY(allow_lds(simple_totals<float, 0>, lds));
+        hipLaunchKernelGGL((simple_totals<float, 0>), grid, dim3(kThreads), lds, st, a, (const float *)K,
+                           (const float *)V, (const float *)nullptr, (const float *)nullptr, state);
+    } else {
+        RACE_TRY(allow_lds(simple_totals<bf16_t, 0>, lds));
+        hipLaunchKernelGGL((simple_totals<bf16_t, 0>), grid, dim3(kThreads), lds, st, a, (const bf16_t *)K,
+                           (const bf16_t *)V, (const bf16_t *)nullptr, (const float *)nullptr, state);
+    }
+    const size_t total = static_cast<size_t>(p.BH) * p.L * p.R * (p.d + 1);
+    hipLaunchKernelGGL(simple_bucket_tap, dim3(blocks_for(total, 256)), dim3(256), 0, st, a, p.BH, state, A, Bsum);
+    return hipGetLastError();
+}
+
+}  // namespace race

@@ -1,0 +1,67 @@
+"""Shared helpers of the GPU parity tests: run the HIP path through the C-ABI binding, run the oracle on
+the same (rounded) inputs, and compare with the error measure of the build's tolerance statement."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import paper_2510_04008_amd as ra
+from oracle import race_oracle as ro
+from oracle import stream as oracle_stream
+from paper_2510_04008_amd import synth
+
+# max |gpu - oracle| / max |oracle| per output tensor
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def desc_of(w: synth.Workload):
+    return ra.make_desc(w.B, w.H, w.N, w.d, w.L, w.P, w.sharpening, w.causal,
+                        ra.RACE_F32 if w.dtype == "f32" else ra.RACE_BF16, w.chunk)
+
+
+def to_f64(t: torch.Tensor) -> np.ndarray:
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def oracle_w(w: synth.Workload, seeds):
+    return np.stack([ro.expand_projection(s, w.L, w.P, w.d, round_bf16=(w.dtype == "bf16")) for s in seeds])
+
+
+def rel_err(gpu: torch.Tensor, ref: np.ndarray) -> float:
+    g = to_f64(gpu)
+    assert np.isfinite(g).all(), "non-finite values in GPU result"
+    scale = np.abs(ref).max()
+    return float(np.abs(g - ref).max() / (scale if scale > 0 else 1.0))
+
+
+def run_gpu(w: synth.Workload, tensors=None, seeds=None):
+    Q, K, V, dO = tensors if tensors is not None else synth.make_inputs(w, "cuda")
+    seeds = seeds if seeds is not None else synth.projection_seeds(w)
+    d = desc_of(w)
+    O, den = ra.race_attn_fwd(d, Q, K, V, seeds)
+    dQ, dK, dV = ra.race_attn_bwd(d, Q, K, V, O, den, dO, seeds)
+    torch.cuda.synchronize()
+    return dict(Q=Q, K=K, V=V, dO=dO, O=O, den=den, dQ=dQ, dK=dK, dV=dV, seeds=seeds)
+
+
+def run_oracle(w: synth.Workload, g):
+    W = oracle_w(w, g["seeds"])
+    Q, K, V, dO = (to_f64(g[n]) for n in ("Q", "K", "V", "dO"))
+    O, den = oracle_stream.forward(Q, K, V, W, w.sharpening, w.L, w.P, w.causal)
+    # the backward pass is a function of (Q, K, V, O, den, dO); feed it the oracle's own O and den
+    dQ, dK, dV = oracle_stream.backward(Q, K, V, W, w.sharpening, w.L, w.P, w.causal, O, den, dO)
+    return dict(O=O, den=den, dQ=dQ, dK=dK, dV=dV)
+
+
+def check_case(w: synth.Workload, tensors=None, tol=None, verbose=True):
+    tol = tol or TOL[w.dtype]
+    g = run_gpu(w, tensors)
+    r = run_oracle(w, g)
+    errs = {n: rel_err(g[n], r[n]) for n in ("O", "den", "dQ", "dK", "dV")}
+    if verbose:
+        print("%s: family=%d " % (w.name, ra.race_attn_kernel_family(desc_of(w))) +
+              " ".join("%s=%.2e" % kv for kv in errs.items()), flush=True)
+    assert r["den"].min() > 1e-30
+    for n, e in errs.items():
+        assert e < tol, "%s: %s rel err %.3e >= %.1e" % (w.name, n, e, tol)
+    return g, r, errs
