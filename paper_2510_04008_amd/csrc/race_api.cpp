@@ -253,9 +253,9 @@ race_status_t race_attn_fwd(const race_attn_desc_t *desc, const void *Q, const v
     Plan p;
     race_status_t s = make_plan(desc, &p);
     if (s != RACE_OK) return s;
+    if (p.N == 0) return RACE_OK;      // nothing to do, pointers may be null
     if (!Q || !K || !V || !proj_seeds || !O || !den) return RACE_ERR_INVALID_ARG;
     if (any_equal({O, den}, {Q, K, V, O, den})) return RACE_ERR_INVALID_ARG;
-    if (p.N == 0) return RACE_OK;
     if ((s = check_workspace(p, workspace, workspace_bytes, p.total)) != RACE_OK) return s;
     char *ws = static_cast<char *>(workspace);
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
@@ -273,9 +273,9 @@ race_status_t race_attn_bwd(const race_attn_desc_t *desc, const void *Q, const v
     Plan p;
     race_status_t s = make_plan(desc, &p);
     if (s != RACE_OK) return s;
+    if (p.N == 0) return RACE_OK;      // nothing to do, pointers may be null
     if (!Q || !K || !V || !O || !den || !dO || !proj_seeds || !dQ || !dK || !dV) return RACE_ERR_INVALID_ARG;
     if (any_equal({dQ, dK, dV}, {Q, K, V, O, den, dO, dQ, dK, dV})) return RACE_ERR_INVALID_ARG;
-    if (p.N == 0) return RACE_OK;
     if ((s = check_workspace(p, workspace, workspace_bytes, p.total)) != RACE_OK) return s;
     char *ws = static_cast<char *>(workspace);
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
@@ -302,8 +302,8 @@ race_status_t race_attn_debug_hash(const race_attn_desc_t *desc, const void *X, 
     Plan p;
     race_status_t s = make_plan(desc, &p);
     if (s != RACE_OK) return s;
+    if (p.N == 0) return RACE_OK;      // nothing to do, pointers may be null
     if (!X || !proj_seeds || !codes) return RACE_ERR_INVALID_ARG;
-    if (p.N == 0) return RACE_OK;
     if ((s = check_workspace(p, workspace, workspace_bytes, p.off_W + p.bytes_W)) != RACE_OK) return s;
     char *ws = static_cast<char *>(workspace);
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
@@ -320,8 +320,8 @@ race_status_t race_attn_debug_buckets(const race_attn_desc_t *desc, const void *
     Plan p;
     race_status_t s = make_plan(desc, &p);
     if (s != RACE_OK) return s;
+    if (p.N == 0) return RACE_OK;      // nothing to do, pointers may be null
     if (!K || !V || !proj_seeds || !A || !Bsum) return RACE_ERR_INVALID_ARG;
-    if (p.N == 0) return RACE_OK;
     if ((s = check_workspace(p, workspace, workspace_bytes, p.total)) != RACE_OK) return s;
     char *ws = static_cast<char *>(workspace);
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);

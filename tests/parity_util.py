@@ -27,10 +27,11 @@ def oracle_w(w: synth.Workload, seeds):
     return np.stack([ro.expand_projection(s, w.L, w.P, w.d, round_bf16=(w.dtype == "bf16")) for s in seeds])
 
 
-def rel_err(gpu: torch.Tensor, ref: np.ndarray) -> float:
+def rel_err(gpu: torch.Tensor, ref: np.ndarray, floor: float = 0.0) -> float:
+    """floor: lower bound of the scale, for tensors that are zero in exact arithmetic."""
     g = to_f64(gpu)
     assert np.isfinite(g).all(), "non-finite values in GPU result"
-    scale = np.abs(ref).max()
+    scale = max(np.abs(ref).max(), floor)
     return float(np.abs(g - ref).max() / (scale if scale > 0 else 1.0))
 
 
@@ -53,11 +54,12 @@ def run_oracle(w: synth.Workload, g):
     return dict(O=O, den=den, dQ=dQ, dK=dK, dV=dV)
 
 
-def check_case(w: synth.Workload, tensors=None, tol=None, verbose=True):
+def check_case(w: synth.Workload, tensors=None, tol=None, verbose=True, floors=None):
     tol = tol or TOL[w.dtype]
+    floors = floors or {}
     g = run_gpu(w, tensors)
     r = run_oracle(w, g)
-    errs = {n: rel_err(g[n], r[n]) for n in ("O", "den", "dQ", "dK", "dV")}
+    errs = {n: rel_err(g[n], r[n], floors.get(n, 0.0)) for n in ("O", "den", "dQ", "dK", "dV")}
     if verbose:
         print("%s: family=%d " % (w.name, ra.race_attn_kernel_family(desc_of(w))) +
               " ".join("%s=%.2e" % kv for kv in errs.items()), flush=True)

@@ -31,8 +31,11 @@ def test_ragged_multi_segment(causal, dtype, monkeypatch):
 
 @pytest.mark.parametrize("N", [1, 5, 8, 9])
 def test_tiny_sequences(N):
-    check_case(Workload("tinyN%d" % N, 1, 2, N, 16, 2, 2, 1.5, True, "f32", normalize_qk=True))
-    check_case(Workload("tinyN%d-nc" % N, 1, 2, N, 16, 2, 2, 1.5, False, "f32", normalize_qk=True))
+    # a single token attends only to itself: O = V and dQ = dK = 0 exactly, so those two are
+    # compared on an absolute scale
+    floors = {"dQ": 1.0, "dK": 1.0} if N == 1 else None
+    check_case(Workload("tinyN%d" % N, 1, 2, N, 16, 2, 2, 1.5, True, "f32", normalize_qk=True), floors=floors)
+    check_case(Workload("tinyN%d-nc" % N, 1, 2, N, 16, 2, 2, 1.5, False, "f32", normalize_qk=True), floors=floors)
 
 
 @pytest.mark.parametrize("L,P,d", [(1, 1, 8), (2, 8, 64), (5, 2, 256), (8, 6, 128)])
