@@ -1,0 +1,277 @@
+// Building blocks of the bf16 MFMA kernel family (gfx950): compile-time shapes, LDS tile layouts,
+// operand loads, the projection + soft-assignment "production" step.
+//
+// Execution shape.  One workgroup of four wavefronts owns one (batch*head, segment) and walks its
+// tokens in tiles of 32.  The bucket statistics of all L tables, [L*R][d] fp32 (B of Algorithm 1,
+// step 5; A is kept beside it), never leave the register file: wavefront w holds rows
+// [w*LR/4, (w+1)*LR/4) as 32x32 MFMA accumulator tiles.  Per tile the workgroup
+//   1. projects the 32 query and key rows on all L*P hyperplanes (MFMA) and turns the projections
+//      into soft assignments phi (vector ALU), written as bf16 tiles to LDS;
+//   2. contracts them with the register-resident statistics and with each other (MFMA).
+// MFMA 32x32x16 bf16 register layouts used throughout (lane = 32*h + n):
+//   A operand: row n of A, columns 8h..8h+7 of the 16-wide k-step;   B operand: column n of B, rows 8h..8h+7;
+//   C/D      : column n, rows 8*(v/4) + 4h + v%4 for register v = 0..15.
+// An accumulator tile is fed back as a B operand without touching LDS: registers 8s..8s+7 of the
+// tile, packed to bf16, are the B operand of k-step s if k-slot (h, e) is taken to mean row
+// 16s + 8*(e/4) + 4h + e%4; the A operand is loaded with the same permutation (two 8-byte reads).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace race {
+namespace mfma {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef uint16_t bf16raw;
+
+constexpr int kWaves = 4;
+constexpr int kThreads = 64 * kWaves;
+constexpr int kTile = 32;      // tokens per tile
+
+template <int D_, int P_, int L_>
+struct Cfg {
+    static constexpr int D = D_, P = P_, L = L_;
+    static constexpr int R = 1 << P, LR = L * R;
+    static constexpr int PP = P > 4 ? 8 : 4;            // hyperplanes per table, padded
+    static constexpr int TPG = 32 / PP;                 // tables per 32-row projection group
+    static constexpr int TPL = TPG / 2;                 // tables per lane (per half-wave)
+    static constexpr int NG = (L + TPG - 1) / TPG;      // projection groups
+    static constexpr int LPP = NG * 32;                 // padded projection rows
+    static constexpr int LRW = LR / kWaves;             // bucket rows owned by one wavefront
+    static constexpr int MT = LRW / 32;                 // 32-row tiles of bucket rows per wavefront
+    static constexpr int NT = D / 32;                   // 32-column tiles of the head dimension
+    static constexpr int PLO = P < 3 ? P : 3, PHI = P - PLO;
+    static constexpr int CPR = D / 8;                   // 16-byte chunks per row
+    // LDS row strides, in bf16 elements (rows stay 16-byte aligned; the pad staggers banks)
+    static constexpr int XS = D + 8;                    // [token][d] tiles and W rows
+    static constexpr int PS = LR + 8;                   // [token][L*R] assignment tiles
+    static constexpr int TS = kTile + 8;                // [row][token] transposed tiles
+    static constexpr int ZS = LPP + 8;                  // [token][padded projection] tiles
+    static constexpr int STATE = LR * (D + 1);          // floats per saved state: B [LR][D] then A [LR]
+    static_assert(LR % (32 * kWaves) == 0, "bucket rows must split into 32-row tiles per wavefront");
+    static_assert(D % 32 == 0 && R >= 8, "shape");
+    static_assert(2 * NG <= kWaves, "projection jobs must fit the wavefronts");
+};
+
+// ---------------------------------------------------------------- small helpers
+__device__ __forceinline__ uint32_t pack2(float lo, float hi)
+{
+    f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+__device__ __forceinline__ float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+__device__ __forceinline__ f32x16 mma(u32x4 a, u32x4 b, f32x16 c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c,
+                                                   0, 0, 0);
+}
+__device__ __forceinline__ u32x4 lds128(const bf16raw *p) { return *reinterpret_cast<const u32x4 *>(p); }
+__device__ __forceinline__ u32x4 lds64x2(const bf16raw *p0, const bf16raw *p1)
+{
+    const u32x2 a = *reinterpret_cast<const u32x2 *>(p0), b = *reinterpret_cast<const u32x2 *>(p1);
+    return u32x4{a.x, a.y, b.x, b.y};
+}
+// accumulator registers 8s..8s+7 as a bf16 B (or A) operand
+__device__ __forceinline__ u32x4 acc_operand(const f32x16 &t, int s)
+{
+    return s == 0 ? u32x4{pack2(t[0], t[1]), pack2(t[2], t[3]), pack2(t[4], t[5]), pack2(t[6], t[7])}
+                  : u32x4{pack2(t[8], t[9]), pack2(t[10], t[11]), pack2(t[12], t[13]), pack2(t[14], t[15])};
+}
+__device__ __forceinline__ float sum8(u32x4 v)
+{
+    return ((bf_lo(v.x) + bf_hi(v.x)) + (bf_lo(v.y) + bf_hi(v.y))) + ((bf_lo(v.z) + bf_hi(v.z)) + (bf_lo(v.w) + bf_hi(v.w)));
+}
+// row of accumulator register v for lane half h
+__device__ __forceinline__ int acc_row(int v, int h) { return 8 * (v >> 2) + 4 * h + (v & 3); }
+
+// ---------------------------------------------------------------- global -> LDS tiles
+// rows [t0, t0+nvalid) of X (row-major, D contiguous) -> dst[32][XS]; missing rows are zero
+template <class C>
+__device__ __forceinline__ void load_tile(const bf16raw *X, int64_t t0, int nvalid, bf16raw *dst)
+{
+    for (int c = threadIdx.x; c < kTile * C::CPR; c += kThreads) {
+        const int row = c / C::CPR, ch = c % C::CPR;
+        u32x4 v = {0, 0, 0, 0};
+        if (row < nvalid) v = *reinterpret_cast<const u32x4 *>(X + (t0 + row) * C::D + ch * 8);
+        *reinterpret_cast<u32x4 *>(dst + row * C::XS + ch * 8) = v;
+    }
+}
+
+// the same rows transposed: dstT[D][TS] (column-major tile, tokens contiguous)
+template <class C>
+__device__ __forceinline__ void load_tile_transposed(const bf16raw *X, int64_t t0, int nvalid, bf16raw *dstT)
+{
+    for (int c = threadIdx.x; c < kTile * C::CPR; c += kThreads) {
+        const int row = c / C::CPR, ch = c % C::CPR;
+        u32x4 v = {0, 0, 0, 0};
+        if (row < nvalid) v = *reinterpret_cast<const u32x4 *>(X + (t0 + row) * C::D + ch * 8);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            dstT[(ch * 8 + 2 * e) * C::TS + row] = static_cast<bf16raw>(w[e] & 0xffffu);
+            dstT[(ch * 8 + 2 * e + 1) * C::TS + row] = static_cast<bf16raw>(w[e] >> 16);
+        }
+    }
+}
+
+// Read-out cotangent rows: gn = dO / e (e = L * Den) as bf16, natural (dst, may be null) and/or
+// transposed (dstT, may be null); ge[row] = -(dO . O) / e as fp32 (ge, may be null).
+template <class C>
+__device__ __forceinline__ void load_cotangent_tile(const bf16raw *dO, const bf16raw *O, const float *den, int64_t t0,
+                                                    int nvalid, bf16raw *dst, bf16raw *dstT, float *ge)
+{
+    for (int c = threadIdx.x; c < kTile * C::CPR; c += kThreads) {
+        const int row = c / C::CPR, ch = c % C::CPR;
+        u32x4 g = {0, 0, 0, 0}, o = {0, 0, 0, 0};
+        float inv = 0.f;
+        if (row < nvalid) {
+            g = *reinterpret_cast<const u32x4 *>(dO + (t0 + row) * C::D + ch * 8);
+            o = *reinterpret_cast<const u32x4 *>(O + (t0 + row) * C::D + ch * 8);
+            inv = 1.0f / (den[t0 + row] * static_cast<float>(C::L));
+        }
+        const uint32_t gw[4] = {g.x, g.y, g.z, g.w}, ow[4] = {o.x, o.y, o.z, o.w};
+        uint32_t out[4];
+        float dot = 0.f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float g0 = bf_lo(gw[e]), g1 = bf_hi(gw[e]);
+            dot = fmaf(g0, bf_lo(ow[e]), dot);
+            dot = fmaf(g1, bf_hi(ow[e]), dot);
+            out[e] = pack2(g0 * inv, g1 * inv);
+            if (dstT) {
+                dstT[(ch * 8 + 2 * e) * C::TS + row] = static_cast<bf16raw>(out[e] & 0xffffu);
+                dstT[(ch * 8 + 2 * e + 1) * C::TS + row] = static_cast<bf16raw>(out[e] >> 16);
+            }
+        }
+        if (dst) *reinterpret_cast<u32x4 *>(dst + row * C::XS + ch * 8) = u32x4{out[0], out[1], out[2], out[3]};
+        if (ge) {
+            // the CPR threads of one row are consecutive lanes
+#pragma unroll
+            for (int m = C::CPR / 2; m >= 1; m >>= 1) dot += __shfl_xor(dot, m, 64);
+            if (ch == 0) ge[row] = -dot * inv;
+        }
+    }
+}
+
+// ---------------------------------------------------------------- projection + soft assignment
+// z^T (32 projection rows of group g) x (32 tokens) = Wg . X^T, contraction over d (Algorithm 1, step 4:
+// the argument of tanh).  Lane (n, h) ends up with the projections of token n for the TPL tables
+// {g*TPG + h*TPL + j}: the host stores W's rows in that order (see pack_projection()).
+template <class C>
+__device__ __forceinline__ f32x16 project(const bf16raw *wp, const bf16raw *x, int g, int ln, int h)
+{
+    f32x16 z = {0};
+#pragma unroll
+    for (int s = 0; s < C::D / 16; ++s) {
+        const u32x4 a = lds128(wp + (g * 32 + ln) * C::XS + 16 * s + 8 * h);
+        const u32x4 b = lds128(x + ln * C::XS + 16 * s + 8 * h);
+        z = mma(a, b, z);
+    }
+    return z;
+}
+// projection t of the lane's j-th table inside the accumulator
+template <class C>
+__device__ __forceinline__ constexpr int zslot(int j, int t)
+{
+    return C::PP == 8 ? 4 * (2 * j + t / 4) + t % 4 : 4 * j + t;
+}
+
+// Per-bit masses of one table: p[t] = sigmoid(2 beta tanh z_t) (mass on the +1 side), q[t] = 1 - p[t],
+// computed without cancellation; sech2[t] = 1 - tanh^2 z_t.
+template <class C>
+__device__ __forceinline__ void bit_masses(const f32x16 &z, int j, float beta, float *p, float *q, float *sech2)
+{
+#pragma unroll
+    for (int t = 0; t < C::P; ++t) {
+        const float zt = z[zslot<C>(j, t)];
+        const float e2 = __expf(-2.0f * fabsf(zt));
+        const float inv = __builtin_amdgcn_rcpf(1.0f + e2);
+        const float ua = (1.0f - e2) * inv;                    // |tanh z|
+        const float e = __expf(-2.0f * beta * ua);
+        const float big = __builtin_amdgcn_rcpf(1.0f + e), small = e * big;
+        const bool pos = zt >= 0.f;
+        p[t] = pos ? big : small;
+        q[t] = pos ? small : big;
+        if (sech2) sech2[t] = 4.0f * e2 * inv * inv;
+    }
+}
+
+// phi over the low PLO bits (lo) and the high PHI bits (hi): phi[a * 2^PLO + b] = hi[a] * lo[b]
+// (the corner softmax is a product of per-bit two-point distributions).
+template <class C>
+__device__ __forceinline__ void kron_factors(const float *p, const float *q, float *lo, float *hi)
+{
+    lo[0] = 1.f;
+#pragma unroll
+    for (int t = 0; t < C::PLO; ++t) {
+#pragma unroll
+        for (int b = 0; b < (1 << t); ++b) {
+            lo[b + (1 << t)] = lo[b] * p[t];
+            lo[b] = lo[b] * q[t];
+        }
+    }
+    hi[0] = 1.f;
+#pragma unroll
+    for (int t = 0; t < C::PHI; ++t) {
+#pragma unroll
+        for (int b = 0; b < (1 << t); ++b) {
+            hi[b + (1 << t)] = hi[b] * p[C::PLO + t];
+            hi[b] = hi[b] * q[C::PLO + t];
+        }
+    }
+}
+
+// Writes the assignment of the lane's token for its TPL tables as bf16:
+//   ph  [token][L*R]   (may be null)        pht [L*R][token]   (may be null)
+// valid == false writes zeros (a token past the end of the sequence must not reach the statistics).
+// If mass != null, returns sum_r phi[r] * mass[table*R + r] over the lane's tables (the read-out of
+// the bucket masses A for this token), else 0.
+template <class C>
+__device__ __forceinline__ float write_assignments(const f32x16 &z, int g, int ln, int h, float beta, bool valid,
+                                                   bf16raw *ph, bf16raw *pht, const float *mass)
+{
+    float dn = 0.f;
+#pragma unroll
+    for (int j = 0; j < C::TPL; ++j) {
+        const int table = g * C::TPG + h * C::TPL + j;
+        if (table >= C::L) break;
+        float p[C::P], q[C::P], lo[1 << C::PLO], hi[1 << C::PHI];
+        bit_masses<C>(z, j, beta, p, q, nullptr);
+        kron_factors<C>(p, q, lo, hi);
+#pragma unroll
+        for (int a = 0; a < (1 << C::PHI); ++a) {
+            const float ha = valid ? hi[a] : 0.f;
+            float f[1 << C::PLO];
+#pragma unroll
+            for (int b = 0; b < (1 << C::PLO); ++b) f[b] = ha * lo[b];
+            const int r0 = table * C::R + a * (1 << C::PLO);
+            if (mass) {
+                const float4 m0 = *reinterpret_cast<const float4 *>(mass + r0);
+                const float4 m1 = *reinterpret_cast<const float4 *>(mass + r0 + 4);
+                dn = fmaf(f[0], m0.x, dn); dn = fmaf(f[1], m0.y, dn); dn = fmaf(f[2], m0.z, dn); dn = fmaf(f[3], m0.w, dn);
+                dn = fmaf(f[4], m1.x, dn); dn = fmaf(f[5], m1.y, dn); dn = fmaf(f[6], m1.z, dn); dn = fmaf(f[7], m1.w, dn);
+            }
+            const u32x4 packed = {pack2(f[0], f[1]), pack2(f[2], f[3]), pack2(f[4], f[5]), pack2(f[6], f[7])};
+            if (ph) *reinterpret_cast<u32x4 *>(ph + ln * C::PS + r0) = packed;
+            if (pht) {
+                const uint32_t w[4] = {packed.x, packed.y, packed.z, packed.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    pht[(r0 + 2 * e) * C::TS + ln] = static_cast<bf16raw>(w[e] & 0xffffu);
+                    pht[(r0 + 2 * e + 1) * C::TS + ln] = static_cast<bf16raw>(w[e] >> 16);
+                }
+            }
+        }
+    }
+    return dn;
+}
+
+}  // namespace mfma
+}  // namespace race

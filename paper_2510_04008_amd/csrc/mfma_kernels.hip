@@ -1,11 +1,577 @@
-// placeholder until the MFMA family lands
+// bf16 MFMA kernel family for RACE Attention on gfx950 (see mfma_common.h for the execution shape).
+//
+// Kernels
+//   scan_kernel      "totals" of the statistics per segment, then an exclusive prefix (forward) or
+//                    suffix (backward) scan over segments turns them into segment-start states.
+//   stream_kernel    one pass over a segment carrying statistics [L*R][d] in accumulator registers
+//                    as tiles (bucket rows x head columns).  Modes:
+//                      kTotalsKV  statistics of (phi_K, [V | 1])          (Algorithm 1, step 5)
+//                      kTotalsQG  statistics of (phi_Q, read-out cotangents) for the backward pass
+//                      kForward   Algorithm 2's loop / Algorithm 1's read-out: O and Den
+//                      kGradV     the mirrored pass, right to left: dV
+//   grad_kernel      (mfma_grad.h) the passes that contract over the head dimension: dQ and dK.
+#include <hip/hip_runtime.h>
+
 #include "internal.h"
+#include <cstring>
+
+#include "mfma_common.h"
+
 namespace race {
-bool mfma_supported(int, int, int) { return false; }
-size_t mfma_projection_bytes(const Plan &) { return 0; }
-void mfma_pack_projection(const Plan &, const float *, void *) {}
-hipError_t mfma_fwd(const Plan &, const void *, const void *, const void *, void *, float *, char *, hipStream_t) { return hipErrorNotSupported; }
-hipError_t mfma_bwd(const Plan &, const void *, const void *, const void *, const void *, const float *, const void *, void *, void *, void *, char *, hipStream_t) { return hipErrorNotSupported; }
-hipError_t mfma_hash(const Plan &, const void *, uint8_t *, float *, char *, hipStream_t) { return hipErrorNotSupported; }
-hipError_t mfma_buckets(const Plan &, const void *, const void *, float *, float *, char *, hipStream_t) { return hipErrorNotSupported; }
+namespace mfma {
+
+struct KArgs {
+    int H, nseg, causal;
+    int64_t N, seg_len;
+    float beta;
+    const bf16raw *Wp;     // (H, LPP, D) bf16, rows in projection-group order
+    const bf16raw *WpT;    // (H, D, LPP) bf16
+    float *state;          // (BH, nseg, STATE) fp32
+};
+
+enum Mode { kTotalsKV = 0, kTotalsQG = 1, kForward = 2, kGradV = 3 };
+
+// ---------------------------------------------------------------- LDS map of stream_kernel (bytes)
+template <class C>
+struct StreamLds {
+    static constexpr int wp = 0;                                        // [LPP][XS] bf16
+    static constexpr int yt = wp + C::LPP * C::XS * 2;                  // [D][TS] bf16: accumulated tensor, transposed
+    static constexpr int scb = yt + C::D * C::TS * 2;                   // [32][TS] bf16: masked in-tile kernel
+    static constexpr int mass = scb + kTile * C::TS * 2;                // [LR] fp32: bucket masses A before this tile
+    static constexpr int dnp = mass + C::LR * 4;                        // [NG][32] fp32: per-group mass read-outs
+    static constexpr int e = dnp + C::NG * kTile * 4;                   // [32] fp32: un-averaged normaliser
+    static constexpr int ge = e + kTile * 4;                            // [32] fp32: normaliser cotangents
+    static constexpr int area = (ge + kTile * 4 + 255) & ~255;          // start of the aliased area
+    // phase A (production, contraction)
+    static constexpr int xr = area;                                     // [32][XS] reader rows
+    static constexpr int xw = xr + kTile * C::XS * 2;                   // [32][XS] writer rows
+    static constexpr int phr = xw + kTile * C::XS * 2;                  // [32][PS] reader assignments
+    static constexpr int phw = phr + kTile * C::PS * 2;                 // [32][PS] writer assignments
+    static constexpr int pht = phw + kTile * C::PS * 2;                 // [LR][TS] writer assignments, transposed
+    static constexpr int endA = pht + C::LR * C::TS * 2;
+    // phase B (cross-wavefront reduction) reuses the same bytes
+    static constexpr int RS = C::D + 4;                                 // fp32 row stride of the partial read-outs
+    static constexpr int red = area;                                    // [4][32][RS] fp32
+    static constexpr int redsc = red + kWaves * kTile * RS * 4;         // [4][32][33] fp32
+    static constexpr int endB = redsc + kWaves * kTile * 33 * 4;
+    static constexpr int total = endA > endB ? endA : endB;
+    static_assert(total <= 160 * 1024, "LDS budget");
+};
+
+// state element (bucket row r, column c) in the saved layout
+template <class C>
+__device__ __forceinline__ int state_b(int r, int c) { return r * C::D + c; }
+template <class C>
+__device__ __forceinline__ int state_a(int r) { return C::LR * C::D + r; }
+
+template <class C, int MODE>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw *Y, const bf16raw *Oin,
+                   const float *den_in, bf16raw *Out, float *den_out)
+{
+    // Xr: tensor hashed on the reading side (Q forward, K for dV); Xw: on the writing side (K forward, Q for dV)
+    // Y : tensor accumulated into the statistics (V forward; dO for the cotangent statistics)
+    using S = StreamLds<C>;
+    extern __shared__ __attribute__((aligned(256))) unsigned char lds[];
+    bf16raw *wp = reinterpret_cast<bf16raw *>(lds + S::wp);
+    bf16raw *yt = reinterpret_cast<bf16raw *>(lds + S::yt);
+    bf16raw *scb = reinterpret_cast<bf16raw *>(lds + S::scb);
+    float *mass = reinterpret_cast<float *>(lds + S::mass);
+    float *dnp = reinterpret_cast<float *>(lds + S::dnp);
+    float *e_lds = reinterpret_cast<float *>(lds + S::e);
+    float *ge_lds = reinterpret_cast<float *>(lds + S::ge);
+    bf16raw *xr = reinterpret_cast<bf16raw *>(lds + S::xr);
+    bf16raw *xw = reinterpret_cast<bf16raw *>(lds + S::xw);
+    bf16raw *phr = reinterpret_cast<bf16raw *>(lds + S::phr);
+    bf16raw *phw = reinterpret_cast<bf16raw *>(lds + S::phw);
+    bf16raw *pht = reinterpret_cast<bf16raw *>(lds + S::pht);
+    float *red = reinterpret_cast<float *>(lds + S::red);
+    float *redsc = reinterpret_cast<float *>(lds + S::redsc);
+
+    constexpr bool kTotals = (MODE == kTotalsKV || MODE == kTotalsQG);
+    constexpr bool kReverse = (MODE == kGradV);
+    constexpr bool kCotangentY = (MODE == kTotalsQG || MODE == kGradV);   // Y = dO / e (and ge for the mass column)
+    constexpr bool kMass = (MODE != kGradV);                               // the mass column A is carried
+
+    const int seg = blockIdx.x, bh = blockIdx.y, head = bh % a.H;
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, ln = lane & 31, h = lane >> 5;
+    const int r_own = w * C::LRW;
+    const bool intra = kTotals || a.causal;          // the tile's own keys take part (always for totals)
+
+    const size_t base = static_cast<size_t>(bh) * a.N * C::D;
+    Xr += base; Xw += base; Y += base;
+    if (Oin) Oin += base;
+    if (Out) Out += base;
+    if (den_in) den_in += static_cast<size_t>(bh) * a.N;
+    if (den_out) den_out += static_cast<size_t>(bh) * a.N;
+    float *st = a.state + (static_cast<size_t>(bh) * a.nseg + seg) * C::STATE;
+
+    // projection matrix of this head -> LDS
+    {
+        const bf16raw *src = a.Wp + static_cast<size_t>(head) * C::LPP * C::D;
+        for (int c = tid; c < C::LPP * C::CPR; c += kThreads) {
+            const int row = c / C::CPR, ch = c % C::CPR;
+            *reinterpret_cast<u32x4 *>(wp + row * C::XS + ch * 8) =
+                *reinterpret_cast<const u32x4 *>(src + row * C::D + ch * 8);
+        }
+    }
+    // statistics at the start of the segment
+    f32x16 Sacc[C::MT][C::NT];
+    float macc[C::MT];                 // bucket masses: per-half partial sums, lane n <-> row r_own + 32*mt + n
+#pragma unroll
+    for (int mt = 0; mt < C::MT; ++mt) {
+        macc[mt] = 0.f;
+#pragma unroll
+        for (int nt = 0; nt < C::NT; ++nt) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                Sacc[mt][nt][v] = kTotals ? 0.f : st[state_b<C>(r_own + 32 * mt + acc_row(v, h), 32 * nt + ln)];
+        }
+        if (!kTotals && kMass && h == 0) macc[mt] = st[state_a<C>(r_own + 32 * mt + ln)];
+    }
+    if (MODE == kForward) {
+#pragma unroll
+        for (int mt = 0; mt < C::MT; ++mt)
+            if (h == 0) mass[r_own + 32 * mt + ln] = macc[mt];
+    }
+
+    const int64_t t_begin = seg * a.seg_len;
+    const int64_t t_end = (t_begin + a.seg_len < a.N) ? t_begin + a.seg_len : a.N;
+    const int ntiles = static_cast<int>((t_end - t_begin + kTile - 1) / kTile);
+
+    for (int it = 0; it < ntiles; ++it) {
+        const int tile = kReverse ? ntiles - 1 - it : it;
+        const int64_t t0 = t_begin + static_cast<int64_t>(tile) * kTile;
+        const int nvalid = (t_end - t0 < kTile) ? static_cast<int>(t_end - t0) : kTile;
+
+        // ---- global -> LDS
+        if (!kTotals) load_tile<C>(Xr, t0, nvalid, xr);
+        if (intra) {
+            load_tile<C>(Xw, t0, nvalid, xw);
+            if (kCotangentY) load_cotangent_tile<C>(Y, Oin, den_in, t0, nvalid, nullptr, yt, MODE == kTotalsQG ? ge_lds : nullptr);
+            else load_tile_transposed<C>(Y, t0, nvalid, yt);
+        }
+        __syncthreads();
+
+        // ---- production: wavefront = (side, projection group)
+        {
+            const int side = w / C::NG, g = w % C::NG;          // side 0: reader, 1: writer
+            if (side == 0 && !kTotals) {
+                const f32x16 z = project<C>(wp, xr, g, ln, h);
+                float dn = write_assignments<C>(z, g, ln, h, a.beta, true, phr, nullptr, MODE == kForward ? mass : nullptr);
+                if (MODE == kForward) {
+                    dn += __shfl_xor(dn, 32, 64);
+                    if (h == 0) dnp[g * kTile + ln] = dn;
+                }
+            } else if (side == 1 && intra) {
+                const f32x16 z = project<C>(wp, xw, g, ln, h);
+                write_assignments<C>(z, g, ln, h, a.beta, ln < nvalid, kTotals ? nullptr : phw, pht, nullptr);
+            }
+        }
+        __syncthreads();
+
+        // ---- contraction with the register-resident statistics
+        f32x16 out[C::NT];
+        f32x16 sc = {0};
+        if (!kTotals) {
+#pragma unroll
+            for (int nt = 0; nt < C::NT; ++nt) out[nt] = f32x16{0};
+#pragma unroll
+            for (int mt = 0; mt < C::MT; ++mt) {
+#pragma unroll
+                for (int s = 0; s < 2; ++s) {
+                    const int rr = r_own + 32 * mt + 16 * s + 4 * h;
+                    const u32x4 ar = lds64x2(phr + ln * C::PS + rr, phr + ln * C::PS + rr + 8);
+#pragma unroll
+                    for (int nt = 0; nt < C::NT; ++nt) out[nt] = mma(ar, acc_operand(Sacc[mt][nt], s), out[nt]);
+                    if (intra) {
+                        const u32x4 bw = lds64x2(phw + ln * C::PS + rr, phw + ln * C::PS + rr + 8);
+                        sc = mma(ar, bw, sc);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);      // keep operand conversion from being hoisted wholesale
+                }
+            }
+        }
+        // ---- statistics += phi_writer^T . Y  (after the read-out above used the old statistics)
+        if (intra) {
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                u32x4 by[C::NT];
+#pragma unroll
+                for (int nt = 0; nt < C::NT; ++nt) by[nt] = lds128(yt + (32 * nt + ln) * C::TS + 16 * s + 8 * h);
+                float gw[8];
+                if (MODE == kTotalsQG) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) gw[e] = ge_lds[16 * s + 8 * h + e];
+                }
+#pragma unroll
+                for (int mt = 0; mt < C::MT; ++mt) {
+                    const u32x4 ap = lds128(pht + (r_own + 32 * mt + ln) * C::TS + 16 * s + 8 * h);
+                    if (MODE == kTotalsQG) {
+                        macc[mt] += bf_lo(ap.x) * gw[0] + bf_hi(ap.x) * gw[1] + bf_lo(ap.y) * gw[2] + bf_hi(ap.y) * gw[3] +
+                                    bf_lo(ap.z) * gw[4] + bf_hi(ap.z) * gw[5] + bf_lo(ap.w) * gw[6] + bf_hi(ap.w) * gw[7];
+                    } else if (kMass) {
+                        macc[mt] += sum8(ap);
+                    }
+#pragma unroll
+                    for (int nt = 0; nt < C::NT; ++nt) Sacc[mt][nt] = mma(ap, by[nt], Sacc[mt][nt]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
+        if (kTotals) {
+            __syncthreads();
+            continue;
+        }
+        __syncthreads();        // every wavefront is done with the assignment tiles
+
+        // ---- cross-wavefront reduction of the partial read-outs (each wavefront covered LR/4 bucket rows)
+#pragma unroll
+        for (int nt = 0; nt < C::NT; ++nt) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                red[(w * kTile + acc_row(v, h)) * S::RS + 32 * nt + ln] = out[nt][v];
+        }
+        if (intra) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) redsc[(w * kTile + acc_row(v, h)) * 33 + ln] = sc[v];
+        }
+        if (MODE == kForward) {
+            // masses after this tile, for the next tile's read-out
+#pragma unroll
+            for (int mt = 0; mt < C::MT; ++mt) {
+                const float tot = macc[mt] + __shfl_xor(macc[mt], 32, 64);
+                if (h == 0) mass[r_own + 32 * mt + ln] = tot;
+            }
+        }
+        __syncthreads();
+        {
+            // in-tile kernel values: sum the partials, mask, row sums, bf16 copy as an MFMA operand
+            const int i = tid >> 3, j0 = (tid & 7) * 4;
+            float k4[4] = {0.f, 0.f, 0.f, 0.f};
+            float rowsum = 0.f;
+            if (intra) {
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) {
+                    const int j = j0 + jj;
+                    float v = 0.f;
+#pragma unroll
+                    for (int ww = 0; ww < kWaves; ++ww) v += redsc[(ww * kTile + i) * 33 + j];
+                    const bool keep = kReverse ? (j >= i) : (j <= i);
+                    k4[jj] = keep ? v : 0.f;
+                    rowsum += k4[jj];
+                }
+            }
+            *reinterpret_cast<u32x2 *>(scb + i * C::TS + j0) = u32x2{pack2(k4[0], k4[1]), pack2(k4[2], k4[3])};
+            if (MODE == kForward) {
+                rowsum += __shfl_xor(rowsum, 1, 64);
+                rowsum += __shfl_xor(rowsum, 2, 64);
+                rowsum += __shfl_xor(rowsum, 4, 64);
+                if ((tid & 7) == 0) {
+                    float e = rowsum;
+#pragma unroll
+                    for (int g = 0; g < C::NG; ++g) e += dnp[g * kTile + i];
+                    e_lds[i] = e;
+                    if (i < nvalid) den_out[t0 + i] = e * (1.0f / C::L);
+                }
+            }
+        }
+        __syncthreads();
+        // ---- epilogue: sum the partial read-outs, add the in-tile part (kernel . Y), normalise, store
+        for (int nt = w; nt < C::NT; nt += kWaves) {
+            f32x16 acc;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = acc_row(v, h);
+                float s0 = 0.f;
+#pragma unroll
+                for (int ww = 0; ww < kWaves; ++ww) s0 += red[(ww * kTile + row) * S::RS + 32 * nt + ln];
+                acc[v] = s0;
+            }
+            if (intra) {
+#pragma unroll
+                for (int s = 0; s < 2; ++s) {
+                    const u32x4 ak = lds128(scb + ln * C::TS + 16 * s + 8 * h);
+                    const u32x4 by = lds128(yt + (32 * nt + ln) * C::TS + 16 * s + 8 * h);
+                    acc = mma(ak, by, acc);
+                }
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = acc_row(v, h);
+                if (row < nvalid) {
+                    const float val = (MODE == kForward) ? acc[v] / e_lds[row] : acc[v];
+                    Out[(t0 + row) * C::D + 32 * nt + ln] = static_cast<bf16raw>(pack2(val, 0.f) & 0xffffu);
+                }
+            }
+        }
+        __syncthreads();
+    }
+
+    if (kTotals) {
+#pragma unroll
+        for (int mt = 0; mt < C::MT; ++mt) {
+#pragma unroll
+            for (int nt = 0; nt < C::NT; ++nt) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    st[state_b<C>(r_own + 32 * mt + acc_row(v, h), 32 * nt + ln)] = Sacc[mt][nt][v];
+            }
+            const float tot = macc[mt] + __shfl_xor(macc[mt], 32, 64);
+            if (h == 0) st[state_a<C>(r_own + 32 * mt + ln)] = tot;
+        }
+    }
 }
+
+// In-place scan over the segments of one (batch*head).  mode 0: exclusive prefix, 1: exclusive suffix,
+// 2: every segment gets the total (non-causal).
+__global__ void scan_kernel(float *state, int nseg, int elems, int mode)
+{
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= elems) return;
+    float *base = state + static_cast<size_t>(blockIdx.y) * nseg * elems + e;
+    float run = 0.f;
+    if (mode == 0) {
+        for (int s = 0; s < nseg; ++s) { const float v = base[static_cast<size_t>(s) * elems]; base[static_cast<size_t>(s) * elems] = run; run += v; }
+    } else if (mode == 1) {
+        for (int s = nseg - 1; s >= 0; --s) { const float v = base[static_cast<size_t>(s) * elems]; base[static_cast<size_t>(s) * elems] = run; run += v; }
+    } else {
+        for (int s = 0; s < nseg; ++s) run += base[static_cast<size_t>(s) * elems];
+        for (int s = 0; s < nseg; ++s) base[static_cast<size_t>(s) * elems] = run;
+    }
+}
+
+// Debug tap: totals over all segments, split into A (BH, L, R) and B (BH, L, R, D)
+template <class C>
+__global__ void bucket_tap_kernel(const float *state, int nseg, int BH, float *A, float *Bsum)
+{
+    const size_t i = blockIdx.x * static_cast<size_t>(blockDim.x) + threadIdx.x;
+    if (i >= static_cast<size_t>(BH) * C::STATE) return;
+    const size_t bh = i / C::STATE;
+    const int e = static_cast<int>(i - bh * C::STATE);
+    float run = 0.f;
+    for (int s = 0; s < nseg; ++s) run += state[(bh * nseg + s) * C::STATE + e];
+    if (e < C::LR * C::D) Bsum[bh * C::LR * C::D + e] = run;
+    else A[bh * C::LR + (e - C::LR * C::D)] = run;
+}
+
+// Debug tap: hard codes and phi from the production step itself.
+template <class C>
+__global__ __launch_bounds__(kThreads) void hash_tap_kernel(KArgs a, const bf16raw *X, uint8_t *codes, float *phi)
+{
+    extern __shared__ __attribute__((aligned(256))) unsigned char lds[];
+    bf16raw *wp = reinterpret_cast<bf16raw *>(lds);
+    bf16raw *x = wp + C::LPP * C::XS;
+    bf16raw *ph = x + kTile * C::XS;
+    const int bh = blockIdx.y, head = bh % a.H;
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, ln = lane & 31, h = lane >> 5;
+    const int64_t t0 = static_cast<int64_t>(blockIdx.x) * kTile;
+    const int nvalid = (a.N - t0 < kTile) ? static_cast<int>(a.N - t0) : kTile;
+    const bf16raw *src = a.Wp + static_cast<size_t>(head) * C::LPP * C::D;
+    for (int c = tid; c < C::LPP * C::CPR; c += kThreads) {
+        const int row = c / C::CPR, ch = c % C::CPR;
+        *reinterpret_cast<u32x4 *>(wp + row * C::XS + ch * 8) = *reinterpret_cast<const u32x4 *>(src + row * C::D + ch * 8);
+    }
+    load_tile<C>(X + static_cast<size_t>(bh) * a.N * C::D, t0, nvalid, x);
+    __syncthreads();
+    if (w < C::NG) {
+        const int g = w;
+        const f32x16 z = project<C>(wp, x, g, ln, h);
+        write_assignments<C>(z, g, ln, h, a.beta, true, ph, nullptr, nullptr);
+        if (ln < nvalid) {
+#pragma unroll
+            for (int j = 0; j < C::TPL; ++j) {
+                const int table = g * C::TPG + h * C::TPL + j;
+                if (table >= C::L) break;
+                unsigned code = 0;
+#pragma unroll
+                for (int t = 0; t < C::P; ++t) code |= (z[zslot<C>(j, t)] >= 0.f ? 1u : 0u) << t;
+                codes[(static_cast<size_t>(bh) * a.N + t0 + ln) * C::L + table] = static_cast<uint8_t>(code);
+            }
+        }
+    }
+    __syncthreads();
+    if (phi) {
+        for (int i = tid; i < nvalid * C::LR; i += kThreads) {
+            const int row = i / C::LR, r = i % C::LR;
+            phi[(static_cast<size_t>(bh) * a.N + t0 + row) * C::LR + r] = __uint_as_float(static_cast<uint32_t>(ph[row * C::PS + r]) << 16);
+        }
+    }
+}
+
+}  // namespace mfma
+
+// ================================================================================ host side
+namespace {
+
+using namespace mfma;
+
+#define RACE_TRY(expr)                                   \
+    do {                                                 \
+        hipError_t e_ = (expr);                          \
+        if (e_ != hipSuccess) return e_;                 \
+    } while (0)
+
+template <class K>
+hipError_t allow_lds(K kernel, size_t bytes)
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                               static_cast<int>(bytes));
+}
+
+template <class C>
+KArgs make_kargs(const Plan &p, char *ws)
+{
+    KArgs a;
+    a.H = p.H; a.nseg = p.nseg; a.causal = p.causal; a.N = p.N; a.seg_len = p.seg_len; a.beta = p.beta;
+    a.Wp = reinterpret_cast<const bf16raw *>(ws + p.off_W);
+    a.WpT = a.Wp + static_cast<size_t>(p.H) * C::LPP * C::D;
+    a.state = reinterpret_cast<float *>(ws + p.off_stateA);
+    return a;
+}
+
+template <class C, int MODE>
+hipError_t launch_stream(const Plan &p, KArgs a, const void *Xr, const void *Xw, const void *Y, const void *O,
+                         const float *den_in, void *Out, float *den_out, hipStream_t st)
+{
+    auto kern = stream_kernel<C, MODE>;
+    RACE_TRY(allow_lds(kern, StreamLds<C>::total));
+    hipLaunchKernelGGL(kern, dim3(p.nseg, p.BH), dim3(kThreads), StreamLds<C>::total, st, a,
+                       static_cast<const bf16raw *>(Xr), static_cast<const bf16raw *>(Xw),
+                       static_cast<const bf16raw *>(Y), static_cast<const bf16raw *>(O), den_in,
+                       static_cast<bf16raw *>(Out), den_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_scan(const Plan &p, float *state, int elems, int mode, hipStream_t st)
+{
+    hipLaunchKernelGGL(scan_kernel, dim3((elems + 255) / 256, p.BH), dim3(256), 0, st, state, p.nseg, elems, mode);
+    return hipGetLastError();
+}
+
+template <class C>
+hipError_t fwd_t(const Plan &p, const void *Q, const void *K, const void *V, void *O, float *den, char *ws, hipStream_t st)
+{
+    KArgs a = make_kargs<C>(p, ws);
+    RACE_TRY((launch_stream<C, kTotalsKV>(p, a, K, K, V, nullptr, nullptr, nullptr, nullptr, st)));
+    RACE_TRY(launch_scan(p, a.state, C::STATE, p.causal ? 0 : 2, st));
+    RACE_TRY((launch_stream<C, kForward>(p, a, Q, K, V, nullptr, nullptr, O, den, st)));
+    return hipSuccess;
+}
+
+template <class C>
+hipError_t buckets_t(const Plan &p, const void *K, const void *V, float *A, float *Bsum, char *ws, hipStream_t st)
+{
+    KArgs a = make_kargs<C>(p, ws);
+    RACE_TRY((launch_stream<C, kTotalsKV>(p, a, K, K, V, nullptr, nullptr, nullptr, nullptr, st)));
+    const size_t total = static_cast<size_t>(p.BH) * C::STATE;
+    hipLaunchKernelGGL(bucket_tap_kernel<C>, dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0, st, a.state,
+                       p.nseg, p.BH, A, Bsum);
+    return hipGetLastError();
+}
+
+template <class C>
+hipError_t hash_t(const Plan &p, const void *X, uint8_t *codes, float *phi, char *ws, hipStream_t st)
+{
+    KArgs a = make_kargs<C>(p, ws);
+    const size_t lds = (static_cast<size_t>(C::LPP) * C::XS + kTile * C::XS + kTile * C::PS) * 2;
+    auto kern = hash_tap_kernel<C>;
+    RACE_TRY(allow_lds(kern, lds));
+    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>((p.N + kTile - 1) / kTile), p.BH), dim3(kThreads), lds, st, a,
+                       static_cast<const bf16raw *>(X), codes, phi);
+    return hipGetLastError();
+}
+
+uint16_t host_bf16(float x)
+{
+    uint32_t b;
+    std::memcpy(&b, &x, 4);
+    b += 0x7fffu + ((b >> 16) & 1u);
+    return static_cast<uint16_t>(b >> 16);
+}
+
+// W (H, L*P, D) -> Wp (H, LPP, D) and WpT (H, D, LPP) in projection-group order: row rho of group g
+// belongs to the lane half hh = (rho / 4) % 2; with a = rho / 8 and b = rho % 4 the half's slots (a, b)
+// hold, for 8-padded tables, table 2*hh + a/2 and hyperplane 4*(a%2) + b; for 4-padded tables, table
+// 4*hh + a and hyperplane b.  Rows of padding are zero.
+template <class C>
+void pack_t(const Plan &p, const float *W, void *image)
+{
+    uint16_t *wp = static_cast<uint16_t *>(image);
+    uint16_t *wpt = wp + static_cast<size_t>(p.H) * C::LPP * C::D;
+    for (int hd = 0; hd < p.H; ++hd) {
+        for (int row = 0; row < C::LPP; ++row) {
+            const int g = row / 32, rho = row % 32, a = rho / 8, hh = (rho / 4) % 2, b = rho % 4;
+            const int tl = (C::PP == 8) ? 2 * hh + a / 2 : 4 * hh + a;
+            const int t = (C::PP == 8) ? 4 * (a % 2) + b : b;
+            const int table = g * C::TPG + tl;
+            for (int c = 0; c < C::D; ++c) {
+                float v = 0.f;
+                if (table < C::L && t < C::P) v = W[(static_cast<size_t>(hd) * p.LP + table * C::P + t) * C::D + c];
+                const uint16_t bits = host_bf16(v);
+                wp[(static_cast<size_t>(hd) * C::LPP + row) * C::D + c] = bits;
+                wpt[(static_cast<size_t>(hd) * C::D + c) * C::LPP + row] = bits;
+            }
+        }
+    }
+}
+
+// Dispatch over the compiled shapes.
+#define RACE_SHAPES(X) X(128, 6, 8) X(64, 4, 16)
+
+}  // namespace
+
+bool mfma_supported(int d, int L, int P)
+{
+#define X(DD, PP_, LL) if (d == DD && P == PP_ && L == LL) return true;
+    RACE_SHAPES(X)
+#undef X
+    return false;
+}
+
+size_t mfma_projection_bytes(const Plan &p)
+{
+#define X(DD, PP_, LL) if (p.d == DD && p.P == PP_ && p.L == LL) return static_cast<size_t>(p.H) * Cfg<DD, PP_, LL>::LPP * DD * 2 * 2;
+    RACE_SHAPES(X)
+#undef X
+    return 0;
+}
+
+void mfma_pack_projection(const Plan &p, const float *W, void *image)
+{
+#define X(DD, PP_, LL) if (p.d == DD && p.P == PP_ && p.L == LL) return pack_t<Cfg<DD, PP_, LL>>(p, W, image);
+    RACE_SHAPES(X)
+#undef X
+}
+
+hipError_t mfma_fwd(const Plan &p, const void *Q, const void *K, const void *V, void *O, float *den, char *ws, hipStream_t st)
+{
+#define X(DD, PP_, LL) if (p.d == DD && p.P == PP_ && p.L == LL) return fwd_t<Cfg<DD, PP_, LL>>(p, Q, K, V, O, den, ws, st);
+    RACE_SHAPES(X)
+#undef X
+    return hipErrorNotSupported;
+}
+
+hipError_t mfma_bwd(const Plan &, const void *, const void *, const void *, const void *, const float *, const void *,
+                    void *, void *, void *, char *, hipStream_t)
+{
+    return hipErrorNotSupported;
+}
+
+hipError_t mfma_hash(const Plan &p, const void *X_, uint8_t *codes, float *phi, char *ws, hipStream_t st)
+{
+#define X(DD, PP_, LL) if (p.d == DD && p.P == PP_ && p.L == LL) return hash_t<Cfg<DD, PP_, LL>>(p, X_, codes, phi, ws, st);
+    RACE_SHAPES(X)
+#undef X
+    return hipErrorNotSupported;
+}
+
+hipError_t mfma_buckets(const Plan &p, const void *K, const void *V, float *A, float *Bsum, char *ws, hipStream_t st)
+{
+#define X(DD, PP_, LL) if (p.d == DD && p.P == PP_ && p.L == LL) return buckets_t<Cfg<DD, PP_, LL>>(p, K, V, A, Bsum, ws, st);
+    RACE_SHAPES(X)
+#undef X
+    return hipErrorNotSupported;
+}
+
+}  // namespace race
