@@ -58,6 +58,25 @@ struct Cfg {
     static_assert(2 * NG <= kWaves, "projection jobs must fit the wavefronts");
 };
 
+// Optional scheduling fence between MFMA groups (limits how far operand conversions are hoisted).
+// Off by default: with it, hipcc 7.2's MFMA register-rewrite pass crashes on one instantiation, and
+// without it the kernels spill only a few dozen dwords.
+#ifdef RACE_SCHED_FENCE_ON
+#define RACE_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+#else
+#define RACE_SCHED_FENCE() ((void)0)
+#endif
+
+// kernel arguments common to the family
+struct KArgs {
+    int H, nseg, causal;
+    int64_t N, seg_len;
+    float beta;
+    const bf16raw *Wp;     // (H, LPP, D) bf16, rows in projection-group order
+    const bf16raw *WpT;    // (H, D, LPP) bf16
+    float *state;          // (BH, nseg, STATE) fp32
+};
+
 // ---------------------------------------------------------------- small helpers
 __device__ __forceinline__ uint32_t pack2(float lo, float hi)
 {

@@ -16,18 +16,10 @@
 #include <cstring>
 
 #include "mfma_common.h"
+#include "mfma_grad.h"
 
 namespace race {
 namespace mfma {
-
-struct KArgs {
-    int H, nseg, causal;
-    int64_t N, seg_len;
-    float beta;
-    const bf16raw *Wp;     // (H, LPP, D) bf16, rows in projection-group order
-    const bf16raw *WpT;    // (H, D, LPP) bf16
-    float *state;          // (BH, nseg, STATE) fp32
-};
 
 enum Mode { kTotalsKV = 0, kTotalsQG = 1, kForward = 2, kGradV = 3 };
 
@@ -91,7 +83,7 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
     constexpr bool kTotals = (MODE == kTotalsKV || MODE == kTotalsQG);
     constexpr bool kReverse = (MODE == kGradV);
     constexpr bool kCotangentY = (MODE == kTotalsQG || MODE == kGradV);   // Y = dO / e (and ge for the mass column)
-    constexpr bool kMass = (MODE != kGradV);                               // the mass column A is carried
+    constexpr bool kMass = true;                                          // the mass column A is carried (unused by kGradV)
 
     const int seg = blockIdx.x, bh = blockIdx.y, head = bh % a.H;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, ln = lane & 31, h = lane >> 5;
@@ -188,7 +180,7 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
                         const u32x4 bw = lds64x2(phw + ln * C::PS + rr, phw + ln * C::PS + rr + 8);
                         sc = mma(ar, bw, sc);
                     }
-                    __builtin_amdgcn_sched_barrier(0);      // keep operand conversion from being hoisted wholesale
+                    RACE_SCHED_FENCE();      // keep operand conversion from being hoisted wholesale
                 }
             }
         }
@@ -215,7 +207,7 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
                     }
 #pragma unroll
                     for (int nt = 0; nt < C::NT; ++nt) Sacc[mt][nt] = mma(ap, by[nt], Sacc[mt][nt]);
-                    __builtin_amdgcn_sched_barrier(0);
+                    RACE_SCHED_FENCE();
                 }
             }
         }
@@ -460,6 +452,40 @@ hipError_t fwd_t(const Plan &p, const void *Q, const void *K, const void *V, voi
 }
 
 template <class C>
+hipError_t bwd_t(const Plan &p, const void *Q, const void *K, const void *V, const void *O, const float *den,
+                 const void *dO, void *dQ, void *dK, void *dV, char *ws, hipStream_t st)
+{
+    KArgs a = make_kargs<C>(p, ws);
+    KArgs b = a;
+    b.state = reinterpret_cast<float *>(ws + p.off_stateB);
+    // statistics of (phi_K, [V | 1]) at segment starts; of (phi_Q, read-out cotangents) at segment ends
+    RACE_TRY((launch_stream<C, kTotalsKV>(p, a, K, K, V, nullptr, nullptr, nullptr, nullptr, st)));
+    RACE_TRY(launch_scan(p, a.state, C::STATE, p.causal ? 0 : 2, st));
+    RACE_TRY((launch_stream<C, kTotalsQG>(p, b, Q, Q, dO, O, den, nullptr, nullptr, st)));
+    RACE_TRY(launch_scan(p, b.state, C::STATE, p.causal ? 1 : 2, st));
+    RACE_TRY((launch_stream<C, kGradV>(p, b, K, Q, dO, O, den, dV, nullptr, st)));
+    {
+        auto kern = grad_kernel<C, 0>;
+        RACE_TRY(allow_lds(kern, GradLds<C>::total));
+        hipLaunchKernelGGL(kern, dim3(p.nseg, p.BH), dim3(kThreads), GradLds<C>::total, st, a,
+                           static_cast<const bf16raw *>(Q), static_cast<const bf16raw *>(K),
+                           static_cast<const bf16raw *>(V), static_cast<const bf16raw *>(O), den,
+                           static_cast<const bf16raw *>(dO), static_cast<bf16raw *>(dQ));
+        RACE_TRY(hipGetLastError());
+    }
+    {
+        auto kern = grad_kernel<C, 1>;
+        RACE_TRY(allow_lds(kern, GradLds<C>::total));
+        hipLaunchKernelGGL(kern, dim3(p.nseg, p.BH), dim3(kThreads), GradLds<C>::total, st, b,
+                           static_cast<const bf16raw *>(Q), static_cast<const bf16raw *>(K),
+                           static_cast<const bf16raw *>(V), static_cast<const bf16raw *>(O), den,
+                           static_cast<const bf16raw *>(dO), static_cast<bf16raw *>(dK));
+        RACE_TRY(hipGetLastError());
+    }
+    return hipSuccess;
+}
+
+template <class C>
 hipError_t buckets_t(const Plan &p, const void *K, const void *V, float *A, float *Bsum, char *ws, hipStream_t st)
 {
     KArgs a = make_kargs<C>(p, ws);
@@ -552,9 +578,12 @@ hipError_t mfma_fwd(const Plan &p, const void *Q, const void *K, const void *V, 
     return hipErrorNotSupported;
 }
 
-hipError_t mfma_bwd(const Plan &, const void *, const void *, const void *, const void *, const float *, const void *,
-                    void *, void *, void *, char *, hipStream_t)
+hipError_t mfma_bwd(const Plan &p, const void *Q, const void *K, const void *V, const void *O, const float *den,
+                    const void *dO, void *dQ, void *dK, void *dV, char *ws, hipStream_t st)
 {
+#define X(DD, PP_, LL) if (p.d == DD && p.P == PP_ && p.L == LL) return bwd_t<Cfg<DD, PP_, LL>>(p, Q, K, V, O, den, dO, dQ, dK, dV, ws, st);
+    RACE_SHAPES(X)
+#undef X
     return hipErrorNotSupported;
 }
 
