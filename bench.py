@@ -1,0 +1,176 @@
+#!/usr/bin/env python3
+"""Benchmark: RACE Attention forward+backward tokens/s on one MI355X, with the dominant kernel's
+roofline fraction and the fp64 oracle timed on the host cores as a baseline.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C5|C4|C2|C3] [--tokens N]
+
+A step is one race_attn_fwd plus one race_attn_bwd over one batch of synthetic, seeded inputs that
+are resident in HBM before the timed region starts.  Prints ONE JSON line on stdout.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X published peaks
+PEAK_BF16_FLOPS = 2.5e15
+PEAK_HBM_BYTES = 8.0e12
+
+
+def algorithmic_counts(w):
+    """Per token-head work the method itself needs (no N x N work, no implementation extras):
+    Proj = 4 d L P (projections of Q and K), U = 2 L R (d+1) (one contraction with the bucket
+    statistics).  forward = Proj + 2U, backward = 2 Proj + 4U, bytes = 12 d s + 8."""
+    R = 1 << w.P
+    proj = 4 * w.d * w.L * w.P
+    U = 2 * w.L * R * (w.d + 1)
+    s = 2 if w.dtype == "bf16" else 4
+    return proj, U, 12 * w.d * s + 8
+
+
+def kernel_shares(w):
+    """Algorithmic flops per token-head credited to each kernel; they add up to 3 Proj + 6 U.
+    The segment-total and scan kernels exist only because the sequence is cut into segments and get 0."""
+    proj, U, _ = algorithmic_counts(w)
+    return {
+        "stream_forward": proj + 2 * U,      # projections, accumulate, read-out
+        "stream_grad_v": proj + 2 * U,       # projections again, cotangent statistics, dV read-out
+        "grad_q": proj / 2 + U,              # dphi_Q and W^T dz for Q
+        "grad_k": proj / 2 + U,              # dphi_K and W^T dz for K
+        "stream_totals_kv": 0.0, "stream_totals_qg": 0.0, "segment_scan": 0.0,
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="C5")
+    ap.add_argument("--tokens", type=int, default=0, help="override N of the workload")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=196608)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.stderr.write("bench.py: this build runs on one GPU; --gpus %d is not supported "
+                         "(the path has no collectives; see the sharding note in DESIGN.md)\n" % args.gpus)
+        return 2
+
+    import numpy as np
+    import torch
+    import paper_2510_04008_amd as ra
+    from paper_2510_04008_amd import synth
+
+    w = synth.WORKLOADS[args.workload]
+    if args.tokens:
+        w = w.scaled(args.tokens)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    desc = ra.make_desc(w.B, w.H, w.N, w.d, w.L, w.P, w.sharpening, w.causal,
+                        ra.RACE_F32 if w.dtype == "f32" else ra.RACE_BF16, w.chunk)
+    family = ra.race_attn_kernel_family(desc)
+    if family == 0:
+        raise SystemExit("unsupported workload")
+    seeds = synth.projection_seeds(w)
+
+    t_gen = time.perf_counter()
+    Q, K, V, dO = synth.make_inputs(w, dev, on_device_rng=True)
+    O = torch.empty_like(V)
+    den = torch.empty((w.B, w.H, w.N), dtype=torch.float32, device=dev)
+    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+    ws = torch.empty(ra.race_attn_workspace_bytes(desc), dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+    sys.stderr.write("inputs resident after %.1f s; workspace %.1f MiB; kernel family %d\n"
+                     % (time.perf_counter() - t_gen, ws.numel() / 2 ** 20, family))
+
+    def step():
+        ra.race_attn_fwd(desc, Q, K, V, seeds, O=O, den=den, workspace=ws)
+        ra.race_attn_bwd(desc, Q, K, V, O, den, dO, seeds, dQ=dQ, dK=dK, dV=dV, workspace=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ra.race_attn_profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = ra.race_attn_profile_read()
+    ra.race_attn_profile_enable(False)
+
+    ms_per_step = 1e3 * elapsed / args.steps
+    tokens_per_s = w.B * w.N * args.steps / elapsed
+    proj, U, bytes_th = algorithmic_counts(w)
+    token_heads = w.B * w.H * w.N
+    step_flops = (3 * proj + 6 * U) * token_heads
+    step_bytes = bytes_th * token_heads
+
+    roofline = None
+    kernels = {}
+    if prof:
+        shares = kernel_shares(w)
+        for name, (ms, n) in prof.items():
+            kernels[name] = {"avg_ms": ms / n, "launches_per_step": n / args.steps,
+                             "ms_per_step": ms / args.steps}
+        name = max(prof, key=lambda k: prof[k][0])
+        avg_s = 1e-3 * prof[name][0] / prof[name][1]
+        flops = shares.get(name, 0.0) * token_heads
+        achieved = flops / avg_s / 1e12
+        roofline = {"kernel": name, "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_FLOPS / 1e12,
+                    "unit": "TFLOP/s", "frac": achieved / (PEAK_BF16_FLOPS / 1e12), "traffic": None,
+                    "avg_launch_ms": 1e3 * avg_s, "algorithmic_flops_per_launch": flops}
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        from oracle import race_oracle as ro
+        from oracle import stream as oracle_stream
+        n0 = min(w.N, args.cpu_sample_tokens)
+        rounded = w.dtype == "bf16"
+        Wm = np.stack([ro.expand_projection(s, w.L, w.P, w.d, round_bf16=rounded) for s in seeds])
+        b_sample = 1                                   # one batch element is enough for a rate
+        host = [t[:b_sample, :, :n0].float().cpu().numpy().astype(np.float64) for t in (Q, K, V, dO)]
+        tc = time.perf_counter()
+        Oo, deno = oracle_stream.forward(host[0], host[1], host[2], Wm, w.sharpening, w.L, w.P, w.causal)
+        go = oracle_stream.backward(host[0], host[1], host[2], Wm, w.sharpening, w.L, w.P, w.causal, Oo, deno, host[3])
+        cpu_s = time.perf_counter() - tc
+        cpu_baseline = {"value": b_sample * n0 / cpu_s, "unit": "tokens/s", "cores": oracle_stream.threads(),
+                        "kind": "oracle",
+                        "sample": "first %d tokens of batch element 0 (all %d heads), fwd+bwd, fp64, %.1f s"
+                                  % (n0, w.H, cpu_s)}
+        if w.causal:
+            # causal: the first n0 outputs depend on the first n0 tokens only, so the sample doubles as a
+            # parity check of the benchmarked launch configuration (dK, dV of a prefix do not have this property)
+            def err(g, r):
+                g = g[:b_sample, :, :n0].float().cpu().numpy().astype(np.float64)
+                return float(np.abs(g - r).max() / np.abs(r).max())
+            sys.stderr.write("prefix parity vs oracle: O %.2e den %.2e dQ %.2e\n"
+                             % (err(O, Oo), err(den, deno), err(dQ, go[0])))
+
+    out = {
+        "metric": "RACE attn fwd+bwd tokens/sec at N=1M-12M (B=1,H=4,d=128); % MFMA/HBM roof",
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "H": w.H, "N": w.N, "d": w.d, "L": w.L, "P": w.P,
+                   "sharpening": w.sharpening, "causal": w.causal, "kernel_family": family},
+        "roofline": roofline,
+        "cpu_baseline": cpu_baseline,
+        "step_roofline": {"algorithmic_tflop": step_flops / 1e12, "algorithmic_gb": step_bytes / 1e9,
+                          "frac_of_mfma_roof": step_flops / (elapsed / args.steps) / PEAK_BF16_FLOPS,
+                          "frac_of_hbm_roof": step_bytes / (elapsed / args.steps) / PEAK_HBM_BYTES},
+        "kernels": kernels,
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

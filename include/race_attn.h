@@ -127,6 +127,15 @@ const char *race_attn_last_error(void);
  * kernels, 2 = bf16 MFMA kernels.  Informational (benchmarks and tests report it). */
 int race_attn_kernel_family(const race_attn_desc_t *desc);
 
+/* Benchmark aid (no passage of the paper; callers: benchmarks and profilers).  While enabled for the
+ * calling thread, every kernel the library launches is bracketed by a pair of HIP events recorded on the
+ * call's own stream.  race_attn_profile_read() waits for the recorded events, adds up the elapsed time per
+ * kernel name since the previous read, writes up to max_entries results (names are static strings, total_ms
+ * in milliseconds, launches = number of launches) and returns how many distinct kernels ran.  Enabling
+ * creates HIP events (host allocations); results are discarded by disabling. */
+void race_attn_profile_enable(int on);
+int race_attn_profile_read(int max_entries, const char **names, float *total_ms, int *launches);
+
 #ifdef __cplusplus
 }
 #endif

@@ -58,6 +58,11 @@ def lib() -> ctypes.CDLL:
         L.race_attn_debug_hash.restype = ctypes.c_int
         L.race_attn_debug_buckets.argtypes = [dp, vp, vp, u64p, fp, fp, vp, ctypes.c_size_t, vp]
         L.race_attn_debug_buckets.restype = ctypes.c_int
+        L.race_attn_profile_enable.argtypes = [ctypes.c_int]
+        L.race_attn_profile_enable.restype = None
+        L.race_attn_profile_read.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_char_p),
+                                             ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int)]
+        L.race_attn_profile_read.restype = ctypes.c_int
         L.race_status_string.argtypes = [ctypes.c_int]
         L.race_status_string.restype = ctypes.c_char_p
         L.race_attn_last_error.argtypes = []
@@ -192,3 +197,16 @@ def race_attn_debug_buckets(desc: RaceAttnDesc, K, V, proj_seeds: Sequence[int],
     if st != RACE_OK:
         raise RaceAttnError(st, "race_attn_debug_buckets")
     return A, Bsum
+
+
+def race_attn_profile_enable(on: bool) -> None:
+    lib().race_attn_profile_enable(int(bool(on)))
+
+
+def race_attn_profile_read(max_entries: int = 32):
+    """{kernel name: (total milliseconds, launches)} since the previous read."""
+    names = (ctypes.c_char_p * max_entries)()
+    ms = (ctypes.c_float * max_entries)()
+    cnt = (ctypes.c_int * max_entries)()
+    n = min(lib().race_attn_profile_read(max_entries, names, ms, cnt), max_entries)
+    return {names[i].decode(): (float(ms[i]), int(cnt[i])) for i in range(n)}

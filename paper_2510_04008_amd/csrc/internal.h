@@ -45,6 +45,14 @@ const void *projection_image(const Plan &plan, const uint64_t *seeds, size_t *by
 // Host: plain (H, L*P, d) expansion into caller memory.
 void expand_projection_host(int H, int L, int P, int d, int dtype, const uint64_t *seeds, float *out);
 
+// Brackets one kernel launch with HIP events on its stream while profiling is enabled (benchmark aid).
+struct ProfileScope {
+    ProfileScope(const char *name, hipStream_t st);
+    ~ProfileScope();
+    void *rec_;
+    hipStream_t st_;
+};
+
 // ---- simple family (simple_kernels.hip)
 hipError_t simple_fwd(const Plan &p, const void *Q, const void *K, const void *V, void *O, float *den,
                       char *ws, hipStream_t st);

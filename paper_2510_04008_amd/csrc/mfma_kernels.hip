@@ -426,8 +426,10 @@ template <class C, int MODE>
 hipError_t launch_stream(const Plan &p, KArgs a, const void *Xr, const void *Xw, const void *Y, const void *O,
                          const float *den_in, void *Out, float *den_out, hipStream_t st)
 {
+    static const char *const names[] = {"stream_totals_kv", "stream_totals_qg", "stream_forward", "stream_grad_v"};
     auto kern = stream_kernel<C, MODE>;
     RACE_TRY(allow_lds(kern, StreamLds<C>::total));
+    ProfileScope prof(names[MODE], st);
     hipLaunchKernelGGL(kern, dim3(p.nseg, p.BH), dim3(kThreads), StreamLds<C>::total, st, a,
                        static_cast<const bf16raw *>(Xr), static_cast<const bf16raw *>(Xw),
                        static_cast<const bf16raw *>(Y), static_cast<const bf16raw *>(O), den_in,
@@ -437,6 +439,7 @@ hipError_t launch_stream(const Plan &p, KArgs a, const void *Xr, const void *Xw,
 
 hipError_t launch_scan(const Plan &p, float *state, int elems, int mode, hipStream_t st)
 {
+    ProfileScope prof("segment_scan", st);
     hipLaunchKernelGGL(scan_kernel, dim3((elems + 255) / 256, p.BH), dim3(256), 0, st, state, p.nseg, elems, mode);
     return hipGetLastError();
 }
@@ -467,6 +470,7 @@ hipError_t bwd_t(const Plan &p, const void *Q, const void *K, const void *V, con
     {
         auto kern = grad_kernel<C, 0>;
         RACE_TRY(allow_lds(kern, GradLds<C>::total));
+        ProfileScope prof("grad_q", st);
         hipLaunchKernelGGL(kern, dim3(p.nseg, p.BH), dim3(kThreads), GradLds<C>::total, st, a,
                            static_cast<const bf16raw *>(Q), static_cast<const bf16raw *>(K),
                            static_cast<const bf16raw *>(V), static_cast<const bf16raw *>(O), den,
@@ -476,6 +480,7 @@ hipError_t bwd_t(const Plan &p, const void *Q, const void *K, const void *V, con
     {
         auto kern = grad_kernel<C, 1>;
         RACE_TRY(allow_lds(kern, GradLds<C>::total));
+        ProfileScope prof("grad_k", st);
         hipLaunchKernelGGL(kern, dim3(p.nseg, p.BH), dim3(kThreads), GradLds<C>::total, st, b,
                            static_cast<const bf16raw *>(Q), static_cast<const bf16raw *>(K),
                            static_cast<const bf16raw *>(V), static_cast<const bf16raw *>(O), den,

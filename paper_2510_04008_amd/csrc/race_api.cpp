@@ -128,6 +128,43 @@ const void *projection_image(const Plan &p, const uint64_t *seeds, size_t *bytes
     return it->second.pinned;
 }
 
+// ---------------------------------------------------------------- per-kernel timing (benchmark aid)
+namespace {
+struct ProfileRecord { const char *name; hipEvent_t start, stop; };
+thread_local bool g_profile_on = false;
+thread_local std::vector<ProfileRecord> g_profile_records;
+thread_local std::vector<hipEvent_t> g_profile_pool;
+
+hipEvent_t take_event()
+{
+    if (!g_profile_pool.empty()) {
+        hipEvent_t e = g_profile_pool.back();
+        g_profile_pool.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    (void)hipEventCreate(&e);
+    return e;
+}
+}  // namespace
+
+ProfileScope::ProfileScope(const char *name, hipStream_t st) : rec_(nullptr), st_(st)
+{
+    if (!g_profile_on) return;
+    ProfileRecord r{name, take_event(), take_event()};
+    if (!r.start || !r.stop) return;
+    (void)hipEventRecord(r.start, st);
+    g_profile_records.push_back(r);
+    rec_ = reinterpret_cast<void *>(g_profile_records.size());      // index + 1
+}
+
+ProfileScope::~ProfileScope()
+{
+    if (!rec_) return;
+    const size_t i = reinterpret_cast<size_t>(rec_) - 1;
+    if (i < g_profile_records.size()) (void)hipEventRecord(g_profile_records[i].stop, st_);
+}
+
 race_status_t make_plan(const race_attn_desc_t *desc, Plan *pl)
 {
     if (!desc) return RACE_ERR_INVALID_ARG;
@@ -344,5 +381,39 @@ const char *race_status_string(race_status_t status)
 }
 
 const char *race_attn_last_error(void) { return g_last_error.c_str(); }
+
+void race_attn_profile_enable(int on)
+{
+    g_profile_on = on != 0;
+    if (!on) {
+        for (auto &r : g_profile_records) { g_profile_pool.push_back(r.start); g_profile_pool.push_back(r.stop); }
+        g_profile_records.clear();
+    }
+}
+
+int race_attn_profile_read(int max_entries, const char **names, float *total_ms, int *launches)
+{
+    std::vector<const char *> seen;
+    std::vector<float> ms;
+    std::vector<int> cnt;
+    for (auto &r : g_profile_records) {
+        float t = 0.f;
+        if (hipEventSynchronize(r.stop) == hipSuccess) (void)hipEventElapsedTime(&t, r.start, r.stop);
+        size_t k = 0;
+        while (k < seen.size() && std::strcmp(seen[k], r.name) != 0) ++k;
+        if (k == seen.size()) { seen.push_back(r.name); ms.push_back(0.f); cnt.push_back(0); }
+        ms[k] += t;
+        cnt[k] += 1;
+        g_profile_pool.push_back(r.start);
+        g_profile_pool.push_back(r.stop);
+    }
+    g_profile_records.clear();
+    for (size_t k = 0; k < seen.size() && static_cast<int>(k) < max_entries; ++k) {
+        if (names) names[k] = seen[k];
+        if (total_ms) total_ms[k] = ms[k];
+        if (launches) launches[k] = cnt[k];
+    }
+    return static_cast<int>(seen.size());
+}
 
 }  // extern "C"
