@@ -1,0 +1,177 @@
+"""GPU parity of the bf16 MFMA kernel family against the fp64 oracle, through the C ABI.
+
+Small and medium cases are compared element by element.  The long-context configurations are run
+at full size in the launch configuration the benchmark times, and checked (a) on a prefix, which in
+the causal case depends on no later token, against the oracle, and (b) through properties that hold
+at any size.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2510_04008_amd as ra
+from oracle import race_oracle as ro
+from oracle import stream as oracle_stream
+from paper_2510_04008_amd import synth
+from paper_2510_04008_amd.synth import Workload
+
+from parity_util import TOL, check_case, desc_of, oracle_w, rel_err, run_gpu, to_f64
+
+pytestmark = pytest.mark.gpu
+
+
+def _is_mfma(w):
+    return ra.race_attn_kernel_family(desc_of(w)) == 2
+
+
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("N,chunk", [(1, 0), (31, 0), (32, 0), (33, 0), (1000, 256), (4100, 1024)])
+def test_headline_shape_small(N, chunk, causal):
+    w = Workload("mfma-N%d" % N, 1, 2, N, 128, 8, 6, 8.0, causal, "bf16", normalize_qk=True, chunk=chunk)
+    assert _is_mfma(w)
+    floors = None
+    if N == 1:
+        # One token attends only to itself: dQ = dK = 0 exactly, as the difference of two equal terms
+        # phi_K[r] (dO.V) / e.  bf16 operands cannot reproduce an exact zero, so the error is measured
+        # against the size of those terms pushed through the chain rule: beta |dO.V| / e ||W||_2.
+        Q, K, V, dO = synth.make_inputs(w, "cuda")
+        seeds = synth.projection_seeds(w)
+        W = oracle_w(w, seeds)
+        scale = 0.0
+        for h in range(w.H):
+            _, den = ro.forward_quadratic(to_f64(Q)[0, h], to_f64(K)[0, h], to_f64(V)[0, h], W[h], w.sharpening, w.L, w.P, causal)
+            gv = abs(float(to_f64(dO)[0, h, 0] @ to_f64(V)[0, h, 0]))
+            scale = max(scale, w.sharpening * gv / (w.L * den[0]) * np.linalg.norm(W[h], 2))
+        floors = {"dQ": scale, "dK": scale}
+    check_case(w, floors=floors)
+
+
+def test_headline_shape_batch_and_heads_saturated_inputs():
+    # raw N(0,1) rows: |z| ~ 11, tanh saturates; two batches share W, heads do not
+    w = Workload("mfma-bh", 2, 3, 777, 128, 8, 6, 8.0, True, "bf16", chunk=256)
+    assert _is_mfma(w)
+    check_case(w)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_encoder_shape_small(causal):
+    w = Workload("mfma-enc", 2, 2, 900, 64, 16, 4, 4.0, causal, "bf16", chunk=128 if causal else 0)
+    assert _is_mfma(w)
+    check_case(w)
+
+
+def test_config2_causal_64k_full():
+    assert _is_mfma(synth.C2)
+    check_case(synth.C2)
+
+
+def test_config3_noncausal_full():
+    assert _is_mfma(synth.C3)
+    check_case(synth.C3)
+
+
+def test_hash_tap_runs_the_production_projection_and_is_bit_exact():
+    w = Workload("mfma-hash", 1, 4, 2048 + 17, 128, 8, 6, 8.0, True, "bf16", normalize_qk=True)
+    Q, K, V, dO = synth.make_inputs(w, "cuda")
+    seeds = synth.projection_seeds(w)
+    codes, phi = ra.race_attn_debug_hash(desc_of(w), Q, seeds, want_phi=True)
+    torch.cuda.synchronize()
+    W = oracle_w(w, seeds)
+    Qh = to_f64(Q)
+    in_band = flips_in_band = out_of_band = 0
+    for h in range(w.H):
+        z = ro.project(Qh[0, h], W[h], w.L, w.P)
+        ref = ro.hard_codes(Qh[0, h], W[h], w.L, w.P)
+        got = codes[0, h].cpu().numpy().astype(np.int64)
+        # bf16 x bf16 products are exact in fp32; only the fp32 accumulation order can move a sign,
+        # and only where |z| is within the rounding band of the dot product
+        tau = 2.0 ** -16 * np.linalg.norm(Qh[0, h], axis=1)[:, None, None] * np.linalg.norm(W[h], axis=1).reshape(1, w.L, w.P)
+        band = (np.abs(z) <= tau).any(axis=2)
+        in_band += int(band.sum())
+        flips_in_band += int(((got != ref) & band).sum())
+        out_of_band += int(((got != ref) & ~band).sum())
+        ref_phi = ro.soft_hash(Qh[0, h], W[h], w.sharpening, w.L, w.P)
+        got_phi = phi[0, h].cpu().numpy().reshape(ref_phi.shape)
+        assert np.abs(got_phi - ref_phi).max() < 2.0 ** -8            # phi is held as bf16
+        # the hard code is an arg-max corner of phi (bf16 rounding may create ties, never a larger value)
+        at_code = np.take_along_axis(got_phi, got[:, :, None], axis=2)[:, :, 0]
+        assert np.array_equal(at_code, got_phi.max(axis=2))
+    print("hash tap: %d (token, table) pairs in the rounding band, %d flipped there, %d flipped outside"
+          % (in_band, flips_in_band, out_of_band), flush=True)
+    assert out_of_band == 0
+
+
+def test_bucket_tap():
+    w = Workload("mfma-buckets", 1, 2, 1500, 128, 8, 6, 8.0, True, "bf16", normalize_qk=True, chunk=512)
+    Q, K, V, dO = synth.make_inputs(w, "cuda")
+    seeds = synth.projection_seeds(w)
+    A, Bsum = ra.race_attn_debug_buckets(desc_of(w), K, V, seeds)
+    torch.cuda.synchronize()
+    W = oracle_w(w, seeds)
+    for h in range(w.H):
+        rA, rB = ro.bucket_statistics(to_f64(K)[0, h], to_f64(V)[0, h], W[h], w.sharpening, w.L, w.P)
+        assert rel_err(A[0, h], rA) < 5e-3 and rel_err(Bsum[0, h], rB) < 5e-3
+
+
+def test_determinism_and_invariants():
+    w = Workload("mfma-inv", 1, 2, 3000, 128, 8, 6, 8.0, True, "bf16", normalize_qk=True, chunk=512)
+    Q, K, V, dO = synth.make_inputs(w, "cuda")
+    g1 = run_gpu(w, (Q, K, V, dO))
+    g2 = run_gpu(w, (Q, K, V, dO))
+    for n in ("O", "den", "dQ", "dK", "dV"):
+        assert torch.equal(g1[n], g2[n]), n                                   # no atomics anywhere
+    ones = run_gpu(w, (Q, K, torch.ones_like(V), dO))
+    assert (ones["O"].float() - 1.0).abs().max().item() < 1e-2                # attention rows sum to one
+    tot = g1["dV"].float().sum(dim=2)
+    ref = dO.float().sum(dim=2)
+    assert (tot - ref).abs().max().item() < 2e-2 * ref.abs().max().item() + 0.5
+    V2 = V.clone()
+    V2[:, :, :1700] = 0
+    leak = run_gpu(w, (Q, K, V2, dO))
+    assert leak["O"][:, :, :1700].abs().max().item() == 0.0                   # nothing flows from the future
+
+
+def _long_context(w, n0):
+    """Full-size run in the benchmark's launch configuration; prefix parity and size-free properties."""
+    assert _is_mfma(w)
+    Q, K, V, dO = synth.make_inputs(w, "cuda", on_device_rng=True)
+    g = run_gpu(w, (Q, K, V, dO))
+    W = oracle_w(w, g["seeds"])
+    host = [to_f64(t[:, :, :n0]) for t in (Q, K, V, dO)]
+    O, den = oracle_stream.forward(host[0], host[1], host[2], W, w.sharpening, w.L, w.P, True)
+    dQ = oracle_stream.backward(host[0], host[1], host[2], W, w.sharpening, w.L, w.P, True, O, den, host[3])[0]
+    errs = dict(O=rel_err(g["O"][:, :, :n0], O), den=rel_err(g["den"][:, :, :n0], den), dQ=rel_err(g["dQ"][:, :, :n0], dQ))
+    print(w.name, "prefix %d:" % n0, " ".join("%s=%.2e" % kv for kv in errs.items()), flush=True)
+    for n, e in errs.items():
+        assert e < TOL["bf16"], (n, e)
+    # the same ratio per 1024-token block near the end of the prefix (late rows of O are small)
+    blk = slice(n0 - 1024, n0)
+    assert rel_err(g["O"][:, :, blk], O[:, :, blk]) < TOL["bf16"]
+    for n in ("O", "den", "dQ", "dK", "dV"):
+        assert torch.isfinite(g[n][:, :, ::4097].float()).all(), n
+    assert (g["den"][:, :, ::1000] > 0).all()
+    # rows of the attention matrix sum to one: total value gradient equals total upstream gradient
+    tot = torch.zeros((w.B, w.H, w.d), dtype=torch.float64, device="cuda")
+    ref = torch.zeros_like(tot)
+    step = 1 << 20
+    for s in range(0, w.N, step):
+        tot += g["dV"][:, :, s:s + step].double().sum(dim=2)
+        ref += dO[:, :, s:s + step].double().sum(dim=2)
+    scale = dO.float().abs().max().item() * (w.N ** 0.5)
+    assert (tot - ref).abs().max().item() < 2e-2 * scale
+    del g
+    # constant values come back as that constant at every position
+    V.fill_(1.0)
+    d = desc_of(w)
+    O1, _ = ra.race_attn_fwd(d, Q, K, V, synth.projection_seeds(w))
+    torch.cuda.synchronize()
+    for s in range(0, w.N, step):
+        assert (O1[:, :, s:s + step].float() - 1.0).abs().max().item() < 1e-2
+
+
+def test_config4_causal_4m_tokens_sampled():
+    _long_context(synth.C4, 16384)
+
+
+def test_config5_causal_12m_tokens_sampled():
+    _long_context(synth.C5, 16384)
