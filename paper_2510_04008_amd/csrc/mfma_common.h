@@ -50,7 +50,6 @@ struct Cfg {
     // LDS row strides, in bf16 elements (rows stay 16-byte aligned; the pad staggers banks)
     static constexpr int XS = D + 8;                    // [token][d] tiles and W rows
     static constexpr int PS = LR + 8;                   // [token][L*R] assignment tiles
-    static constexpr int TS = kTile + 8;                // [row][token] transposed tiles
     static constexpr int ZS = LPP + 8;                  // [token][padded projection] tiles
     static constexpr int STATE = LR * (D + 1);          // floats per saved state: B [LR][D] then A [LR]
     static_assert(LR % (32 * kWaves) == 0, "bucket rows must split into 32-row tiles per wavefront");
@@ -110,52 +109,93 @@ __device__ __forceinline__ float sum8(u32x4 v)
 // row of accumulator register v for lane half h
 __device__ __forceinline__ int acc_row(int v, int h) { return 8 * (v >> 2) + 4 * h + (v & 3); }
 
-// ---------------------------------------------------------------- global -> LDS tiles
-// rows [t0, t0+nvalid) of X (row-major, D contiguous) -> dst[32][XS]; missing rows are zero
-template <class C>
-__device__ __forceinline__ void load_tile(const bf16raw *X, int64_t t0, int nvalid, bf16raw *dst)
+// ---------------------------------------------------------------- transposing operand reads
+// MFMA operand whose k index runs along the ROWS of a row-major LDS tile M[k][n] (stride in elements):
+// lane (n, h) gets column n0 + n, rows k0a..k0a+3 then k0b..k0b+3.  Built from two ds_read_b64_tr_b16:
+// within a block of 16 lanes, lane i supplies the address of a 4-element row chunk and receives element
+// i%4 of the chunks of lanes i/4, i/4 + 4, i/4 + 8, i/4 + 12; with chunk (row i/4, columns 4(i%4)..) per
+// lane that is column i of four consecutive rows.
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef s16x4 __attribute__((address_space(3))) lds_s16x4;
+__device__ __forceinline__ u32x4 lds_tr8(const bf16raw *M, int stride, int k0a, int k0b, int n0, int ln)
 {
-    for (int c = threadIdx.x; c < kTile * C::CPR; c += kThreads) {
-        const int row = c / C::CPR, ch = c % C::CPR;
-        u32x4 v = {0, 0, 0, 0};
-        if (row < nvalid) v = *reinterpret_cast<const u32x4 *>(X + (t0 + row) * C::D + ch * 8);
-        *reinterpret_cast<u32x4 *>(dst + row * C::XS + ch * 8) = v;
-    }
+    const int sub = ln & 15;
+    const bf16raw *p = M + (sub >> 2) * stride + n0 + 16 * (ln >> 4) + 4 * (sub & 3);
+    const s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + k0a * stride));
+    const s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + k0b * stride));
+    const u32x2 ua = __builtin_bit_cast(u32x2, a), ub = __builtin_bit_cast(u32x2, b);
+    return u32x4{ua.x, ua.y, ub.x, ub.y};
+}
+// k-slots in plain order (rows k0 + 8h + 0..7) or in accumulator order (pairs with acc_operand)
+__device__ __forceinline__ u32x4 lds_tr_plain(const bf16raw *M, int stride, int k0, int n0, int ln, int h)
+{
+    return lds_tr8(M, stride, k0 + 8 * h, k0 + 8 * h + 4, n0, ln);
+}
+__device__ __forceinline__ u32x4 lds_tr_acc(const bf16raw *M, int stride, int k0, int n0, int ln, int h)
+{
+    return lds_tr8(M, stride, k0 + 4 * h, k0 + 8 + 4 * h, n0, ln);
 }
 
-// the same rows transposed: dstT[D][TS] (column-major tile, tokens contiguous)
+// ---------------------------------------------------------------- global -> registers -> LDS tiles
+// A 32-row tile is CPR*32 chunks of 16 bytes; thread t owns chunks t, t + 256, ...  Loads are issued one
+// tile ahead (fetch) and written to LDS at the start of the tile that uses them (store), so that HBM
+// latency overlaps the previous tile's arithmetic.
 template <class C>
-__device__ __forceinline__ void load_tile_transposed(const bf16raw *X, int64_t t0, int nvalid, bf16raw *dstT)
+struct RowChunks {
+    static constexpr int N = kTile * C::CPR / kThreads;
+    u32x4 v[N];
+};
+
+template <class C>
+__device__ __forceinline__ void fetch_rows(const bf16raw *X, int64_t t0, int nvalid, RowChunks<C> &r)
 {
-    for (int c = threadIdx.x; c < kTile * C::CPR; c += kThreads) {
-        const int row = c / C::CPR, ch = c % C::CPR;
-        u32x4 v = {0, 0, 0, 0};
-        if (row < nvalid) v = *reinterpret_cast<const u32x4 *>(X + (t0 + row) * C::D + ch * 8);
-        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            dstT[(ch * 8 + 2 * e) * C::TS + row] = static_cast<bf16raw>(w[e] & 0xffffu);
-            dstT[(ch * 8 + 2 * e + 1) * C::TS + row] = static_cast<bf16raw>(w[e] >> 16);
-        }
+    for (int k = 0; k < RowChunks<C>::N; ++k) {
+        const int c = threadIdx.x + k * kThreads, row = c / C::CPR, ch = c % C::CPR;
+        r.v[k] = u32x4{0, 0, 0, 0};
+        if (row < nvalid) r.v[k] = *reinterpret_cast<const u32x4 *>(X + (t0 + row) * C::D + ch * 8);
     }
 }
 
-// Read-out cotangent rows: gn = dO / e (e = L * Den) as bf16, natural (dst, may be null) and/or
-// transposed (dstT, may be null); ge[row] = -(dO . O) / e as fp32 (ge, may be null).
 template <class C>
-__device__ __forceinline__ void load_cotangent_tile(const bf16raw *dO, const bf16raw *O, const float *den, int64_t t0,
-                                                    int nvalid, bf16raw *dst, bf16raw *dstT, float *ge)
+__device__ __forceinline__ void store_rows(const RowChunks<C> &r, bf16raw *dst)
 {
-    for (int c = threadIdx.x; c < kTile * C::CPR; c += kThreads) {
-        const int row = c / C::CPR, ch = c % C::CPR;
-        u32x4 g = {0, 0, 0, 0}, o = {0, 0, 0, 0};
-        float inv = 0.f;
-        if (row < nvalid) {
-            g = *reinterpret_cast<const u32x4 *>(dO + (t0 + row) * C::D + ch * 8);
-            o = *reinterpret_cast<const u32x4 *>(O + (t0 + row) * C::D + ch * 8);
-            inv = 1.0f / (den[t0 + row] * static_cast<float>(C::L));
-        }
-        const uint32_t gw[4] = {g.x, g.y, g.z, g.w}, ow[4] = {o.x, o.y, o.z, o.w};
+#pragma unroll
+    for (int k = 0; k < RowChunks<C>::N; ++k) {
+        const int c = threadIdx.x + k * kThreads, row = c / C::CPR, ch = c % C::CPR;
+        *reinterpret_cast<u32x4 *>(dst + row * C::XS + ch * 8) = r.v[k];
+    }
+}
+
+// Read-out cotangent rows: gn = dO / e (e = L * Den) as bf16 rows, ge[row] = -(dO . O) / e as fp32.
+template <class C>
+struct CotChunks {
+    RowChunks<C> g, o;
+    float inv[RowChunks<C>::N];
+};
+
+template <class C>
+__device__ __forceinline__ void fetch_cotangent(const bf16raw *dO, const bf16raw *O, const float *den, int64_t t0,
+                                                int nvalid, CotChunks<C> &r)
+{
+    fetch_rows<C>(dO, t0, nvalid, r.g);
+    fetch_rows<C>(O, t0, nvalid, r.o);
+#pragma unroll
+    for (int k = 0; k < RowChunks<C>::N; ++k) {
+        const int row = (threadIdx.x + k * kThreads) / C::CPR;
+        r.inv[k] = (row < nvalid) ? den[t0 + row] : 0.f;
+    }
+}
+
+template <class C>
+__device__ __forceinline__ void store_cotangent(const CotChunks<C> &r, bf16raw *dst, float *ge)
+{
+#pragma unroll
+    for (int k = 0; k < RowChunks<C>::N; ++k) {
+        const int c = threadIdx.x + k * kThreads, row = c / C::CPR, ch = c % C::CPR;
+        const float inv = r.inv[k] > 0.f ? 1.0f / (r.inv[k] * static_cast<float>(C::L)) : 0.f;
+        const uint32_t gw[4] = {r.g.v[k].x, r.g.v[k].y, r.g.v[k].z, r.g.v[k].w};
+        const uint32_t ow[4] = {r.o.v[k].x, r.o.v[k].y, r.o.v[k].z, r.o.v[k].w};
         uint32_t out[4];
         float dot = 0.f;
 #pragma unroll
@@ -164,12 +204,8 @@ __device__ __forceinline__ void load_cotangent_tile(const bf16raw *dO, const bf1
             dot = fmaf(g0, bf_lo(ow[e]), dot);
             dot = fmaf(g1, bf_hi(ow[e]), dot);
             out[e] = pack2(g0 * inv, g1 * inv);
-            if (dstT) {
-                dstT[(ch * 8 + 2 * e) * C::TS + row] = static_cast<bf16raw>(out[e] & 0xffffu);
-                dstT[(ch * 8 + 2 * e + 1) * C::TS + row] = static_cast<bf16raw>(out[e] >> 16);
-            }
         }
-        if (dst) *reinterpret_cast<u32x4 *>(dst + row * C::XS + ch * 8) = u32x4{out[0], out[1], out[2], out[3]};
+        *reinterpret_cast<u32x4 *>(dst + row * C::XS + ch * 8) = u32x4{out[0], out[1], out[2], out[3]};
         if (ge) {
             // the CPR threads of one row are consecutive lanes
 #pragma unroll
@@ -247,16 +283,12 @@ __device__ __forceinline__ void kron_factors(const float *p, const float *q, flo
     }
 }
 
-// Writes the assignment of the lane's token for its TPL tables as bf16:
-//   ph  [token][L*R]   (may be null)        pht [L*R][token]   (may be null)
+// Writes the assignment of the lane's token for its TPL tables as bf16 into ph [token][L*R].
 // valid == false writes zeros (a token past the end of the sequence must not reach the statistics).
-// If mass != null, returns sum_r phi[r] * mass[table*R + r] over the lane's tables (the read-out of
-// the bucket masses A for this token), else 0.
 template <class C>
-__device__ __forceinline__ float write_assignments(const f32x16 &z, int g, int ln, int h, float beta, bool valid,
-                                                   bf16raw *ph, bf16raw *pht, const float *mass)
+__device__ __forceinline__ void write_assignments(const f32x16 &z, int g, int ln, int h, float beta, bool valid,
+                                                  bf16raw *ph)
 {
-    float dn = 0.f;
 #pragma unroll
     for (int j = 0; j < C::TPL; ++j) {
         const int table = g * C::TPG + h * C::TPL + j;
@@ -267,29 +299,12 @@ __device__ __forceinline__ float write_assignments(const f32x16 &z, int g, int l
 #pragma unroll
         for (int a = 0; a < (1 << C::PHI); ++a) {
             const float ha = valid ? hi[a] : 0.f;
-            float f[1 << C::PLO];
-#pragma unroll
-            for (int b = 0; b < (1 << C::PLO); ++b) f[b] = ha * lo[b];
             const int r0 = table * C::R + a * (1 << C::PLO);
-            if (mass) {
-                const float4 m0 = *reinterpret_cast<const float4 *>(mass + r0);
-                const float4 m1 = *reinterpret_cast<const float4 *>(mass + r0 + 4);
-                dn = fmaf(f[0], m0.x, dn); dn = fmaf(f[1], m0.y, dn); dn = fmaf(f[2], m0.z, dn); dn = fmaf(f[3], m0.w, dn);
-                dn = fmaf(f[4], m1.x, dn); dn = fmaf(f[5], m1.y, dn); dn = fmaf(f[6], m1.z, dn); dn = fmaf(f[7], m1.w, dn);
-            }
-            const u32x4 packed = {pack2(f[0], f[1]), pack2(f[2], f[3]), pack2(f[4], f[5]), pack2(f[6], f[7])};
-            if (ph) *reinterpret_cast<u32x4 *>(ph + ln * C::PS + r0) = packed;
-            if (pht) {
-                const uint32_t w[4] = {packed.x, packed.y, packed.z, packed.w};
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    pht[(r0 + 2 * e) * C::TS + ln] = static_cast<bf16raw>(w[e] & 0xffffu);
-                    pht[(r0 + 2 * e + 1) * C::TS + ln] = static_cast<bf16raw>(w[e] >> 16);
-                }
-            }
+            *reinterpret_cast<u32x4 *>(ph + ln * C::PS + r0) =
+                u32x4{pack2(ha * lo[0], ha * lo[1]), pack2(ha * lo[2], ha * lo[3]), pack2(ha * lo[4], ha * lo[5]),
+                      pack2(ha * lo[6], ha * lo[7])};
         }
     }
-    return dn;
 }
 
 }  // namespace mfma

@@ -17,6 +17,19 @@
 namespace race {
 namespace mfma {
 
+// Developer aid: per-phase cycle counts of one workgroup (build with -DRACE_PHASE_TIMING).
+#ifdef RACE_PHASE_TIMING
+#define GRAD_PHASE_DECL long long ph_t[13] = {0}; long long ph_last = clock64();
+#define GRAD_PHASE(i) { long long now_ = clock64(); ph_t[i] += now_ - ph_last; ph_last = now_; }
+#define GRAD_PHASE_PRINT() if (blockIdx.x == 1 && blockIdx.y == 0 && (threadIdx.x & 63) == 0) \
+    printf("grad side %d wave %d tiles %d: load %lld prod %lld tt %lld dP %lld upd %lld dphiw %lld smbwd %lld dX %lld | waits %lld %lld %lld %lld %lld\n", SIDE, (int)(threadIdx.x >> 6), ntiles, \
+           ph_t[0], ph_t[2], ph_t[4], ph_t[5], ph_t[6], ph_t[8], ph_t[10], ph_t[12], ph_t[1], ph_t[3], ph_t[7], ph_t[9], ph_t[11]);
+#else
+#define GRAD_PHASE_DECL
+#define GRAD_PHASE(i)
+#define GRAD_PHASE_PRINT()
+#endif
+
 template <class C>
 struct GradLds {
     static constexpr int wp = 0;                                        // [LPP][XS] bf16
@@ -30,9 +43,8 @@ struct GradLds {
     static constexpr int xw = xr + kTile * C::XS * 2;
     static constexpr int yr = xw + kTile * C::XS * 2;                   // reader-Y rows
     static constexpr int yw = yr + kTile * C::XS * 2;                   // writer-Y rows
-    static constexpr int ywt = yw + kTile * C::XS * 2;                  // [D][TS] writer-Y transposed
-    static constexpr int pht = ywt + C::D * C::TS * 2;                  // [LR][TS] writer assignments transposed
-    static constexpr int endA = pht + C::LR * C::TS * 2;
+    static constexpr int phw = yw + kTile * C::XS * 2;                  // [32][PS] writer assignments
+    static constexpr int endA = phw + kTile * C::PS * 2;
     // phase B
     static constexpr int DS = C::LR + 4;                                // fp32 row stride
     static constexpr int dphi = area;                                   // [32][DS] fp32
@@ -57,8 +69,7 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
     bf16raw *xw = reinterpret_cast<bf16raw *>(lds + S::xw);
     bf16raw *yr = reinterpret_cast<bf16raw *>(lds + S::yr);
     bf16raw *yw = reinterpret_cast<bf16raw *>(lds + S::yw);
-    bf16raw *ywt = reinterpret_cast<bf16raw *>(lds + S::ywt);
-    bf16raw *pht = reinterpret_cast<bf16raw *>(lds + S::pht);
+    bf16raw *phw = reinterpret_cast<bf16raw *>(lds + S::phw);
     float *dphi = reinterpret_cast<float *>(lds + S::dphi);
 
     constexpr bool kReverse = (SIDE == 1);
@@ -103,27 +114,47 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
     const int64_t t_end = (t_begin + a.seg_len < a.N) ? t_begin + a.seg_len : a.N;
     const int ntiles = static_cast<int>((t_end - t_begin + kTile - 1) / kTile);
 
-    for (int it = 0; it < ntiles; ++it) {
-        const int tile = kReverse ? ntiles - 1 - it : it;
-        const int64_t t0 = t_begin + static_cast<int64_t>(tile) * kTile;
-        const int nvalid = (t_end - t0 < kTile) ? static_cast<int>(t_end - t0) : kTile;
+    auto tile_t0 = [&](int it) { return t_begin + static_cast<int64_t>(kReverse ? ntiles - 1 - it : it) * kTile; };
+    auto tile_nv = [&](int64_t t0) { return (t_end - t0 < kTile) ? static_cast<int>(t_end - t0) : kTile; };
 
-        // ---- global -> LDS
-        load_tile<C>(Xr, t0, nvalid, xr);
-        if (intra) load_tile<C>(Xw, t0, nvalid, xw);
+    // loads run one tile ahead of the arithmetic
+    RowChunks<C> pre_r, pre_w, pre_v;
+    CotChunks<C> pre_c;
+    auto fetch = [&](int it) {
+        const int64_t t0 = tile_t0(it);
+        const int nv = tile_nv(t0);
+        fetch_rows<C>(Xr, t0, nv, pre_r);
+        if (intra) fetch_rows<C>(Xw, t0, nv, pre_w);
+        if (SIDE == 1 || intra) fetch_rows<C>(V, t0, nv, pre_v);
+        if (SIDE == 0 || intra) fetch_cotangent<C>(dO, O, den, t0, nv, pre_c);
+    };
+#ifdef RACE_GRAD_PREFETCH
+    if (ntiles > 0) fetch(0);
+#endif
+
+    GRAD_PHASE_DECL
+    for (int it = 0; it < ntiles; ++it) {
+        const int64_t t0 = tile_t0(it);
+        const int nvalid = tile_nv(t0);
+
+        // ---- registers -> LDS
+#ifndef RACE_GRAD_PREFETCH
+        fetch(it);
+#endif
+        store_rows<C>(pre_r, xr);
+        if (intra) store_rows<C>(pre_w, xw);
         if (SIDE == 0) {
-            load_cotangent_tile<C>(dO, O, den, t0, nvalid, yr, nullptr, sr);
-            if (intra) {
-                load_tile<C>(V, t0, nvalid, yw);
-                load_tile_transposed<C>(V, t0, nvalid, ywt);
-            }
+            store_cotangent<C>(pre_c, yr, sr);
+            if (intra) store_rows<C>(pre_v, yw);
             if (tid < kTile) sw[tid] = 1.f;
         } else {
-            load_tile<C>(V, t0, nvalid, yr);
-            if (intra) load_cotangent_tile<C>(dO, O, den, t0, nvalid, yw, ywt, sw);
+            store_rows<C>(pre_v, yr);
+            if (intra) store_cotangent<C>(pre_c, yw, sw);
             if (tid < kTile) sr[tid] = 1.f;
         }
+        GRAD_PHASE(0)
         __syncthreads();
+        GRAD_PHASE(1)
 
         // ---- production
         const int side = w / C::NG, g = w % C::NG;
@@ -132,9 +163,11 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
             z = project<C>(wp, xr, g, ln, h);
         } else if (side == 1 && intra) {
             const f32x16 zw = project<C>(wp, xw, g, ln, h);
-            write_assignments<C>(zw, g, ln, h, a.beta, ln < nvalid, nullptr, pht, nullptr);
+            write_assignments<C>(zw, g, ln, h, a.beta, ln < nvalid, phw);
         }
+        GRAD_PHASE(2)
         __syncthreads();
+        GRAD_PHASE(3)
 
         // ---- in-tile part: T^T[b][a] = Yw_b . Yr_a + sw_b * sr_a, masked
         f32x16 tt = {0};
@@ -153,6 +186,7 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
                 tt[v] = keep ? fmaf(sw[b], sra, tt[v]) : 0.f;
             }
         }
+        GRAD_PHASE(4)
         // ---- cotangent of the reader's assignments for this wavefront's bucket rows
         f32x16 dP[C::MT];
 #pragma unroll
@@ -173,10 +207,8 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
             for (int s = 0; s < 2; ++s) {
                 const u32x4 at = acc_operand(tt, s);
 #pragma unroll
-                for (int ntc = 0; ntc < C::MT; ++ntc) {
-                    const bf16raw *row = pht + (r_own + 32 * ntc + ln) * C::TS + 16 * s + 4 * h;
-                    dP[ntc] = mma(at, lds64x2(row, row + 8), dP[ntc]);
-                }
+                for (int ntc = 0; ntc < C::MT; ++ntc)
+                    dP[ntc] = mma(at, lds_tr_acc(phw, C::PS, 16 * s, r_own + 32 * ntc, ln, h), dP[ntc]);
             }
         }
         {
@@ -191,19 +223,20 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
                 for (int v = 0; v < 16; ++v) dP[ntc][v] = fmaf(srv[v], m, dP[ntc][v]);
             }
         }
+        GRAD_PHASE(5)
         // ---- statistics += Yw^T . phi_writer
         if (intra) {
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
                 u32x4 ya[C::NT];
 #pragma unroll
-                for (int mtc = 0; mtc < C::NT; ++mtc) ya[mtc] = lds128(ywt + (32 * mtc + ln) * C::TS + 16 * s + 8 * h);
+                for (int mtc = 0; mtc < C::NT; ++mtc) ya[mtc] = lds_tr_plain(yw, C::XS, 16 * s, 32 * mtc, ln, h);
                 float gw[8];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) gw[e] = sw[16 * s + 8 * h + e];
 #pragma unroll
                 for (int ntc = 0; ntc < C::MT; ++ntc) {
-                    const u32x4 bp = lds128(pht + (r_own + 32 * ntc + ln) * C::TS + 16 * s + 8 * h);
+                    const u32x4 bp = lds_tr_plain(phw, C::PS, 16 * s, r_own + 32 * ntc, ln, h);
                     macc[ntc] += bf_lo(bp.x) * gw[0] + bf_hi(bp.x) * gw[1] + bf_lo(bp.y) * gw[2] + bf_hi(bp.y) * gw[3] +
                                  bf_lo(bp.z) * gw[4] + bf_hi(bp.z) * gw[5] + bf_lo(bp.w) * gw[6] + bf_hi(bp.w) * gw[7];
 #pragma unroll
@@ -212,7 +245,9 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
                 }
             }
         }
+        GRAD_PHASE(6)
         __syncthreads();        // phase-A tiles are dead from here on
+        GRAD_PHASE(7)
 
         // ---- hand the cotangents to the lanes that own (token, table)
 #pragma unroll
@@ -220,7 +255,13 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
 #pragma unroll
             for (int v = 0; v < 16; ++v) dphi[acc_row(v, h) * S::DS + r_own + 32 * ntc + ln] = dP[ntc][v];
         }
+        // the next tile's loads fly during the vector-ALU phases below (few registers are live here)
+#ifdef RACE_GRAD_PREFETCH
+        if (it + 1 < ntiles) fetch(it + 1);
+#endif
+        GRAD_PHASE(8)
         __syncthreads();
+        GRAD_PHASE(9)
 
         // ---- back through the corner softmax and tanh (Algorithm 1, step 4):
         //      with w_r = phi_r dphi_r, m = sum_r w_r, E_t = sum_r v_{r,t} w_r:
@@ -272,7 +313,9 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
                     u32x2{pack2(dzv[4 * aa], dzv[4 * aa + 1]), pack2(dzv[4 * aa + 2], dzv[4 * aa + 3])};
             }
         }
+        GRAD_PHASE(10)
         __syncthreads();
+        GRAD_PHASE(11)
 
         // ---- dX = dZ . W
         for (int nt = w; nt < C::NT; nt += kWaves) {
@@ -289,8 +332,11 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
                 if (row < nvalid) dX[(t0 + row) * C::D + 32 * nt + ln] = static_cast<bf16raw>(pack2(acc[v], 0.f) & 0xffffu);
             }
         }
+        GRAD_PHASE(12)
         __syncthreads();
+        GRAD_PHASE(1)
     }
+    GRAD_PHASE_PRINT()
 }
 
 }  // namespace mfma

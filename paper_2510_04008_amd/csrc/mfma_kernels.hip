@@ -23,29 +23,37 @@ namespace mfma {
 
 enum Mode { kTotalsKV = 0, kTotalsQG = 1, kForward = 2, kGradV = 3 };
 
+// Developer aid: per-phase cycle counts of workgroup (0,0), printed at kernel end (build with -DRACE_PHASE_TIMING).
+#ifdef RACE_PHASE_TIMING
+#define RACE_PHASE_DECL long long ph_t[12] = {0}; long long ph_last = clock64();
+#define RACE_PHASE(i) { long long now_ = clock64(); ph_t[i] += now_ - ph_last; ph_last = now_; }
+#define RACE_PHASE_PRINT(tag) if (blockIdx.x == 1 && blockIdx.y == 0 && (threadIdx.x & 63) == 0) \
+    printf("%s mode %d wave %d tiles %d: load %lld prod %lld contr %lld upd %lld redw %lld epi %lld | waits %lld %lld %lld %lld %lld\n", tag, MODE, (int)(threadIdx.x >> 6), ntiles, \
+           ph_t[0], ph_t[2], ph_t[4], ph_t[5], ph_t[7], ph_t[9], ph_t[1], ph_t[3], ph_t[6], ph_t[8], ph_t[10]);
+#else
+#define RACE_PHASE_DECL
+#define RACE_PHASE(i)
+#define RACE_PHASE_PRINT(tag)
+#endif
+
 // ---------------------------------------------------------------- LDS map of stream_kernel (bytes)
 template <class C>
 struct StreamLds {
     static constexpr int wp = 0;                                        // [LPP][XS] bf16
-    static constexpr int yt = wp + C::LPP * C::XS * 2;                  // [D][TS] bf16: accumulated tensor, transposed
-    static constexpr int scb = yt + C::D * C::TS * 2;                   // [32][TS] bf16: masked in-tile kernel
-    static constexpr int mass = scb + kTile * C::TS * 2;                // [LR] fp32: bucket masses A before this tile
-    static constexpr int dnp = mass + C::LR * 4;                        // [NG][32] fp32: per-group mass read-outs
-    static constexpr int e = dnp + C::NG * kTile * 4;                   // [32] fp32: un-averaged normaliser
-    static constexpr int ge = e + kTile * 4;                            // [32] fp32: normaliser cotangents
+    static constexpr int y = wp + C::LPP * C::XS * 2;                   // [32][XS] bf16: accumulated tensor rows
+    static constexpr int mass = y + kTile * C::XS * 2;                  // [LR] fp32: bucket masses A before this tile
+    static constexpr int ge = mass + C::LR * 4;                         // [32] fp32: normaliser cotangents
     static constexpr int area = (ge + kTile * 4 + 255) & ~255;          // start of the aliased area
     // phase A (production, contraction)
     static constexpr int xr = area;                                     // [32][XS] reader rows
     static constexpr int xw = xr + kTile * C::XS * 2;                   // [32][XS] writer rows
     static constexpr int phr = xw + kTile * C::XS * 2;                  // [32][PS] reader assignments
     static constexpr int phw = phr + kTile * C::PS * 2;                 // [32][PS] writer assignments
-    static constexpr int pht = phw + kTile * C::PS * 2;                 // [LR][TS] writer assignments, transposed
-    static constexpr int endA = pht + C::LR * C::TS * 2;
+    static constexpr int endA = phw + kTile * C::PS * 2;
     // phase B (cross-wavefront reduction) reuses the same bytes
-    static constexpr int RS = C::D + 4;                                 // fp32 row stride of the partial read-outs
+    static constexpr int RS = C::D + 4;                                 // fp32 row stride: D numerators, 2 normaliser parts
     static constexpr int red = area;                                    // [4][32][RS] fp32
-    static constexpr int redsc = red + kWaves * kTile * RS * 4;         // [4][32][33] fp32
-    static constexpr int endB = redsc + kWaves * kTile * 33 * 4;
+    static constexpr int endB = red + kWaves * kTile * RS * 4;
     static constexpr int total = endA > endB ? endA : endB;
     static_assert(total <= 160 * 1024, "LDS budget");
 };
@@ -66,24 +74,18 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
     using S = StreamLds<C>;
     extern __shared__ __attribute__((aligned(256))) unsigned char lds[];
     bf16raw *wp = reinterpret_cast<bf16raw *>(lds + S::wp);
-    bf16raw *yt = reinterpret_cast<bf16raw *>(lds + S::yt);
-    bf16raw *scb = reinterpret_cast<bf16raw *>(lds + S::scb);
+    bf16raw *ytile = reinterpret_cast<bf16raw *>(lds + S::y);
     float *mass = reinterpret_cast<float *>(lds + S::mass);
-    float *dnp = reinterpret_cast<float *>(lds + S::dnp);
-    float *e_lds = reinterpret_cast<float *>(lds + S::e);
     float *ge_lds = reinterpret_cast<float *>(lds + S::ge);
     bf16raw *xr = reinterpret_cast<bf16raw *>(lds + S::xr);
     bf16raw *xw = reinterpret_cast<bf16raw *>(lds + S::xw);
     bf16raw *phr = reinterpret_cast<bf16raw *>(lds + S::phr);
     bf16raw *phw = reinterpret_cast<bf16raw *>(lds + S::phw);
-    bf16raw *pht = reinterpret_cast<bf16raw *>(lds + S::pht);
     float *red = reinterpret_cast<float *>(lds + S::red);
-    float *redsc = reinterpret_cast<float *>(lds + S::redsc);
 
     constexpr bool kTotals = (MODE == kTotalsKV || MODE == kTotalsQG);
     constexpr bool kReverse = (MODE == kGradV);
     constexpr bool kCotangentY = (MODE == kTotalsQG || MODE == kGradV);   // Y = dO / e (and ge for the mass column)
-    constexpr bool kMass = true;                                          // the mass column A is carried (unused by kGradV)
 
     const int seg = blockIdx.x, bh = blockIdx.y, head = bh % a.H;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, ln = lane & 31, h = lane >> 5;
@@ -119,7 +121,7 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
             for (int v = 0; v < 16; ++v)
                 Sacc[mt][nt][v] = kTotals ? 0.f : st[state_b<C>(r_own + 32 * mt + acc_row(v, h), 32 * nt + ln)];
         }
-        if (!kTotals && kMass && h == 0) macc[mt] = st[state_a<C>(r_own + 32 * mt + ln)];
+        if (!kTotals && h == 0) macc[mt] = st[state_a<C>(r_own + 32 * mt + ln)];
     }
     if (MODE == kForward) {
 #pragma unroll
@@ -131,41 +133,63 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
     const int64_t t_end = (t_begin + a.seg_len < a.N) ? t_begin + a.seg_len : a.N;
     const int ntiles = static_cast<int>((t_end - t_begin + kTile - 1) / kTile);
 
-    for (int it = 0; it < ntiles; ++it) {
-        const int tile = kReverse ? ntiles - 1 - it : it;
-        const int64_t t0 = t_begin + static_cast<int64_t>(tile) * kTile;
-        const int nvalid = (t_end - t0 < kTile) ? static_cast<int>(t_end - t0) : kTile;
+    // tile index -> first token and number of valid rows
+    auto tile_t0 = [&](int it) { return t_begin + static_cast<int64_t>(kReverse ? ntiles - 1 - it : it) * kTile; };
+    auto tile_nv = [&](int64_t t0) { return (t_end - t0 < kTile) ? static_cast<int>(t_end - t0) : kTile; };
 
-        // ---- global -> LDS
-        if (!kTotals) load_tile<C>(Xr, t0, nvalid, xr);
+    // loads run one tile ahead of the arithmetic
+    RowChunks<C> pre_r, pre_w, pre_y;
+    CotChunks<C> pre_c;
+    auto fetch = [&](int it) {
+        const int64_t t0 = tile_t0(it);
+        const int nv = tile_nv(t0);
+        if (!kTotals) fetch_rows<C>(Xr, t0, nv, pre_r);
         if (intra) {
-            load_tile<C>(Xw, t0, nvalid, xw);
-            if (kCotangentY) load_cotangent_tile<C>(Y, Oin, den_in, t0, nvalid, nullptr, yt, MODE == kTotalsQG ? ge_lds : nullptr);
-            else load_tile_transposed<C>(Y, t0, nvalid, yt);
+            fetch_rows<C>(Xw, t0, nv, pre_w);
+            if (kCotangentY) fetch_cotangent<C>(Y, Oin, den_in, t0, nv, pre_c);
+            else fetch_rows<C>(Y, t0, nv, pre_y);
         }
+    };
+    if (ntiles > 0) fetch(0);
+
+    RACE_PHASE_DECL
+    for (int it = 0; it < ntiles; ++it) {
+        const int64_t t0 = tile_t0(it);
+        const int nvalid = tile_nv(t0);
+
+        // ---- registers -> LDS, then start the next tile's loads
+        if (!kTotals) store_rows<C>(pre_r, xr);
+        if (intra) {
+            store_rows<C>(pre_w, xw);
+            if (kCotangentY) store_cotangent<C>(pre_c, ytile, MODE == kTotalsQG ? ge_lds : nullptr);
+            else store_rows<C>(pre_y, ytile);
+        }
+        if (it + 1 < ntiles) fetch(it + 1);
+        RACE_PHASE(0)
         __syncthreads();
+        RACE_PHASE(1)
 
         // ---- production: wavefront = (side, projection group)
         {
             const int side = w / C::NG, g = w % C::NG;          // side 0: reader, 1: writer
             if (side == 0 && !kTotals) {
                 const f32x16 z = project<C>(wp, xr, g, ln, h);
-                float dn = write_assignments<C>(z, g, ln, h, a.beta, true, phr, nullptr, MODE == kForward ? mass : nullptr);
-                if (MODE == kForward) {
-                    dn += __shfl_xor(dn, 32, 64);
-                    if (h == 0) dnp[g * kTile + ln] = dn;
-                }
+                write_assignments<C>(z, g, ln, h, a.beta, true, phr);
             } else if (side == 1 && intra) {
                 const f32x16 z = project<C>(wp, xw, g, ln, h);
-                write_assignments<C>(z, g, ln, h, a.beta, ln < nvalid, kTotals ? nullptr : phw, pht, nullptr);
+                write_assignments<C>(z, g, ln, h, a.beta, ln < nvalid, phw);
             }
         }
+        RACE_PHASE(2)
         __syncthreads();
+        RACE_PHASE(3)
 
         // ---- contraction with the register-resident statistics
         f32x16 out[C::NT];
-        f32x16 sc = {0};
+        f32x16 dn = {0};        // read-out of the bucket masses (every column holds the same value)
+        float rowsum = 0.f;     // in-tile part of the normaliser, reader token = ln
         if (!kTotals) {
+            f32x16 sct = {0};   // in-tile kernel values, transposed: row = writer token, lane = reader token
 #pragma unroll
             for (int nt = 0; nt < C::NT; ++nt) out[nt] = f32x16{0};
 #pragma unroll
@@ -176,21 +200,45 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
                     const u32x4 ar = lds64x2(phr + ln * C::PS + rr, phr + ln * C::PS + rr + 8);
 #pragma unroll
                     for (int nt = 0; nt < C::NT; ++nt) out[nt] = mma(ar, acc_operand(Sacc[mt][nt], s), out[nt]);
-                    if (intra) {
-                        const u32x4 bw = lds64x2(phw + ln * C::PS + rr, phw + ln * C::PS + rr + 8);
-                        sc = mma(ar, bw, sc);
+                    if (MODE == kForward) {
+                        const float4 m0 = *reinterpret_cast<const float4 *>(mass + rr);
+                        const float4 m1 = *reinterpret_cast<const float4 *>(mass + rr + 8);
+                        dn = mma(ar, u32x4{pack2(m0.x, m0.y), pack2(m0.z, m0.w), pack2(m1.x, m1.y), pack2(m1.z, m1.w)}, dn);
                     }
-                    RACE_SCHED_FENCE();      // keep operand conversion from being hoisted wholesale
+                    if (intra) {
+                        const u32x4 aw = lds64x2(phw + ln * C::PS + rr, phw + ln * C::PS + rr + 8);
+                        sct = mma(aw, ar, sct);
+                    }
+                    RACE_SCHED_FENCE();
+                }
+            }
+            if (intra) {
+                // mask (writer token j = row, reader token i = lane), row sums, and (mask o kernel) . Y
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int j = acc_row(v, h);
+                    const bool keep = kReverse ? (j >= ln) : (j <= ln);
+                    sct[v] = keep ? sct[v] : 0.f;
+                    rowsum += sct[v];
+                }
+                rowsum += __shfl_xor(rowsum, 32, 64);
+#pragma unroll
+                for (int s = 0; s < 2; ++s) {
+                    const u32x4 ak = acc_operand(sct, s);
+#pragma unroll
+                    for (int nt = 0; nt < C::NT; ++nt)
+                        out[nt] = mma(ak, lds_tr_acc(ytile, C::XS, 16 * s, 32 * nt, ln, h), out[nt]);
                 }
             }
         }
+        RACE_PHASE(4)
         // ---- statistics += phi_writer^T . Y  (after the read-out above used the old statistics)
         if (intra) {
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
                 u32x4 by[C::NT];
 #pragma unroll
-                for (int nt = 0; nt < C::NT; ++nt) by[nt] = lds128(yt + (32 * nt + ln) * C::TS + 16 * s + 8 * h);
+                for (int nt = 0; nt < C::NT; ++nt) by[nt] = lds_tr_plain(ytile, C::XS, 16 * s, 32 * nt, ln, h);
                 float gw[8];
                 if (MODE == kTotalsQG) {
 #pragma unroll
@@ -198,11 +246,11 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
                 }
 #pragma unroll
                 for (int mt = 0; mt < C::MT; ++mt) {
-                    const u32x4 ap = lds128(pht + (r_own + 32 * mt + ln) * C::TS + 16 * s + 8 * h);
+                    const u32x4 ap = lds_tr_plain(phw, C::PS, 16 * s, r_own + 32 * mt, ln, h);
                     if (MODE == kTotalsQG) {
                         macc[mt] += bf_lo(ap.x) * gw[0] + bf_hi(ap.x) * gw[1] + bf_lo(ap.y) * gw[2] + bf_hi(ap.y) * gw[3] +
                                     bf_lo(ap.z) * gw[4] + bf_hi(ap.z) * gw[5] + bf_lo(ap.w) * gw[6] + bf_hi(ap.w) * gw[7];
-                    } else if (kMass) {
+                    } else if (MODE != kGradV) {
                         macc[mt] += sum8(ap);
                     }
 #pragma unroll
@@ -211,11 +259,10 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
                 }
             }
         }
-        if (kTotals) {
-            __syncthreads();
-            continue;
-        }
-        __syncthreads();        // every wavefront is done with the assignment tiles
+        RACE_PHASE(5)
+        __syncthreads();        // every wavefront is done with the tiles of this step
+        RACE_PHASE(6)
+        if (kTotals) continue;
 
         // ---- cross-wavefront reduction of the partial read-outs (each wavefront covered LR/4 bucket rows)
 #pragma unroll
@@ -224,11 +271,12 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
             for (int v = 0; v < 16; ++v)
                 red[(w * kTile + acc_row(v, h)) * S::RS + 32 * nt + ln] = out[nt][v];
         }
-        if (intra) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) redsc[(w * kTile + acc_row(v, h)) * 33 + ln] = sc[v];
-        }
         if (MODE == kForward) {
+            if (ln == 0) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) red[(w * kTile + acc_row(v, h)) * S::RS + C::D] = dn[v];
+            }
+            if (h == 0) red[(w * kTile + ln) * S::RS + C::D + 1] = rowsum;
             // masses after this tile, for the next tile's read-out
 #pragma unroll
             for (int mt = 0; mt < C::MT; ++mt) {
@@ -236,69 +284,44 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
                 if (h == 0) mass[r_own + 32 * mt + ln] = tot;
             }
         }
+        RACE_PHASE(7)
         __syncthreads();
+        RACE_PHASE(8)
+        // ---- epilogue: thread = (token, D/8 consecutive columns): sum the partials, normalise, store rows
         {
-            // in-tile kernel values: sum the partials, mask, row sums, bf16 copy as an MFMA operand
-            const int i = tid >> 3, j0 = (tid & 7) * 4;
-            float k4[4] = {0.f, 0.f, 0.f, 0.f};
-            float rowsum = 0.f;
-            if (intra) {
+            constexpr int CW = C::D / 8;                 // columns per thread
+            const int tok = tid >> 3, c0 = (tid & 7) * CW;
+            float acc[CW];
 #pragma unroll
-                for (int jj = 0; jj < 4; ++jj) {
-                    const int j = j0 + jj;
-                    float v = 0.f;
+            for (int c = 0; c < CW; ++c) acc[c] = 0.f;
+            float e = 0.f;
 #pragma unroll
-                    for (int ww = 0; ww < kWaves; ++ww) v += redsc[(ww * kTile + i) * 33 + j];
-                    const bool keep = kReverse ? (j >= i) : (j <= i);
-                    k4[jj] = keep ? v : 0.f;
-                    rowsum += k4[jj];
+            for (int ww = 0; ww < kWaves; ++ww) {
+                const float *src = red + (ww * kTile + tok) * S::RS;
+#pragma unroll
+                for (int c = 0; c < CW; c += 4) {
+                    const float4 p4 = *reinterpret_cast<const float4 *>(src + c0 + c);
+                    acc[c] += p4.x; acc[c + 1] += p4.y; acc[c + 2] += p4.z; acc[c + 3] += p4.w;
                 }
+                if (MODE == kForward) e += src[C::D] + src[C::D + 1];
             }
-            *reinterpret_cast<u32x2 *>(scb + i * C::TS + j0) = u32x2{pack2(k4[0], k4[1]), pack2(k4[2], k4[3])};
-            if (MODE == kForward) {
-                rowsum += __shfl_xor(rowsum, 1, 64);
-                rowsum += __shfl_xor(rowsum, 2, 64);
-                rowsum += __shfl_xor(rowsum, 4, 64);
-                if ((tid & 7) == 0) {
-                    float e = rowsum;
+            if (tok < nvalid) {
+                const float scale = (MODE == kForward) ? 1.0f / e : 1.0f;
+                uint32_t packed[CW / 2];
 #pragma unroll
-                    for (int g = 0; g < C::NG; ++g) e += dnp[g * kTile + i];
-                    e_lds[i] = e;
-                    if (i < nvalid) den_out[t0 + i] = e * (1.0f / C::L);
-                }
+                for (int c = 0; c < CW; c += 2) packed[c / 2] = pack2(acc[c] * scale, acc[c + 1] * scale);
+#pragma unroll
+                for (int c = 0; c < CW / 2; c += 4)
+                    *reinterpret_cast<u32x4 *>(Out + (t0 + tok) * C::D + c0 + 2 * c) =
+                        u32x4{packed[c], packed[c + 1], packed[c + 2], packed[c + 3]};
+                if (MODE == kForward && (tid & 7) == 0) den_out[t0 + tok] = e * (1.0f / C::L);
             }
         }
+        RACE_PHASE(9)
         __syncthreads();
-        // ---- epilogue: sum the partial read-outs, add the in-tile part (kernel . Y), normalise, store
-        for (int nt = w; nt < C::NT; nt += kWaves) {
-            f32x16 acc;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = acc_row(v, h);
-                float s0 = 0.f;
-#pragma unroll
-                for (int ww = 0; ww < kWaves; ++ww) s0 += red[(ww * kTile + row) * S::RS + 32 * nt + ln];
-                acc[v] = s0;
-            }
-            if (intra) {
-#pragma unroll
-                for (int s = 0; s < 2; ++s) {
-                    const u32x4 ak = lds128(scb + ln * C::TS + 16 * s + 8 * h);
-                    const u32x4 by = lds128(yt + (32 * nt + ln) * C::TS + 16 * s + 8 * h);
-                    acc = mma(ak, by, acc);
-                }
-            }
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = acc_row(v, h);
-                if (row < nvalid) {
-                    const float val = (MODE == kForward) ? acc[v] / e_lds[row] : acc[v];
-                    Out[(t0 + row) * C::D + 32 * nt + ln] = static_cast<bf16raw>(pack2(val, 0.f) & 0xffffu);
-                }
-            }
-        }
-        __syncthreads();
+        RACE_PHASE(10)
     }
+    RACE_PHASE_PRINT("stream")
 
     if (kTotals) {
 #pragma unroll
@@ -364,12 +387,16 @@ __global__ __launch_bounds__(kThreads) void hash_tap_kernel(KArgs a, const bf16r
         const int row = c / C::CPR, ch = c % C::CPR;
         *reinterpret_cast<u32x4 *>(wp + row * C::XS + ch * 8) = *reinterpret_cast<const u32x4 *>(src + row * C::D + ch * 8);
     }
-    load_tile<C>(X + static_cast<size_t>(bh) * a.N * C::D, t0, nvalid, x);
+    {
+        RowChunks<C> rows;
+        fetch_rows<C>(X + static_cast<size_t>(bh) * a.N * C::D, t0, nvalid, rows);
+        store_rows<C>(rows, x);
+    }
     __syncthreads();
     if (w < C::NG) {
         const int g = w;
         const f32x16 z = project<C>(wp, x, g, ln, h);
-        write_assignments<C>(z, g, ln, h, a.beta, true, ph, nullptr, nullptr);
+        write_assignments<C>(z, g, ln, h, a.beta, true, ph);
         if (ln < nvalid) {
 #pragma unroll
             for (int j = 0; j < C::TPL; ++j) {
