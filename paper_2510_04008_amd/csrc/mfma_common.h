@@ -102,6 +102,12 @@ __device__ __forceinline__ u32x4 acc_operand(const f32x16 &t, int s)
     return s == 0 ? u32x4{pack2(t[0], t[1]), pack2(t[2], t[3]), pack2(t[4], t[5]), pack2(t[6], t[7])}
                   : u32x4{pack2(t[8], t[9]), pack2(t[10], t[11]), pack2(t[12], t[13]), pack2(t[14], t[15])};
 }
+// fp32 value as a bf16 pair (hi, lo) with hi + lo = x to 16 mantissa bits
+__device__ __forceinline__ void split_bf16(float x, float &hi, float &lo)
+{
+    hi = bf_lo(pack2(x, 0.f));
+    lo = x - hi;
+}
 __device__ __forceinline__ float sum8(u32x4 v)
 {
     return ((bf_lo(v.x) + bf_hi(v.x)) + (bf_lo(v.y) + bf_hi(v.y))) + ((bf_lo(v.z) + bf_hi(v.z)) + (bf_lo(v.w) + bf_hi(v.w)));
@@ -285,14 +291,16 @@ __device__ __forceinline__ void kron_factors(const float *p, const float *q, flo
 
 // Writes the assignment of the lane's token for its TPL tables as bf16 into ph [token][L*R].
 // valid == false writes zeros (a token past the end of the sequence must not reach the statistics).
+// Only the lane's tables j = j0, j0 + jstep, ... are written (lets several wavefronts share a group).
 template <class C>
 __device__ __forceinline__ void write_assignments(const f32x16 &z, int g, int ln, int h, float beta, bool valid,
-                                                  bf16raw *ph)
+                                                  bf16raw *ph, int j0 = 0, int jstep = 1)
 {
 #pragma unroll
     for (int j = 0; j < C::TPL; ++j) {
         const int table = g * C::TPG + h * C::TPL + j;
         if (table >= C::L) break;
+        if (j < j0 || (j - j0) % jstep != 0) continue;
         float p[C::P], q[C::P], lo[1 << C::PLO], hi[1 << C::PHI];
         bit_masses<C>(z, j, beta, p, q, nullptr);
         kron_factors<C>(p, q, lo, hi);
