@@ -17,9 +17,6 @@ FLAGS = [
     "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
     # keep the compiler from forming packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    # let MFMA results live in either register bank: the bucket statistics fill the accumulator
-    # bank, the per-tile partial products must go to the vector bank
-    "-mllvm", "-amdgpu-mfma-vgpr-form",
     "-Wall", "-Wno-unused-function", "-Wno-unknown-attributes",
 ]
 

@@ -62,8 +62,10 @@ hipError_t simple_hash(const Plan &p, const void *X, uint8_t *codes, float *phi,
 hipError_t simple_buckets(const Plan &p, const void *K, const void *V, float *A, float *Bsum, char *ws,
                           hipStream_t st);
 
-// ---- MFMA family (mfma_kernels.hip)
+// ---- MFMA family (mfma_kernels.hip, mfma_grad.hip).  Compiled shapes: X(d, P, L)
+#define RACE_MFMA_SHAPES(X) X(128, 6, 8) X(64, 4, 16)
 bool mfma_supported(int d, int L, int P);
+size_t mfma_scratch_bytes(const Plan &p);      // backward-pass scratch beyond the two state areas
 size_t mfma_projection_bytes(const Plan &p);
 void mfma_pack_projection(const Plan &p, const float *W, void *image);   // host
 hipError_t mfma_fwd(const Plan &p, const void *Q, const void *K, const void *V, void *O, float *den,

@@ -1,10 +1,12 @@
 // Building blocks of the bf16 MFMA kernel family (gfx950): compile-time shapes, LDS tile layouts,
 // operand loads, the projection + soft-assignment "production" step.
 //
-// Execution shape.  One workgroup of four wavefronts owns one (batch*head, segment) and walks its
-// tokens in tiles of 32.  The bucket statistics of all L tables, [L*R][d] fp32 (B of Algorithm 1,
-// step 5; A is kept beside it), never leave the register file: wavefront w holds rows
-// [w*LR/4, (w+1)*LR/4) as 32x32 MFMA accumulator tiles.  Per tile the workgroup
+// Execution shape.  One workgroup of eight wavefronts (two per SIMD, 256 registers each) owns one
+// (batch*head, segment) and walks its tokens in tiles of 32.  The bucket statistics of all L tables,
+// [L*R][d] fp32 (B of Algorithm 1, step 5; A is kept beside it), never leave the register file: every
+// wavefront holds an eighth of them as 32x32 MFMA accumulator tiles (stream kernels: a quarter of the
+// bucket rows x half of the columns; grad kernel: an eighth of the bucket rows x all columns, transposed).
+// Per tile the workgroup
 //   1. projects the 32 query and key rows on all L*P hyperplanes (MFMA) and turns the projections
 //      into soft assignments phi (vector ALU), written as bf16 tiles to LDS;
 //   2. contracts them with the register-resident statistics and with each other (MFMA).
@@ -29,8 +31,9 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 typedef uint16_t bf16raw;
 
-constexpr int kWaves = 4;
+constexpr int kWaves = 8;
 constexpr int kThreads = 64 * kWaves;
+constexpr int kRowGroups = 4;  // stream kernels: wavefront w owns bucket-row group w % 4 and column group w / 4
 constexpr int kTile = 32;      // tokens per tile
 
 template <int D_, int P_, int L_>
@@ -42,9 +45,13 @@ struct Cfg {
     static constexpr int TPL = TPG / 2;                 // tables per lane (per half-wave)
     static constexpr int NG = (L + TPG - 1) / TPG;      // projection groups
     static constexpr int LPP = NG * 32;                 // padded projection rows
-    static constexpr int LRW = LR / kWaves;             // bucket rows owned by one wavefront
-    static constexpr int MT = LRW / 32;                 // 32-row tiles of bucket rows per wavefront
+    static constexpr int LRW = LR / kRowGroups;         // bucket rows of one row group (stream kernels)
+    static constexpr int MT = LRW / 32;                 // 32-row tiles of bucket rows per row group
     static constexpr int NT = D / 32;                   // 32-column tiles of the head dimension
+    static constexpr int NTW = NT / 2;                  // column tiles per wavefront (stream kernels)
+    static constexpr int LRG = LR / kWaves;             // bucket rows per wavefront (grad kernel)
+    static constexpr int MTG = LRG / 32;                // 32-row tiles per wavefront (grad kernel)
+    static constexpr int JSTEP = 4 / NG;                // wavefronts that share one projection group
     static constexpr int PLO = P < 3 ? P : 3, PHI = P - PLO;
     static constexpr int CPR = D / 8;                   // 16-byte chunks per row
     // LDS row strides, in bf16 elements (rows stay 16-byte aligned; the pad staggers banks)
@@ -52,19 +59,14 @@ struct Cfg {
     static constexpr int PS = LR + 8;                   // [token][L*R] assignment tiles
     static constexpr int ZS = LPP + 8;                  // [token][padded projection] tiles
     static constexpr int STATE = LR * (D + 1);          // floats per saved state: B [LR][D] then A [LR]
-    static_assert(LR % (32 * kWaves) == 0, "bucket rows must split into 32-row tiles per wavefront");
-    static_assert(D % 32 == 0 && R >= 8, "shape");
-    static_assert(2 * NG <= kWaves, "projection jobs must fit the wavefronts");
+    static_assert(LR % (32 * kRowGroups) == 0, "bucket rows must split into 32-row tiles per row group");
+    static_assert(D % 64 == 0 && R >= 8, "shape");
+    static_assert(4 % NG == 0 && NG <= 4, "projection groups must divide four wavefronts");
 };
 
-// Optional scheduling fence between MFMA groups (limits how far operand conversions are hoisted).
-// Off by default: with it, hipcc 7.2's MFMA register-rewrite pass crashes on one instantiation, and
-// without it the kernels spill only a few dozen dwords.
-#ifdef RACE_SCHED_FENCE_ON
+// Scheduling fence: keeps the instruction scheduler from hoisting the loads and conversions of later
+// loop iterations (and with them dozens of live registers) above this point.
 #define RACE_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
-#else
-#define RACE_SCHED_FENCE() ((void)0)
-#endif
 
 // kernel arguments common to the family
 struct KArgs {
@@ -74,6 +76,7 @@ struct KArgs {
     const bf16raw *Wp;     // (H, LPP, D) bf16, rows in projection-group order
     const bf16raw *WpT;    // (H, D, LPP) bf16
     float *state;          // (BH, nseg, STATE) fp32
+    bf16raw *dZ;           // (BH, N, LPP) bf16: cotangents of the projections (backward only)
 };
 
 // ---------------------------------------------------------------- small helpers
@@ -143,63 +146,62 @@ __device__ __forceinline__ u32x4 lds_tr_acc(const bf16raw *M, int stride, int k0
 }
 
 // ---------------------------------------------------------------- global -> registers -> LDS tiles
-// A 32-row tile is CPR*32 chunks of 16 bytes; thread t owns chunks t, t + 256, ...  Loads are issued one
-// tile ahead (fetch) and written to LDS at the start of the tile that uses them (store), so that HBM
-// latency overlaps the previous tile's arithmetic.
-template <class C>
+// A tile of ROWS rows is ROWS*CPR chunks of 16 bytes; thread t owns chunks t, t + 512, ...  Loads are
+// issued ahead of use (fetch) and written to LDS later (store), so that HBM latency overlaps arithmetic.
+template <class C, int ROWS>
 struct RowChunks {
-    static constexpr int N = kTile * C::CPR / kThreads;
+    static constexpr int N = (ROWS * C::CPR + kThreads - 1) / kThreads;
     u32x4 v[N];
 };
 
-template <class C>
-__device__ __forceinline__ void fetch_rows(const bf16raw *X, int64_t t0, int nvalid, RowChunks<C> &r)
+template <class C, int ROWS>
+__device__ __forceinline__ void fetch_rows(const bf16raw *X, int64_t t0, int nvalid, RowChunks<C, ROWS> &r)
 {
 #pragma unroll
-    for (int k = 0; k < RowChunks<C>::N; ++k) {
+    for (int k = 0; k < RowChunks<C, ROWS>::N; ++k) {
         const int c = threadIdx.x + k * kThreads, row = c / C::CPR, ch = c % C::CPR;
         r.v[k] = u32x4{0, 0, 0, 0};
         if (row < nvalid) r.v[k] = *reinterpret_cast<const u32x4 *>(X + (t0 + row) * C::D + ch * 8);
     }
 }
 
-template <class C>
-__device__ __forceinline__ void store_rows(const RowChunks<C> &r, bf16raw *dst)
+template <class C, int ROWS>
+__device__ __forceinline__ void store_rows(const RowChunks<C, ROWS> &r, bf16raw *dst)
 {
 #pragma unroll
-    for (int k = 0; k < RowChunks<C>::N; ++k) {
+    for (int k = 0; k < RowChunks<C, ROWS>::N; ++k) {
         const int c = threadIdx.x + k * kThreads, row = c / C::CPR, ch = c % C::CPR;
-        *reinterpret_cast<u32x4 *>(dst + row * C::XS + ch * 8) = r.v[k];
+        if (row < ROWS) *reinterpret_cast<u32x4 *>(dst + row * C::XS + ch * 8) = r.v[k];
     }
 }
 
 // Read-out cotangent rows: gn = dO / e (e = L * Den) as bf16 rows, ge[row] = -(dO . O) / e as fp32.
-template <class C>
+template <class C, int ROWS>
 struct CotChunks {
-    RowChunks<C> g, o;
-    float inv[RowChunks<C>::N];
+    RowChunks<C, ROWS> g, o;
+    float den[RowChunks<C, ROWS>::N];
 };
 
-template <class C>
+template <class C, int ROWS>
 __device__ __forceinline__ void fetch_cotangent(const bf16raw *dO, const bf16raw *O, const float *den, int64_t t0,
-                                                int nvalid, CotChunks<C> &r)
+                                                int nvalid, CotChunks<C, ROWS> &r)
 {
-    fetch_rows<C>(dO, t0, nvalid, r.g);
-    fetch_rows<C>(O, t0, nvalid, r.o);
+    fetch_rows<C, ROWS>(dO, t0, nvalid, r.g);
+    fetch_rows<C, ROWS>(O, t0, nvalid, r.o);
 #pragma unroll
-    for (int k = 0; k < RowChunks<C>::N; ++k) {
+    for (int k = 0; k < RowChunks<C, ROWS>::N; ++k) {
         const int row = (threadIdx.x + k * kThreads) / C::CPR;
-        r.inv[k] = (row < nvalid) ? den[t0 + row] : 0.f;
+        r.den[k] = (row < nvalid) ? den[t0 + row] : 0.f;
     }
 }
 
-template <class C>
-__device__ __forceinline__ void store_cotangent(const CotChunks<C> &r, bf16raw *dst, float *ge)
+template <class C, int ROWS>
+__device__ __forceinline__ void store_cotangent(const CotChunks<C, ROWS> &r, bf16raw *dst, float *ge)
 {
 #pragma unroll
-    for (int k = 0; k < RowChunks<C>::N; ++k) {
+    for (int k = 0; k < RowChunks<C, ROWS>::N; ++k) {
         const int c = threadIdx.x + k * kThreads, row = c / C::CPR, ch = c % C::CPR;
-        const float inv = r.inv[k] > 0.f ? 1.0f / (r.inv[k] * static_cast<float>(C::L)) : 0.f;
+        const float inv = r.den[k] > 0.f ? 1.0f / (r.den[k] * static_cast<float>(C::L)) : 0.f;
         const uint32_t gw[4] = {r.g.v[k].x, r.g.v[k].y, r.g.v[k].z, r.g.v[k].w};
         const uint32_t ow[4] = {r.o.v[k].x, r.o.v[k].y, r.o.v[k].z, r.o.v[k].w};
         uint32_t out[4];
@@ -211,12 +213,12 @@ __device__ __forceinline__ void store_cotangent(const CotChunks<C> &r, bf16raw *
             dot = fmaf(g1, bf_hi(ow[e]), dot);
             out[e] = pack2(g0 * inv, g1 * inv);
         }
-        *reinterpret_cast<u32x4 *>(dst + row * C::XS + ch * 8) = u32x4{out[0], out[1], out[2], out[3]};
+        if (row < ROWS) *reinterpret_cast<u32x4 *>(dst + row * C::XS + ch * 8) = u32x4{out[0], out[1], out[2], out[3]};
         if (ge) {
             // the CPR threads of one row are consecutive lanes
 #pragma unroll
             for (int m = C::CPR / 2; m >= 1; m >>= 1) dot += __shfl_xor(dot, m, 64);
-            if (ch == 0) ge[row] = -dot * inv;
+            if (ch == 0 && row < ROWS) ge[row] = -dot * inv;
         }
     }
 }
@@ -289,12 +291,14 @@ __device__ __forceinline__ void kron_factors(const float *p, const float *q, flo
     }
 }
 
-// Writes the assignment of the lane's token for its TPL tables as bf16 into ph [token][L*R].
+// Writes the assignment of the lane's token as bf16 into row `row` of ph [token][L*R].
 // valid == false writes zeros (a token past the end of the sequence must not reach the statistics).
-// Only the lane's tables j = j0, j0 + jstep, ... are written (lets several wavefronts share a group).
+// Only the lane's tables j = j0, j0 + jstep, ... and the high-bit indices a0 <= a < a1 are written, which
+// lets several wavefronts share the tables of one projection group.
 template <class C>
-__device__ __forceinline__ void write_assignments(const f32x16 &z, int g, int ln, int h, float beta, bool valid,
-                                                  bf16raw *ph, int j0 = 0, int jstep = 1)
+__device__ __forceinline__ void write_assignments(const f32x16 &z, int g, int row, int h, float beta, bool valid,
+                                                  bf16raw *ph, int j0 = 0, int jstep = 1, int a0 = 0,
+                                                  int a1 = 1 << C::PHI)
 {
 #pragma unroll
     for (int j = 0; j < C::TPL; ++j) {
@@ -306,11 +310,13 @@ __device__ __forceinline__ void write_assignments(const f32x16 &z, int g, int ln
         kron_factors<C>(p, q, lo, hi);
 #pragma unroll
         for (int a = 0; a < (1 << C::PHI); ++a) {
+            if (a < a0 || a >= a1) continue;
             const float ha = valid ? hi[a] : 0.f;
             const int r0 = table * C::R + a * (1 << C::PLO);
-            *reinterpret_cast<u32x4 *>(ph + ln * C::PS + r0) =
+            *reinterpret_cast<u32x4 *>(ph + row * C::PS + r0) =
                 u32x4{pack2(ha * lo[0], ha * lo[1]), pack2(ha * lo[2], ha * lo[3]), pack2(ha * lo[4], ha * lo[5]),
                       pack2(ha * lo[6], ha * lo[7])};
+            RACE_SCHED_FENCE();
         }
     }
 }

@@ -23,7 +23,7 @@ namespace mfma {
 
 enum Mode { kTotalsKV = 0, kTotalsQG = 1, kForward = 2, kGradV = 3 };
 
-// Developer aid: per-phase cycle counts of workgroup (0,0), printed at kernel end (build with -DRACE_PHASE_TIMING).
+// Developer aid: per-phase cycle counts of one workgroup, printed at kernel end (build with -DRACE_PHASE_TIMING).
 #ifdef RACE_PHASE_TIMING
 #define RACE_PHASE_DECL long long ph_t[12] = {0}; long long ph_last = clock64();
 #define RACE_PHASE(i) { long long now_ = clock64(); ph_t[i] += now_ - ph_last; ph_last = now_; }
@@ -36,118 +36,223 @@ enum Mode { kTotalsKV = 0, kTotalsQG = 1, kForward = 2, kGradV = 3 };
 #define RACE_PHASE_PRINT(tag)
 #endif
 
-// ---------------------------------------------------------------- LDS map of stream_kernel (bytes)
+// state element (bucket row r, column c) in the saved layout: B [LR][D] row-major, then A [LR]
+template <class C>
+__device__ __forceinline__ int state_b(int r, int c) { return r * C::D + c; }
+template <class C>
+__device__ __forceinline__ int state_a(int r) { return C::LR * C::D + r; }
+
+template <class C>
+__device__ __forceinline__ void load_projection_matrix(const KArgs &a, int head, bf16raw *wp)
+{
+    const bf16raw *src = a.Wp + static_cast<size_t>(head) * C::LPP * C::D;
+    for (int c = threadIdx.x; c < C::LPP * C::CPR; c += kThreads) {
+        const int row = c / C::CPR, ch = c % C::CPR;
+        *reinterpret_cast<u32x4 *>(wp + row * C::XS + ch * 8) = *reinterpret_cast<const u32x4 *>(src + row * C::D + ch * 8);
+    }
+}
+
+// ================================================================ totals_kernel
+// Statistics of one segment from a zero start, 64 tokens per step (both halves of the workgroup hash
+// 32 tokens each).  QG == 0: (phi_K, [V | 1]), Algorithm 1 step 5.  QG == 1: (phi_Q, [dO/e | -(dO.O)/e]),
+// the statistics the key side of the backward pass reads.
+template <class C>
+struct TotalsLds {
+    static constexpr int TT = 64;
+    static constexpr int wp = 0;                                        // [LPP][XS] bf16
+    static constexpr int x = wp + C::LPP * C::XS * 2;                   // [64][XS] hashed rows
+    static constexpr int y = x + TT * C::XS * 2;                        // [64][XS] accumulated rows
+    static constexpr int ph = y + TT * C::XS * 2;                       // [64][PS] assignments
+    static constexpr int ge = ph + TT * C::PS * 2;                      // [64] fp32
+    static constexpr int total = ge + TT * 4;
+    static_assert(total <= 160 * 1024, "LDS budget");
+};
+
+template <class C, int QG>
+__global__ __launch_bounds__(kThreads)
+void totals_kernel(KArgs a, const bf16raw *X, const bf16raw *Y, const bf16raw *Oin, const float *den_in)
+{
+    using S = TotalsLds<C>;
+    constexpr int TT = S::TT;
+    extern __shared__ __attribute__((aligned(256))) unsigned char lds[];
+    bf16raw *wp = reinterpret_cast<bf16raw *>(lds + S::wp);
+    bf16raw *xs = reinterpret_cast<bf16raw *>(lds + S::x);
+    bf16raw *ys = reinterpret_cast<bf16raw *>(lds + S::y);
+    bf16raw *ph = reinterpret_cast<bf16raw *>(lds + S::ph);
+    float *ge_lds = reinterpret_cast<float *>(lds + S::ge);
+
+    const int seg = blockIdx.x, bh = blockIdx.y, head = bh % a.H;
+    const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, ln = lane & 31, h = lane >> 5;
+    const int rg = w % kRowGroups, cg = w / kRowGroups;
+    const int r_own = rg * C::LRW, c_own = cg * (C::D / 2);
+    const size_t base = static_cast<size_t>(bh) * a.N * C::D;
+    X += base; Y += base;
+    if (QG) { Oin += base; den_in += static_cast<size_t>(bh) * a.N; }
+    float *st = a.state + (static_cast<size_t>(bh) * a.nseg + seg) * C::STATE;
+
+    load_projection_matrix<C>(a, head, wp);
+    f32x16 Sacc[C::MT][C::NTW];
+    float macc[C::MT];
+#pragma unroll
+    for (int mt = 0; mt < C::MT; ++mt) {
+        macc[mt] = 0.f;
+#pragma unroll
+        for (int nt = 0; nt < C::NTW; ++nt) Sacc[mt][nt] = f32x16{0};
+    }
+    const int64_t t_begin = seg * a.seg_len;
+    const int64_t t_end = (t_begin + a.seg_len < a.N) ? t_begin + a.seg_len : a.N;
+    const int nsteps = static_cast<int>((t_end - t_begin + TT - 1) / TT);
+    auto step_nv = [&](int64_t t0) { return (t_end - t0 < TT) ? static_cast<int>(t_end - t0) : TT; };
+
+    RowChunks<C, TT> pre_x, pre_y;
+    CotChunks<C, TT> pre_c;
+    auto fetch = [&](int it) {
+        const int64_t t0 = t_begin + static_cast<int64_t>(it) * TT;
+        const int nv = step_nv(t0);
+        fetch_rows<C, TT>(X, t0, nv, pre_x);
+        if (QG) fetch_cotangent<C, TT>(Y, Oin, den_in, t0, nv, pre_c);
+        else fetch_rows<C, TT>(Y, t0, nv, pre_y);
+    };
+    if (nsteps > 0) fetch(0);
+
+    for (int it = 0; it < nsteps; ++it) {
+        const int64_t t0 = t_begin + static_cast<int64_t>(it) * TT;
+        const int nvalid = step_nv(t0);
+        store_rows<C, TT>(pre_x, xs);
+        if (QG) store_cotangent<C, TT>(pre_c, ys, ge_lds);
+        else store_rows<C, TT>(pre_y, ys);
+        if (it + 1 < nsteps) fetch(it + 1);
+        __syncthreads();
+        {
+            // wavefront = (token half, projection group, share of the group's tables)
+            const int half = w / 4, g = w % C::NG, jq = (w % 4) / C::NG;
+            const f32x16 z = project<C>(wp, xs + half * 32 * C::XS, g, ln, h);
+            write_assignments<C>(z, g, half * 32 + ln, h, a.beta, half * 32 + ln < nvalid, ph, jq, C::JSTEP);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int s = 0; s < TT / 16; ++s) {
+            u32x4 by[C::NTW];
+#pragma unroll
+            for (int nt = 0; nt < C::NTW; ++nt) by[nt] = lds_tr_plain(ys, C::XS, 16 * s, c_own + 32 * nt, ln, h);
+            float4 g0 = {1.f, 1.f, 1.f, 1.f}, g1 = g0;
+            if (QG && cg == 0) {
+                g0 = *reinterpret_cast<const float4 *>(ge_lds + 16 * s + 8 * h);
+                g1 = *reinterpret_cast<const float4 *>(ge_lds + 16 * s + 8 * h + 4);
+            }
+#pragma unroll
+            for (int mt = 0; mt < C::MT; ++mt) {
+                const u32x4 ap = lds_tr_plain(ph, C::PS, 16 * s, r_own + 32 * mt, ln, h);
+                if (cg == 0)      // the extra column (bucket mass, or its cotangent) is carried by column group 0
+                    macc[mt] += bf_lo(ap.x) * g0.x + bf_hi(ap.x) * g0.y + bf_lo(ap.y) * g0.z + bf_hi(ap.y) * g0.w +
+                                bf_lo(ap.z) * g1.x + bf_hi(ap.z) * g1.y + bf_lo(ap.w) * g1.z + bf_hi(ap.w) * g1.w;
+#pragma unroll
+                for (int nt = 0; nt < C::NTW; ++nt) Sacc[mt][nt] = mma(ap, by[nt], Sacc[mt][nt]);
+            }
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int mt = 0; mt < C::MT; ++mt) {
+#pragma unroll
+        for (int nt = 0; nt < C::NTW; ++nt) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                st[state_b<C>(r_own + 32 * mt + acc_row(v, h), c_own + 32 * nt + ln)] = Sacc[mt][nt][v];
+        }
+        const float tot = macc[mt] + __shfl_xor(macc[mt], 32, 64);
+        if (cg == 0 && h == 0) st[state_a<C>(r_own + 32 * mt + ln)] = tot;
+    }
+}
+
+// ================================================================ stream_kernel
+// One pass over a segment carrying the statistics as tiles S[bucket row][head column].
+//   kForward: Algorithm 2's loop body (Algorithm 1's read-out when not causal): O and Den.
+//   kGradV  : the mirrored pass, right to left, over the cotangent statistics: dV.
+// "reader" = tensor whose assignments read the statistics (Q forward, K for dV), "writer" = tensor
+// whose assignments feed them (K forward, Q for dV), Y = rows accumulated (V forward, dO/e for dV).
 template <class C>
 struct StreamLds {
     static constexpr int wp = 0;                                        // [LPP][XS] bf16
-    static constexpr int y = wp + C::LPP * C::XS * 2;                   // [32][XS] bf16: accumulated tensor rows
+    static constexpr int y = wp + C::LPP * C::XS * 2;                   // [32][XS] bf16: accumulated rows
     static constexpr int mass = y + kTile * C::XS * 2;                  // [LR] fp32: bucket masses A before this tile
-    static constexpr int ge = mass + C::LR * 4;                         // [32] fp32: normaliser cotangents
-    static constexpr int area = (ge + kTile * 4 + 255) & ~255;          // start of the aliased area
+    static constexpr int area = (mass + C::LR * 4 + 255) & ~255;        // start of the aliased area
     // phase A (production, contraction)
     static constexpr int xr = area;                                     // [32][XS] reader rows
     static constexpr int xw = xr + kTile * C::XS * 2;                   // [32][XS] writer rows
     static constexpr int phr = xw + kTile * C::XS * 2;                  // [32][PS] reader assignments
     static constexpr int phw = phr + kTile * C::PS * 2;                 // [32][PS] writer assignments
     static constexpr int endA = phw + kTile * C::PS * 2;
-    // phase B (cross-wavefront reduction) reuses the same bytes
+    // phase B (reduction over the four bucket-row groups) reuses the same bytes
     static constexpr int RS = C::D + 4;                                 // fp32 row stride: D numerators, 2 normaliser parts
     static constexpr int red = area;                                    // [4][32][RS] fp32
-    static constexpr int endB = red + kWaves * kTile * RS * 4;
+    static constexpr int endB = red + kRowGroups * kTile * RS * 4;
     static constexpr int total = endA > endB ? endA : endB;
     static_assert(total <= 160 * 1024, "LDS budget");
 };
 
-// state element (bucket row r, column c) in the saved layout
-template <class C>
-__device__ __forceinline__ int state_b(int r, int c) { return r * C::D + c; }
-template <class C>
-__device__ __forceinline__ int state_a(int r) { return C::LR * C::D + r; }
-
 template <class C, int MODE>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
+__global__ __launch_bounds__(kThreads)
 void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw *Y, const bf16raw *Oin,
                    const float *den_in, bf16raw *Out, float *den_out)
 {
-    // Xr: tensor hashed on the reading side (Q forward, K for dV); Xw: on the writing side (K forward, Q for dV)
-    // Y : tensor accumulated into the statistics (V forward; dO for the cotangent statistics)
     using S = StreamLds<C>;
     extern __shared__ __attribute__((aligned(256))) unsigned char lds[];
     bf16raw *wp = reinterpret_cast<bf16raw *>(lds + S::wp);
     bf16raw *ytile = reinterpret_cast<bf16raw *>(lds + S::y);
     float *mass = reinterpret_cast<float *>(lds + S::mass);
-    float *ge_lds = reinterpret_cast<float *>(lds + S::ge);
     bf16raw *xr = reinterpret_cast<bf16raw *>(lds + S::xr);
     bf16raw *xw = reinterpret_cast<bf16raw *>(lds + S::xw);
     bf16raw *phr = reinterpret_cast<bf16raw *>(lds + S::phr);
     bf16raw *phw = reinterpret_cast<bf16raw *>(lds + S::phw);
     float *red = reinterpret_cast<float *>(lds + S::red);
 
-    constexpr bool kTotals = (MODE == kTotalsKV || MODE == kTotalsQG);
     constexpr bool kReverse = (MODE == kGradV);
-    constexpr bool kCotangentY = (MODE == kTotalsQG || MODE == kGradV);   // Y = dO / e (and ge for the mass column)
-
     const int seg = blockIdx.x, bh = blockIdx.y, head = bh % a.H;
-    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, ln = lane & 31, h = lane >> 5;
-    const int r_own = w * C::LRW;
-    const bool intra = kTotals || a.causal;          // the tile's own keys take part (always for totals)
+    const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, ln = lane & 31, h = lane >> 5;
+    const int rg = w % kRowGroups, cg = w / kRowGroups;
+    const int r_own = rg * C::LRW, c_own = cg * (C::D / 2);
+    const bool intra = a.causal;                      // the tile's own keys take part
 
     const size_t base = static_cast<size_t>(bh) * a.N * C::D;
-    Xr += base; Xw += base; Y += base;
-    if (Oin) Oin += base;
-    if (Out) Out += base;
-    if (den_in) den_in += static_cast<size_t>(bh) * a.N;
-    if (den_out) den_out += static_cast<size_t>(bh) * a.N;
-    float *st = a.state + (static_cast<size_t>(bh) * a.nseg + seg) * C::STATE;
+    Xr += base; Xw += base; Y += base; Out += base;
+    if (MODE == kGradV) { Oin += base; den_in += static_cast<size_t>(bh) * a.N; }
+    if (MODE == kForward) den_out += static_cast<size_t>(bh) * a.N;
+    const float *st = a.state + (static_cast<size_t>(bh) * a.nseg + seg) * C::STATE;
 
-    // projection matrix of this head -> LDS
-    {
-        const bf16raw *src = a.Wp + static_cast<size_t>(head) * C::LPP * C::D;
-        for (int c = tid; c < C::LPP * C::CPR; c += kThreads) {
-            const int row = c / C::CPR, ch = c % C::CPR;
-            *reinterpret_cast<u32x4 *>(wp + row * C::XS + ch * 8) =
-                *reinterpret_cast<const u32x4 *>(src + row * C::D + ch * 8);
-        }
-    }
+    load_projection_matrix<C>(a, head, wp);
     // statistics at the start of the segment
-    f32x16 Sacc[C::MT][C::NT];
-    float macc[C::MT];                 // bucket masses: per-half partial sums, lane n <-> row r_own + 32*mt + n
+    f32x16 Sacc[C::MT][C::NTW];
+    float macc[C::MT];                 // bucket masses (column group 0 only): per-half partial sums, lane n <-> row
 #pragma unroll
     for (int mt = 0; mt < C::MT; ++mt) {
-        macc[mt] = 0.f;
 #pragma unroll
-        for (int nt = 0; nt < C::NT; ++nt) {
+        for (int nt = 0; nt < C::NTW; ++nt) {
 #pragma unroll
             for (int v = 0; v < 16; ++v)
-                Sacc[mt][nt][v] = kTotals ? 0.f : st[state_b<C>(r_own + 32 * mt + acc_row(v, h), 32 * nt + ln)];
+                Sacc[mt][nt][v] = st[state_b<C>(r_own + 32 * mt + acc_row(v, h), c_own + 32 * nt + ln)];
         }
-        if (!kTotals && h == 0) macc[mt] = st[state_a<C>(r_own + 32 * mt + ln)];
-    }
-    if (MODE == kForward) {
-#pragma unroll
-        for (int mt = 0; mt < C::MT; ++mt)
-            if (h == 0) mass[r_own + 32 * mt + ln] = macc[mt];
+        macc[mt] = (MODE == kForward && cg == 0 && h == 0) ? st[state_a<C>(r_own + 32 * mt + ln)] : 0.f;
+        if (MODE == kForward && cg == 0 && h == 0) mass[r_own + 32 * mt + ln] = macc[mt];
     }
 
     const int64_t t_begin = seg * a.seg_len;
     const int64_t t_end = (t_begin + a.seg_len < a.N) ? t_begin + a.seg_len : a.N;
     const int ntiles = static_cast<int>((t_end - t_begin + kTile - 1) / kTile);
-
-    // tile index -> first token and number of valid rows
     auto tile_t0 = [&](int it) { return t_begin + static_cast<int64_t>(kReverse ? ntiles - 1 - it : it) * kTile; };
     auto tile_nv = [&](int64_t t0) { return (t_end - t0 < kTile) ? static_cast<int>(t_end - t0) : kTile; };
 
     // loads run one tile ahead of the arithmetic
-    RowChunks<C> pre_r, pre_w, pre_y;
-    CotChunks<C> pre_c;
+    RowChunks<C, kTile> pre_r, pre_w, pre_y;
+    CotChunks<C, kTile> pre_c;
     auto fetch = [&](int it) {
         const int64_t t0 = tile_t0(it);
         const int nv = tile_nv(t0);
-        if (!kTotals) fetch_rows<C>(Xr, t0, nv, pre_r);
+        fetch_rows<C, kTile>(Xr, t0, nv, pre_r);
         if (intra) {
-            fetch_rows<C>(Xw, t0, nv, pre_w);
-            if (kCotangentY) fetch_cotangent<C>(Y, Oin, den_in, t0, nv, pre_c);
-            else fetch_rows<C>(Y, t0, nv, pre_y);
+            fetch_rows<C, kTile>(Xw, t0, nv, pre_w);
+            if (MODE == kGradV) fetch_cotangent<C, kTile>(Y, Oin, den_in, t0, nv, pre_c);
+            else fetch_rows<C, kTile>(Y, t0, nv, pre_y);
         }
     };
     if (ntiles > 0) fetch(0);
@@ -158,125 +263,111 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
         const int nvalid = tile_nv(t0);
 
         // ---- registers -> LDS, then start the next tile's loads
-        if (!kTotals) store_rows<C>(pre_r, xr);
+        store_rows<C, kTile>(pre_r, xr);
         if (intra) {
-            store_rows<C>(pre_w, xw);
-            if (kCotangentY) store_cotangent<C>(pre_c, ytile, MODE == kTotalsQG ? ge_lds : nullptr);
-            else store_rows<C>(pre_y, ytile);
+            store_rows<C, kTile>(pre_w, xw);
+            if (MODE == kGradV) store_cotangent<C, kTile>(pre_c, ytile, nullptr);
+            else store_rows<C, kTile>(pre_y, ytile);
         }
-        if (it + 1 < ntiles) fetch(it + 1);
         RACE_PHASE(0)
         __syncthreads();
         RACE_PHASE(1)
 
-        // ---- production: wavefront = (side, projection group)
+        // ---- production: wavefront = (side, projection group, share of the group's tables)
         {
-            const int side = w / C::NG, g = w % C::NG;          // side 0: reader, 1: writer
-            if (side == 0 && !kTotals) {
+            const int side = w / 4, g = w % C::NG, jq = (w % 4) / C::NG;
+            if (side == 0) {
                 const f32x16 z = project<C>(wp, xr, g, ln, h);
-                write_assignments<C>(z, g, ln, h, a.beta, true, phr);
-            } else if (side == 1 && intra) {
+                write_assignments<C>(z, g, ln, h, a.beta, true, phr, jq, C::JSTEP);
+            } else if (intra) {
                 const f32x16 z = project<C>(wp, xw, g, ln, h);
-                write_assignments<C>(z, g, ln, h, a.beta, ln < nvalid, phw);
+                write_assignments<C>(z, g, ln, h, a.beta, ln < nvalid, phw, jq, C::JSTEP);
             }
         }
         RACE_PHASE(2)
         __syncthreads();
         RACE_PHASE(3)
 
-        // ---- contraction with the register-resident statistics
-        f32x16 out[C::NT];
+        // ---- contraction with the register-resident statistics (own bucket rows x own columns)
+        f32x16 out[C::NTW];
         f32x16 dn = {0};        // read-out of the bucket masses (every column holds the same value)
+        f32x16 sct = {0};       // in-tile kernel values, transposed: row = writer token, lane = reader token
         float rowsum = 0.f;     // in-tile part of the normaliser, reader token = ln
-        if (!kTotals) {
-            f32x16 sct = {0};   // in-tile kernel values, transposed: row = writer token, lane = reader token
 #pragma unroll
-            for (int nt = 0; nt < C::NT; ++nt) out[nt] = f32x16{0};
+        for (int nt = 0; nt < C::NTW; ++nt) out[nt] = f32x16{0};
 #pragma unroll
-            for (int mt = 0; mt < C::MT; ++mt) {
-#pragma unroll
-                for (int s = 0; s < 2; ++s) {
-                    const int rr = r_own + 32 * mt + 16 * s + 4 * h;
-                    const u32x4 ar = lds64x2(phr + ln * C::PS + rr, phr + ln * C::PS + rr + 8);
-#pragma unroll
-                    for (int nt = 0; nt < C::NT; ++nt) out[nt] = mma(ar, acc_operand(Sacc[mt][nt], s), out[nt]);
-                    if (MODE == kForward) {
-                        const float4 m0 = *reinterpret_cast<const float4 *>(mass + rr);
-                        const float4 m1 = *reinterpret_cast<const float4 *>(mass + rr + 8);
-                        dn = mma(ar, u32x4{pack2(m0.x, m0.y), pack2(m0.z, m0.w), pack2(m1.x, m1.y), pack2(m1.z, m1.w)}, dn);
-                    }
-                    if (intra) {
-                        const u32x4 aw = lds64x2(phw + ln * C::PS + rr, phw + ln * C::PS + rr + 8);
-                        sct = mma(aw, ar, sct);
-                    }
-                    RACE_SCHED_FENCE();
-                }
-            }
-            if (intra) {
-                // mask (writer token j = row, reader token i = lane), row sums, and (mask o kernel) . Y
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int j = acc_row(v, h);
-                    const bool keep = kReverse ? (j >= ln) : (j <= ln);
-                    sct[v] = keep ? sct[v] : 0.f;
-                    rowsum += sct[v];
-                }
-                rowsum += __shfl_xor(rowsum, 32, 64);
-#pragma unroll
-                for (int s = 0; s < 2; ++s) {
-                    const u32x4 ak = acc_operand(sct, s);
-#pragma unroll
-                    for (int nt = 0; nt < C::NT; ++nt)
-                        out[nt] = mma(ak, lds_tr_acc(ytile, C::XS, 16 * s, 32 * nt, ln, h), out[nt]);
-                }
-            }
-        }
-        RACE_PHASE(4)
-        // ---- statistics += phi_writer^T . Y  (after the read-out above used the old statistics)
-        if (intra) {
+        for (int mt = 0; mt < C::MT; ++mt) {
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
-                u32x4 by[C::NT];
+                const int rr = r_own + 32 * mt + 16 * s + 4 * h;
+                const u32x4 ar = lds64x2(phr + ln * C::PS + rr, phr + ln * C::PS + rr + 8);
 #pragma unroll
-                for (int nt = 0; nt < C::NT; ++nt) by[nt] = lds_tr_plain(ytile, C::XS, 16 * s, 32 * nt, ln, h);
-                float gw[8];
-                if (MODE == kTotalsQG) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) gw[e] = ge_lds[16 * s + 8 * h + e];
+                for (int nt = 0; nt < C::NTW; ++nt) out[nt] = mma(ar, acc_operand(Sacc[mt][nt], s), out[nt]);
+                if (MODE == kForward && cg == 0) {
+                    const float4 m0 = *reinterpret_cast<const float4 *>(mass + rr);
+                    const float4 m1 = *reinterpret_cast<const float4 *>(mass + rr + 8);
+                    dn = mma(ar, u32x4{pack2(m0.x, m0.y), pack2(m0.z, m0.w), pack2(m1.x, m1.y), pack2(m1.z, m1.w)}, dn);
                 }
+                if (intra) {
+                    const u32x4 aw = lds64x2(phw + ln * C::PS + rr, phw + ln * C::PS + rr + 8);
+                    sct = mma(aw, ar, sct);
+                }
+                RACE_SCHED_FENCE();
+            }
+        }
+        if (intra) {
+            // mask (writer token j = row, reader token i = lane), row sums, and (mask o kernel) . Y
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int j = acc_row(v, h);
+                const bool keep = kReverse ? (j >= ln) : (j <= ln);
+                sct[v] = keep ? sct[v] : 0.f;
+                rowsum += sct[v];
+            }
+            rowsum += __shfl_xor(rowsum, 32, 64);
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                const u32x4 ak = acc_operand(sct, s);
+#pragma unroll
+                for (int nt = 0; nt < C::NTW; ++nt)
+                    out[nt] = mma(ak, lds_tr_acc(ytile, C::XS, 16 * s, c_own + 32 * nt, ln, h), out[nt]);
+            }
+            RACE_PHASE(4)
+            // ---- statistics += phi_writer^T . Y  (the read-out above used the old statistics)
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                u32x4 by[C::NTW];
+#pragma unroll
+                for (int nt = 0; nt < C::NTW; ++nt) by[nt] = lds_tr_plain(ytile, C::XS, 16 * s, c_own + 32 * nt, ln, h);
 #pragma unroll
                 for (int mt = 0; mt < C::MT; ++mt) {
                     const u32x4 ap = lds_tr_plain(phw, C::PS, 16 * s, r_own + 32 * mt, ln, h);
-                    if (MODE == kTotalsQG) {
-                        macc[mt] += bf_lo(ap.x) * gw[0] + bf_hi(ap.x) * gw[1] + bf_lo(ap.y) * gw[2] + bf_hi(ap.y) * gw[3] +
-                                    bf_lo(ap.z) * gw[4] + bf_hi(ap.z) * gw[5] + bf_lo(ap.w) * gw[6] + bf_hi(ap.w) * gw[7];
-                    } else if (MODE != kGradV) {
-                        macc[mt] += sum8(ap);
-                    }
+                    if (MODE == kForward && cg == 0) macc[mt] += sum8(ap);
 #pragma unroll
-                    for (int nt = 0; nt < C::NT; ++nt) Sacc[mt][nt] = mma(ap, by[nt], Sacc[mt][nt]);
+                    for (int nt = 0; nt < C::NTW; ++nt) Sacc[mt][nt] = mma(ap, by[nt], Sacc[mt][nt]);
                     RACE_SCHED_FENCE();
                 }
             }
         }
+        // the next tile's loads fly during the reduction and the epilogue (few registers are live there)
+        if (it + 1 < ntiles) fetch(it + 1);
         RACE_PHASE(5)
         __syncthreads();        // every wavefront is done with the tiles of this step
         RACE_PHASE(6)
-        if (kTotals) continue;
 
-        // ---- cross-wavefront reduction of the partial read-outs (each wavefront covered LR/4 bucket rows)
+        // ---- reduction over the four bucket-row groups: partial read-outs through LDS
 #pragma unroll
-        for (int nt = 0; nt < C::NT; ++nt) {
+        for (int nt = 0; nt < C::NTW; ++nt) {
 #pragma unroll
             for (int v = 0; v < 16; ++v)
-                red[(w * kTile + acc_row(v, h)) * S::RS + 32 * nt + ln] = out[nt][v];
+                red[(rg * kTile + acc_row(v, h)) * S::RS + c_own + 32 * nt + ln] = out[nt][v];
         }
-        if (MODE == kForward) {
+        if (MODE == kForward && cg == 0) {
             if (ln == 0) {
 #pragma unroll
-                for (int v = 0; v < 16; ++v) red[(w * kTile + acc_row(v, h)) * S::RS + C::D] = dn[v];
+                for (int v = 0; v < 16; ++v) red[(rg * kTile + acc_row(v, h)) * S::RS + C::D] = dn[v];
             }
-            if (h == 0) red[(w * kTile + ln) * S::RS + C::D + 1] = rowsum;
+            if (h == 0) red[(rg * kTile + ln) * S::RS + C::D + 1] = rowsum;
             // masses after this tile, for the next tile's read-out
 #pragma unroll
             for (int mt = 0; mt < C::MT; ++mt) {
@@ -287,17 +378,17 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
         RACE_PHASE(7)
         __syncthreads();
         RACE_PHASE(8)
-        // ---- epilogue: thread = (token, D/8 consecutive columns): sum the partials, normalise, store rows
+        // ---- epilogue: thread = (token, D/16 consecutive columns): sum the partials, normalise, store rows
         {
-            constexpr int CW = C::D / 8;                 // columns per thread
-            const int tok = tid >> 3, c0 = (tid & 7) * CW;
+            constexpr int CW = C::D / 16;                // columns per thread (8 or 4)
+            const int tok = tid >> 4, c0 = (tid & 15) * CW;
             float acc[CW];
 #pragma unroll
             for (int c = 0; c < CW; ++c) acc[c] = 0.f;
             float e = 0.f;
 #pragma unroll
-            for (int ww = 0; ww < kWaves; ++ww) {
-                const float *src = red + (ww * kTile + tok) * S::RS;
+            for (int gg = 0; gg < kRowGroups; ++gg) {
+                const float *src = red + (gg * kTile + tok) * S::RS;
 #pragma unroll
                 for (int c = 0; c < CW; c += 4) {
                     const float4 p4 = *reinterpret_cast<const float4 *>(src + c0 + c);
@@ -307,14 +398,14 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
             }
             if (tok < nvalid) {
                 const float scale = (MODE == kForward) ? 1.0f / e : 1.0f;
-                uint32_t packed[CW / 2];
-#pragma unroll
-                for (int c = 0; c < CW; c += 2) packed[c / 2] = pack2(acc[c] * scale, acc[c + 1] * scale);
-#pragma unroll
-                for (int c = 0; c < CW / 2; c += 4)
-                    *reinterpret_cast<u32x4 *>(Out + (t0 + tok) * C::D + c0 + 2 * c) =
-                        u32x4{packed[c], packed[c + 1], packed[c + 2], packed[c + 3]};
-                if (MODE == kForward && (tid & 7) == 0) den_out[t0 + tok] = e * (1.0f / C::L);
+                bf16raw *dst = Out + (t0 + tok) * C::D + c0;
+                if (CW == 8) {
+                    *reinterpret_cast<u32x4 *>(dst) = u32x4{pack2(acc[0] * scale, acc[1] * scale), pack2(acc[2] * scale, acc[3] * scale),
+                                                            pack2(acc[4 % CW] * scale, acc[5 % CW] * scale), pack2(acc[6 % CW] * scale, acc[7 % CW] * scale)};
+                } else {
+                    *reinterpret_cast<u32x2 *>(dst) = u32x2{pack2(acc[0] * scale, acc[1] * scale), pack2(acc[2] * scale, acc[3] * scale)};
+                }
+                if (MODE == kForward && (tid & 15) == 0) den_out[t0 + tok] = e * (1.0f / C::L);
             }
         }
         RACE_PHASE(9)
@@ -322,20 +413,6 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
         RACE_PHASE(10)
     }
     RACE_PHASE_PRINT("stream")
-
-    if (kTotals) {
-#pragma unroll
-        for (int mt = 0; mt < C::MT; ++mt) {
-#pragma unroll
-            for (int nt = 0; nt < C::NT; ++nt) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    st[state_b<C>(r_own + 32 * mt + acc_row(v, h), 32 * nt + ln)] = Sacc[mt][nt][v];
-            }
-            const float tot = macc[mt] + __shfl_xor(macc[mt], 32, 64);
-            if (h == 0) st[state_a<C>(r_own + 32 * mt + ln)] = tot;
-        }
-    }
 }
 
 // In-place scan over the segments of one (batch*head).  mode 0: exclusive prefix, 1: exclusive suffix,
@@ -379,7 +456,7 @@ __global__ __launch_bounds__(kThreads) void hash_tap_kernel(KArgs a, const bf16r
     bf16raw *x = wp + C::LPP * C::XS;
     bf16raw *ph = x + kTile * C::XS;
     const int bh = blockIdx.y, head = bh % a.H;
-    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, ln = lane & 31, h = lane >> 5;
+    const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, ln = lane & 31, h = lane >> 5;
     const int64_t t0 = static_cast<int64_t>(blockIdx.x) * kTile;
     const int nvalid = (a.N - t0 < kTile) ? static_cast<int>(a.N - t0) : kTile;
     const bf16raw *src = a.Wp + static_cast<size_t>(head) * C::LPP * C::D;
@@ -388,9 +465,9 @@ __global__ __launch_bounds__(kThreads) void hash_tap_kernel(KArgs a, const bf16r
         *reinterpret_cast<u32x4 *>(wp + row * C::XS + ch * 8) = *reinterpret_cast<const u32x4 *>(src + row * C::D + ch * 8);
     }
     {
-        RowChunks<C> rows;
-        fetch_rows<C>(X + static_cast<size_t>(bh) * a.N * C::D, t0, nvalid, rows);
-        store_rows<C>(rows, x);
+        RowChunks<C, kTile> rows;
+        fetch_rows<C, kTile>(X + static_cast<size_t>(bh) * a.N * C::D, t0, nvalid, rows);
+        store_rows<C, kTile>(rows, x);
     }
     __syncthreads();
     if (w < C::NG) {
@@ -446,7 +523,21 @@ KArgs make_kargs(const Plan &p, char *ws)
     a.Wp = reinterpret_cast<const bf16raw *>(ws + p.off_W);
     a.WpT = a.Wp + static_cast<size_t>(p.H) * C::LPP * C::D;
     a.state = reinterpret_cast<float *>(ws + p.off_stateA);
+    a.dZ = reinterpret_cast<bf16raw *>(ws + p.off_part);
     return a;
+}
+
+template <class C, int QG>
+hipError_t launch_totals(const Plan &p, KArgs a, const void *X, const void *Y, const void *O, const float *den_in,
+                         hipStream_t st)
+{
+    auto kern = totals_kernel<C, QG>;
+    RACE_TRY(allow_lds(kern, TotalsLds<C>::total));
+    ProfileScope prof(QG ? "stream_totals_qg" : "stream_totals_kv", st);
+    hipLaunchKernelGGL(kern, dim3(p.nseg, p.BH), dim3(kThreads), TotalsLds<C>::total, st, a,
+                       static_cast<const bf16raw *>(X), static_cast<const bf16raw *>(Y),
+                       static_cast<const bf16raw *>(O), den_in);
+    return hipGetLastError();
 }
 
 template <class C, int MODE>
@@ -475,9 +566,34 @@ template <class C>
 hipError_t fwd_t(const Plan &p, const void *Q, const void *K, const void *V, void *O, float *den, char *ws, hipStream_t st)
 {
     KArgs a = make_kargs<C>(p, ws);
-    RACE_TRY((launch_stream<C, kTotalsKV>(p, a, K, K, V, nullptr, nullptr, nullptr, nullptr, st)));
+    RACE_TRY((launch_totals<C, 0>(p, a, K, V, nullptr, nullptr, st)));
     RACE_TRY(launch_scan(p, a.state, C::STATE, p.causal ? 0 : 2, st));
     RACE_TRY((launch_stream<C, kForward>(p, a, Q, K, V, nullptr, nullptr, O, den, st)));
+    return hipSuccess;
+}
+
+// dphi and the chain rule through the soft assignment (grad_kernel, one workgroup per share of the
+// tables), then dX = dZ . W for all tables
+template <class C, int SIDE>
+hipError_t launch_grad(const Plan &p, KArgs a, const void *Q, const void *K, const void *V, const void *O,
+                       const float *den, const void *dO, void *dX, hipStream_t st)
+{
+    {
+        auto kern = grad_kernel<C, SIDE>;
+        RACE_TRY(allow_lds(kern, GradLds<C>::total));
+        ProfileScope prof(SIDE == 0 ? "grad_q" : "grad_k", st);
+        hipLaunchKernelGGL(kern, dim3(p.nseg, p.BH, GradCfg<C>::TSPLIT), dim3(kThreads), GradLds<C>::total, st, a,
+                           static_cast<const bf16raw *>(Q), static_cast<const bf16raw *>(K),
+                           static_cast<const bf16raw *>(V), static_cast<const bf16raw *>(O), den,
+                           static_cast<const bf16raw *>(dO), a.dZ);
+        RACE_TRY(hipGetLastError());
+    }
+    {
+        ProfileScope prof("dz_matmul", st);
+        hipLaunchKernelGGL(dz_matmul_kernel<C>, dim3(static_cast<unsigned>((p.N + kTile - 1) / kTile), p.BH),
+                           dim3(64 * C::NT), 0, st, a, a.dZ, static_cast<bf16raw *>(dX));
+        RACE_TRY(hipGetLastError());
+    }
     return hipSuccess;
 }
 
@@ -489,31 +605,13 @@ hipError_t bwd_t(const Plan &p, const void *Q, const void *K, const void *V, con
     KArgs b = a;
     b.state = reinterpret_cast<float *>(ws + p.off_stateB);
     // statistics of (phi_K, [V | 1]) at segment starts; of (phi_Q, read-out cotangents) at segment ends
-    RACE_TRY((launch_stream<C, kTotalsKV>(p, a, K, K, V, nullptr, nullptr, nullptr, nullptr, st)));
+    RACE_TRY((launch_totals<C, 0>(p, a, K, V, nullptr, nullptr, st)));
     RACE_TRY(launch_scan(p, a.state, C::STATE, p.causal ? 0 : 2, st));
-    RACE_TRY((launch_stream<C, kTotalsQG>(p, b, Q, Q, dO, O, den, nullptr, nullptr, st)));
+    RACE_TRY((launch_totals<C, 1>(p, b, Q, dO, O, den, st)));
     RACE_TRY(launch_scan(p, b.state, C::STATE, p.causal ? 1 : 2, st));
     RACE_TRY((launch_stream<C, kGradV>(p, b, K, Q, dO, O, den, dV, nullptr, st)));
-    {
-        auto kern = grad_kernel<C, 0>;
-        RACE_TRY(allow_lds(kern, GradLds<C>::total));
-        ProfileScope prof("grad_q", st);
-        hipLaunchKernelGGL(kern, dim3(p.nseg, p.BH), dim3(kThreads), GradLds<C>::total, st, a,
-                           static_cast<const bf16raw *>(Q), static_cast<const bf16raw *>(K),
-                           static_cast<const bf16raw *>(V), static_cast<const bf16raw *>(O), den,
-                           static_cast<const bf16raw *>(dO), static_cast<bf16raw *>(dQ));
-        RACE_TRY(hipGetLastError());
-    }
-    {
-        auto kern = grad_kernel<C, 1>;
-        RACE_TRY(allow_lds(kern, GradLds<C>::total));
-        ProfileScope prof("grad_k", st);
-        hipLaunchKernelGGL(kern, dim3(p.nseg, p.BH), dim3(kThreads), GradLds<C>::total, st, b,
-                           static_cast<const bf16raw *>(Q), static_cast<const bf16raw *>(K),
-                           static_cast<const bf16raw *>(V), static_cast<const bf16raw *>(O), den,
-                           static_cast<const bf16raw *>(dO), static_cast<bf16raw *>(dK));
-        RACE_TRY(hipGetLastError());
-    }
+    RACE_TRY((launch_grad<C, 0>(p, a, Q, K, V, O, den, dO, dQ, st)));
+    RACE_TRY((launch_grad<C, 1>(p, b, Q, K, V, O, den, dO, dK, st)));
     return hipSuccess;
 }
 
@@ -521,7 +619,7 @@ template <class C>
 hipError_t buckets_t(const Plan &p, const void *K, const void *V, float *A, float *Bsum, char *ws, hipStream_t st)
 {
     KArgs a = make_kargs<C>(p, ws);
-    RACE_TRY((launch_stream<C, kTotalsKV>(p, a, K, K, V, nullptr, nullptr, nullptr, nullptr, st)));
+    RACE_TRY((launch_totals<C, 0>(p, a, K, V, nullptr, nullptr, st)));
     const size_t total = static_cast<size_t>(p.BH) * C::STATE;
     hipLaunchKernelGGL(bucket_tap_kernel<C>, dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0, st, a.state,
                        p.nseg, p.BH, A, Bsum);
@@ -575,7 +673,7 @@ void pack_t(const Plan &p, const float *W, void *image)
 }
 
 // Dispatch over the compiled shapes.
-#define RACE_SHAPES(X) X(128, 6, 8) X(64, 4, 16)
+#define RACE_SHAPES(X) RACE_MFMA_SHAPES(X)
 
 }  // namespace
 
@@ -585,6 +683,14 @@ bool mfma_supported(int d, int L, int P)
     RACE_SHAPES(X)
 #undef X
     return false;
+}
+
+size_t mfma_scratch_bytes(const Plan &p)
+{
+#define X(DD, PP_, LL) if (p.d == DD && p.P == PP_ && p.L == LL) return static_cast<size_t>(p.BH) * static_cast<size_t>(p.N) * Cfg<DD, PP_, LL>::LPP * 2;
+    RACE_SHAPES(X)
+#undef X
+    return 0;
 }
 
 size_t mfma_projection_bytes(const Plan &p)

@@ -216,7 +216,7 @@ race_status_t make_plan(const race_attn_desc_t *desc, Plan *pl)
         p.nseg = static_cast<int>((n + len - 1) / len);
         p.bytes_W = align256(mfma_projection_bytes(p));
         p.bytes_state = align256(static_cast<size_t>(p.BH) * p.nseg * p.LR * (p.d + 1) * sizeof(float));
-        p.bytes_part = 0;
+        p.bytes_part = align256(mfma_scratch_bytes(p));
     }
     p.off_W = 0;
     p.off_stateA = p.off_W + p.bytes_W;
