@@ -68,6 +68,15 @@ struct Cfg {
 // loop iterations (and with them dozens of live registers) above this point.
 #define RACE_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
+// Hides the value of an index from the optimiser inside a loop body, so that the dozens of addresses
+// derived from it (index + constant) are folded into instruction offsets instead of being hoisted out of
+// the loop as separate loop-invariant registers (which then spill).
+__device__ __forceinline__ int opaque(int x)
+{
+    asm volatile("" : "+v"(x));
+    return x;
+}
+
 // kernel arguments common to the family
 struct KArgs {
     int H, nseg, causal;

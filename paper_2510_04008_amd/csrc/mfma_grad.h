@@ -193,9 +193,9 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
         // ---- in-tile part: T^T[b][a] = Yw_b . Yr_a + sw_b * sr_a, masked
         f32x16 tt = {0};
         if (intra) {
+            const int yo = opaque(ln * C::XS + 8 * h);
 #pragma unroll
-            for (int s = 0; s < C::D / 16; ++s)
-                tt = mma(lds128(yw + ln * C::XS + 16 * s + 8 * h), lds128(yr + ln * C::XS + 16 * s + 8 * h), tt);
+            for (int s = 0; s < C::D / 16; ++s) tt = mma(lds128(yw + yo + 16 * s), lds128(yr + yo + 16 * s), tt);
             float sw_hi, sw_lo;
             split_bf16(sw[ln], sw_hi, sw_lo);
             const u32x4 sw_a = (h == 0) ? u32x4{pack2(sw_hi, sw_hi), pack2(sw_lo, 0.f), 0u, 0u} : u32x4{0u, 0u, 0u, 0u};
@@ -223,13 +223,15 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
             for (int s = 0; s < 2; ++s)
                 dP = mma(acc_operand(tt, s), lds_tr_acc(phw, C::PS, 16 * s, r_own, ln, h), dP);
         }
+        {
+            const int yo = opaque(ln * C::XS + 4 * h);
 #pragma unroll
-        for (int mtc = 0; mtc < C::NT; ++mtc) {
+            for (int mtc = 0; mtc < C::NT; ++mtc) {
 #pragma unroll
-            for (int s = 0; s < 2; ++s) {
-                const int cc = 32 * mtc + 16 * s + 4 * h;
-                const u32x4 ay = lds64x2(yr + ln * C::XS + cc, yr + ln * C::XS + cc + 8);
-                dP = mma(ay, acc_operand(ST[mtc], s), dP);
+                for (int s = 0; s < 2; ++s) {
+                    const int cc = 32 * mtc + 16 * s;
+                    dP = mma(lds64x2(yr + yo + cc, yr + yo + cc + 8), acc_operand(ST[mtc], s), dP);
+                }
             }
         }
         GRAD_PHASE(5)
@@ -252,8 +254,11 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
         GRAD_PHASE(7)
 
         // ---- hand the cotangents to the lanes that own (token, table)
+        {
+            const int dbase = opaque(4 * h * S::DS + (r_own - r_base) + ln);
 #pragma unroll
-        for (int v = 0; v < 16; ++v) dphi[acc_row(v, h) * S::DS + (r_own - r_base) + ln] = dP[v];
+            for (int v = 0; v < 16; ++v) dphi[dbase + (8 * (v >> 2) + (v & 3)) * S::DS] = dP[v];
+        }
         // the next tile's loads fly during the vector-ALU phases below (few registers are live here)
         if (it + 1 < ntiles) fetch(it + 1);
         GRAD_PHASE(8)
@@ -281,6 +286,7 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
             float p[C::P], q[C::P], sech2[C::P], lo[1 << C::PLO], hi[1 << C::PHI];
             bit_masses<C>(z, j, a.beta, p, q, sech2);
             kron_factors<C>(p, q, lo, hi);
+            const int dsrc = opaque(ln * S::DS + (table * C::R - r_base));
             float E[C::P];
 #pragma unroll
             for (int t = 0; t < C::P; ++t) E[t] = 0.f;
@@ -288,7 +294,7 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
             float chunk[1 << C::PHI];
 #pragma unroll
             for (int aa = 0; aa < (1 << C::PHI); ++aa) {
-                const float *src = dphi + ln * S::DS + (table * C::R - r_base) + aa * 8;
+                const float *src = dphi + dsrc + aa * 8;
                 const float4 d0 = *reinterpret_cast<const float4 *>(src);
                 const float4 d1 = *reinterpret_cast<const float4 *>(src + 4);
                 const float wv[8] = {hi[aa] * lo[0] * d0.x, hi[aa] * lo[1] * d0.y, hi[aa] * lo[2] * d0.z, hi[aa] * lo[3] * d0.w,

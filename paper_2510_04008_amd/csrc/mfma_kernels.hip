@@ -184,7 +184,7 @@ struct StreamLds {
     static constexpr int phw = phr + kTile * C::PS * 2;                 // [32][PS] writer assignments
     static constexpr int endA = phw + kTile * C::PS * 2;
     // phase B (reduction over the four bucket-row groups) reuses the same bytes
-    static constexpr int RS = C::D + 4;                                 // fp32 row stride: D numerators, 2 normaliser parts
+    static constexpr int RS = C::D + 4;                                 // fp32 row stride: D numerators, 3 normaliser parts
     static constexpr int red = area;                                    // [4][32][RS] fp32
     static constexpr int endB = red + kRowGroups * kTile * RS * 4;
     static constexpr int total = endA > endB ? endA : endB;
@@ -223,7 +223,7 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
     load_projection_matrix<C>(a, head, wp);
     // statistics at the start of the segment
     f32x16 Sacc[C::MT][C::NTW];
-    float macc[C::MT];                 // bucket masses (column group 0 only): per-half partial sums, lane n <-> row
+    float macc[C::MT];                 // bucket masses (tiles mt % 2 == cg): per-half partial sums, lane n <-> row
 #pragma unroll
     for (int mt = 0; mt < C::MT; ++mt) {
 #pragma unroll
@@ -232,8 +232,9 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
             for (int v = 0; v < 16; ++v)
                 Sacc[mt][nt][v] = st[state_b<C>(r_own + 32 * mt + acc_row(v, h), c_own + 32 * nt + ln)];
         }
-        macc[mt] = (MODE == kForward && cg == 0 && h == 0) ? st[state_a<C>(r_own + 32 * mt + ln)] : 0.f;
-        if (MODE == kForward && cg == 0 && h == 0) mass[r_own + 32 * mt + ln] = macc[mt];
+        // the bucket masses of tile mt are carried by column group mt % 2 (balances the vector work)
+        macc[mt] = (MODE == kForward && (mt & 1) == cg && h == 0) ? st[state_a<C>(r_own + 32 * mt + ln)] : 0.f;
+        if (MODE == kForward && (mt & 1) == cg && h == 0) mass[r_own + 32 * mt + ln] = macc[mt];
     }
 
     const int64_t t_begin = seg * a.seg_len;
@@ -290,7 +291,6 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
 
         // ---- contraction with the register-resident statistics (own bucket rows x own columns)
         f32x16 out[C::NTW];
-        f32x16 dn = {0};        // read-out of the bucket masses (every column holds the same value)
         f32x16 sct = {0};       // in-tile kernel values, transposed: row = writer token, lane = reader token
         float rowsum = 0.f;     // in-tile part of the normaliser, reader token = ln
 #pragma unroll
@@ -303,11 +303,6 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
                 const u32x4 ar = lds64x2(phr + ln * C::PS + rr, phr + ln * C::PS + rr + 8);
 #pragma unroll
                 for (int nt = 0; nt < C::NTW; ++nt) out[nt] = mma(ar, acc_operand(Sacc[mt][nt], s), out[nt]);
-                if (MODE == kForward && cg == 0) {
-                    const float4 m0 = *reinterpret_cast<const float4 *>(mass + rr);
-                    const float4 m1 = *reinterpret_cast<const float4 *>(mass + rr + 8);
-                    dn = mma(ar, u32x4{pack2(m0.x, m0.y), pack2(m0.z, m0.w), pack2(m1.x, m1.y), pack2(m1.z, m1.w)}, dn);
-                }
                 if (intra) {
                     const u32x4 aw = lds64x2(phw + ln * C::PS + rr, phw + ln * C::PS + rr + 8);
                     sct = mma(aw, ar, sct);
@@ -332,6 +327,8 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
                 for (int nt = 0; nt < C::NTW; ++nt)
                     out[nt] = mma(ak, lds_tr_acc(ytile, C::XS, 16 * s, c_own + 32 * nt, ln, h), out[nt]);
             }
+        }
+        if (intra) {
             RACE_PHASE(4)
             // ---- statistics += phi_writer^T . Y  (the read-out above used the old statistics)
 #pragma unroll
@@ -342,10 +339,28 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
 #pragma unroll
                 for (int mt = 0; mt < C::MT; ++mt) {
                     const u32x4 ap = lds_tr_plain(phw, C::PS, 16 * s, r_own + 32 * mt, ln, h);
-                    if (MODE == kForward && cg == 0) macc[mt] += sum8(ap);
+                    if (MODE == kForward && (mt & 1) == cg) macc[mt] += sum8(ap);
 #pragma unroll
                     for (int nt = 0; nt < C::NTW; ++nt) Sacc[mt][nt] = mma(ap, by[nt], Sacc[mt][nt]);
                     RACE_SCHED_FENCE();
+                }
+            }
+        }
+        // ---- read-out of the bucket masses for the normaliser (every column of dn holds the same value);
+        //      a second pass over the reader operands so that its accumulator can reuse dead registers;
+        //      the two column groups split the row group's tiles
+        f32x16 dn = {0};
+        if (MODE == kForward) {
+#pragma unroll
+            for (int mt = 0; mt < C::MT; ++mt) {
+                if ((mt & 1) != cg) continue;
+#pragma unroll
+                for (int s = 0; s < 2; ++s) {
+                    const int rr = r_own + 32 * mt + 16 * s + 4 * h;
+                    const u32x4 ar = lds64x2(phr + ln * C::PS + rr, phr + ln * C::PS + rr + 8);
+                    const float4 m0 = *reinterpret_cast<const float4 *>(mass + rr);
+                    const float4 m1 = *reinterpret_cast<const float4 *>(mass + rr + 8);
+                    dn = mma(ar, u32x4{pack2(m0.x, m0.y), pack2(m0.z, m0.w), pack2(m1.x, m1.y), pack2(m1.z, m1.w)}, dn);
                 }
             }
         }
@@ -356,21 +371,24 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
         RACE_PHASE(6)
 
         // ---- reduction over the four bucket-row groups: partial read-outs through LDS
+        const int rbase = opaque((rg * kTile + 4 * h) * S::RS);          // + (8 * (v / 4) + v % 4) rows per register
 #pragma unroll
         for (int nt = 0; nt < C::NTW; ++nt) {
 #pragma unroll
             for (int v = 0; v < 16; ++v)
-                red[(rg * kTile + acc_row(v, h)) * S::RS + c_own + 32 * nt + ln] = out[nt][v];
+                red[rbase + (8 * (v >> 2) + (v & 3)) * S::RS + c_own + 32 * nt + ln] = out[nt][v];
         }
-        if (MODE == kForward && cg == 0) {
+        if (MODE == kForward) {
+            // normaliser parts: columns D + cg (mass read-out of this column group's tiles), D + 2 (in-tile row sums)
             if (ln == 0) {
 #pragma unroll
-                for (int v = 0; v < 16; ++v) red[(rg * kTile + acc_row(v, h)) * S::RS + C::D] = dn[v];
+                for (int v = 0; v < 16; ++v) red[rbase + (8 * (v >> 2) + (v & 3)) * S::RS + C::D + cg] = dn[v];
             }
-            if (h == 0) red[(rg * kTile + ln) * S::RS + C::D + 1] = rowsum;
+            if (cg == 0 && h == 0) red[(rg * kTile + ln) * S::RS + C::D + 2] = rowsum;
             // masses after this tile, for the next tile's read-out
 #pragma unroll
             for (int mt = 0; mt < C::MT; ++mt) {
+                if ((mt & 1) != cg) continue;
                 const float tot = macc[mt] + __shfl_xor(macc[mt], 32, 64);
                 if (h == 0) mass[r_own + 32 * mt + ln] = tot;
             }
@@ -394,7 +412,7 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
                     const float4 p4 = *reinterpret_cast<const float4 *>(src + c0 + c);
                     acc[c] += p4.x; acc[c + 1] += p4.y; acc[c + 2] += p4.z; acc[c + 3] += p4.w;
                 }
-                if (MODE == kForward) e += src[C::D] + src[C::D + 1];
+                if (MODE == kForward) e += (src[C::D] + src[C::D + 1]) + src[C::D + 2];
             }
             if (tok < nvalid) {
                 const float scale = (MODE == kForward) ? 1.0f / e : 1.0f;
