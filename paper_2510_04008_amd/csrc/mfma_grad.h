@@ -46,6 +46,8 @@ struct GradCfg {
     static_assert(TSPLIT >= 1 && C::NG % TSPLIT == 0 && kWaves % NGW == 0, "table split");
     static_assert(AW >= 1 && AN >= 1 && AN * AW == (1 << C::PHI), "assignment split");
     static_assert(NGW * C::TPG * C::R == ROWS, "a workgroup's rows are the tables of its projection groups");
+    static_assert(AW == 1 || (C::TPL == JW && C::P <= 7), "the split backward pass handles one table per wavefront");
+    static_assert(NGW * C::TPL <= kWaves && NGW + 1 <= kWaves, "production roles must fit the wavefronts");
 };
 
 template <class C>
@@ -58,7 +60,8 @@ struct GradLds {
     static constexpr int sw = sr + kTile * 4;                           // [32] fp32 extra column of writer-Y
     static constexpr int zl = (sw + kTile * 4 + 15) & ~15;              // [NGW][64][16] fp32: reader projections
     static constexpr int yr = zl + G::NGW * 64 * 16 * 4;                // [32][XS] reader-Y rows
-    static constexpr int area = (yr + kTile * C::XS * 2 + 255) & ~255;
+    static constexpr int ttop = yr + kTile * C::XS * 2;                 // [2][64] x 16 B: masked in-tile term as MFMA operands
+    static constexpr int area = (ttop + 2 * 64 * 16 + 255) & ~255;
     // phase A
     static constexpr int xr = area;                                     // [32][XS]
     static constexpr int xw = xr + kTile * C::XS * 2;
@@ -68,7 +71,8 @@ struct GradLds {
     // phase B
     static constexpr int DS = G::ROWS + 4;                              // fp32 row stride
     static constexpr int dphi = area;                                   // [32][DS] fp32
-    static constexpr int endB = dphi + kTile * DS * 4;
+    static constexpr int part = dphi + kTile * DS * 4;                  // [AW-1][NGW*JW][64][8] fp32: partial sums
+    static constexpr int endB = part + (G::AW - 1) * G::NGW * G::JW * 64 * 8 * 4;
     static constexpr int total = endA > endB ? endA : endB;
     static_assert(total <= 160 * 1024, "LDS budget");
 };
@@ -92,6 +96,8 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
     bf16raw *yw = reinterpret_cast<bf16raw *>(lds + S::yw);
     bf16raw *phw = reinterpret_cast<bf16raw *>(lds + S::phw);
     float *dphi = reinterpret_cast<float *>(lds + S::dphi);
+    float *part = reinterpret_cast<float *>(lds + S::part);
+    u32x4 *ttop = reinterpret_cast<u32x4 *>(lds + S::ttop);
 
     constexpr bool kReverse = (SIDE == 1);
     const int seg = blockIdx.x, bh = blockIdx.y, head = bh % a.H;
@@ -168,37 +174,35 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
         __syncthreads();
         GRAD_PHASE(1)
 
-        // ---- production: the reader's projections go to LDS for the backward pass through the soft
-        //      assignment; the writer's assignments are split over all eight wavefronts
-        if (w < G::NGW) {
-            const f32x16 zr = project<C>(wp, xr, g, ln, h);
-            float *zdst = zl + (gl * 64 + lane) * 16;
-#pragma unroll
-            for (int v = 0; v < 16; v += 4) *reinterpret_cast<float4 *>(zdst + v) = float4{zr[v], zr[v + 1], zr[v + 2], zr[v + 3]};
-        }
-        if (intra) {
-            const f32x16 zw = project<C>(wp, xw, g, ln, h);
-            write_assignments<C>(zw, g, ln, h, a.beta, ln < nvalid, phw, jq, G::JW, a0, a0 + G::AN);
-        }
-        GRAD_PHASE(2)
-        __syncthreads();
-        GRAD_PHASE(3)
-
         // extra columns as bf16 (hi, lo) pairs: three products hi*hi + hi*lo + lo*hi keep 16 mantissa bits
         float sr_hi, sr_lo;
         split_bf16(sr[ln], sr_hi, sr_lo);
         const u32x4 sr_a = (h == 0) ? u32x4{pack2(sr_hi, sr_hi), pack2(sr_lo, 0.f), 0u, 0u} : u32x4{0u, 0u, 0u, 0u};
-        const u32x4 sr_b = (h == 0) ? u32x4{pack2(sr_hi, sr_lo), pack2(sr_hi, 0.f), 0u, 0u} : u32x4{0u, 0u, 0u, 0u};
 
-        // ---- in-tile part: T^T[b][a] = Yw_b . Yr_a + sw_b * sr_a, masked
-        f32x16 tt = {0};
-        if (intra) {
+        // ---- production, by role: the first NGW*TPL wavefronts hash the writer's tables; the last NGW
+        //      project the reader (kept for the backward pass through the soft assignment); one more forms
+        //      the in-tile term T^T[b][a] = Yw_b . Yr_a + sw_b * sr_a, masked, as MFMA operands for everybody
+        if (intra && w < G::NGW * C::TPL) {
+            const int pg = w % G::NGW, pj = w / G::NGW;
+            const f32x16 zw = project<C>(wp, xw, th * G::NGW + pg, ln, h);
+            write_assignments<C>(zw, th * G::NGW + pg, ln, h, a.beta, ln < nvalid, phw, pj, C::TPL);
+        }
+        if (w >= kWaves - G::NGW) {
+            const int pg = kWaves - 1 - w;
+            const f32x16 zr = project<C>(wp, xr, th * G::NGW + pg, ln, h);
+            float *zdst = zl + (pg * 64 + lane) * 16;
+#pragma unroll
+            for (int v = 0; v < 16; v += 4) *reinterpret_cast<float4 *>(zdst + v) = float4{zr[v], zr[v + 1], zr[v + 2], zr[v + 3]};
+        }
+        if (intra && w == kWaves - 1 - G::NGW) {
+            f32x16 tt = {0};
             const int yo = opaque(ln * C::XS + 8 * h);
 #pragma unroll
             for (int s = 0; s < C::D / 16; ++s) tt = mma(lds128(yw + yo + 16 * s), lds128(yr + yo + 16 * s), tt);
             float sw_hi, sw_lo;
             split_bf16(sw[ln], sw_hi, sw_lo);
             const u32x4 sw_a = (h == 0) ? u32x4{pack2(sw_hi, sw_hi), pack2(sw_lo, 0.f), 0u, 0u} : u32x4{0u, 0u, 0u, 0u};
+            const u32x4 sr_b = (h == 0) ? u32x4{pack2(sr_hi, sr_lo), pack2(sr_hi, 0.f), 0u, 0u} : u32x4{0u, 0u, 0u, 0u};
             tt = mma(sw_a, sr_b, tt);
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
@@ -206,8 +210,12 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
                 const bool keep = kReverse ? (b >= ln) : (b <= ln);
                 tt[v] = keep ? tt[v] : 0.f;
             }
-            RACE_SCHED_FENCE();
+            ttop[lane] = acc_operand(tt, 0);
+            ttop[64 + lane] = acc_operand(tt, 1);
         }
+        GRAD_PHASE(2)
+        __syncthreads();
+        GRAD_PHASE(3)
         GRAD_PHASE(4)
         // ---- cotangent of the reader's assignments for this wavefront's 32 bucket rows
         f32x16 dP;
@@ -221,7 +229,7 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
         if (intra) {
 #pragma unroll
             for (int s = 0; s < 2; ++s)
-                dP = mma(acc_operand(tt, s), lds_tr_acc(phw, C::PS, 16 * s, r_own, ln, h), dP);
+                dP = mma(ttop[64 * s + lane], lds_tr_acc(phw, C::PS, 16 * s, r_own, ln, h), dP);
         }
         {
             const int yo = opaque(ln * C::XS + 4 * h);
@@ -268,10 +276,15 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
         // ---- back through the corner softmax and tanh (Algorithm 1, step 4):
         //      with w_r = phi_r dphi_r, m = sum_r w_r, E_t = sum_r v_{r,t} w_r:
         //      du_t = beta (E_t - m (p_t - q_t)),  dz_t = du_t (1 - tanh^2 z_t)
+        //      The R corners of a table are split over AW wavefronts by their high bits; wavefronts aq > 0
+        //      hand their partial sums (m, E_t) to wavefront aq == 0 of the same table through LDS.
+        float Efin[C::P + 1];          // aq == 0 only: E_t and m after combining (last table of the lane)
+        float p_k[C::P], q_k[C::P], s_k[C::P];
+        int jfin = -1;
 #pragma unroll
         for (int j = 0; j < C::TPL; ++j) {
             const int table = g * C::TPG + h * C::TPL + j;
-            if (table >= C::L || aq != 0) break;
+            if (table >= C::L) break;
             if (j < jq || (j - jq) % G::JW != 0) continue;
             constexpr int ZW = C::PP;                              // the table's slots are contiguous
             f32x16 z = {0};
@@ -291,9 +304,9 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
 #pragma unroll
             for (int t = 0; t < C::P; ++t) E[t] = 0.f;
             float m = 0.f;
-            float chunk[1 << C::PHI];
 #pragma unroll
             for (int aa = 0; aa < (1 << C::PHI); ++aa) {
+                if (aa < a0 || aa >= a0 + G::AN) continue;
                 const float *src = dphi + dsrc + aa * 8;
                 const float4 d0 = *reinterpret_cast<const float4 *>(src);
                 const float4 d1 = *reinterpret_cast<const float4 *>(src + 4);
@@ -304,24 +317,60 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
                 if (C::PLO > 1) E[1] += (s23 - s01) + (s67 - s45);
                 const float s0123 = s01 + s23, s4567 = s45 + s67;
                 if (C::PLO > 2) E[2] += s4567 - s0123;
-                chunk[aa] = s0123 + s4567;
+                const float chunk = s0123 + s4567;
+                m += chunk;
+#pragma unroll
+                for (int t = 0; t < C::PHI; ++t) E[C::PLO + t] += ((aa >> t) & 1) ? chunk : -chunk;
                 RACE_SCHED_FENCE();
             }
-#pragma unroll
-            for (int aa = 0; aa < (1 << C::PHI); ++aa) {
-                m += chunk[aa];
-#pragma unroll
-                for (int t = 0; t < C::PHI; ++t) E[C::PLO + t] += ((aa >> t) & 1) ? chunk[aa] : -chunk[aa];
+            if (G::AW > 1 && aq > 0) {
+                float *dst = part + (((aq - 1) * G::NGW * G::JW + (w % (G::NGW * G::JW))) * 64 + lane) * 8;
+                *reinterpret_cast<float4 *>(dst) = float4{m, E[0], E[1], E[2]};
+                *reinterpret_cast<float4 *>(dst + 4) = float4{C::P > 3 ? E[3 % C::P] : 0.f, C::P > 4 ? E[4 % C::P] : 0.f,
+                                                              C::P > 5 ? E[5 % C::P] : 0.f, C::P > 6 ? E[6 % C::P] : 0.f};
             }
-            float dzv[ZW];
+            if (G::AW == 1) {
+                // one wavefront sees the whole table: finish here
+                float dzv[ZW];
 #pragma unroll
-            for (int t = 0; t < ZW; ++t) dzv[t] = (t < C::P) ? a.beta * (E[t] - m * (p[t] - q[t])) * sech2[t] : 0.f;
-            // slot v = ZW*j + t of the projection accumulator is projection row acc_row(v, h) of group g
+                for (int t = 0; t < ZW; ++t) dzv[t] = (t < C::P) ? a.beta * (E[t] - m * (p[t] - q[t])) * sech2[t] : 0.f;
 #pragma unroll
-            for (int t = 0; t < ZW; t += 4) {
-                const int v = ZW * j + t;
-                *reinterpret_cast<u32x2 *>(dz + ln * S::DZS + gl * 32 + 8 * (v >> 2) + 4 * h) =
-                    u32x2{pack2(dzv[t], dzv[t + 1]), pack2(dzv[t + 2], dzv[t + 3])};
+                for (int t = 0; t < ZW; t += 4) {
+                    const int v = ZW * j + t;      // slot v of the projection accumulator is projection row acc_row(v, h)
+                    *reinterpret_cast<u32x2 *>(dz + ln * S::DZS + gl * 32 + 8 * (v >> 2) + 4 * h) =
+                        u32x2{pack2(dzv[t], dzv[t + 1]), pack2(dzv[t + 2], dzv[t + 3])};
+                }
+            } else {
+                jfin = j;
+                Efin[C::P] = m;
+#pragma unroll
+                for (int t = 0; t < C::P; ++t) { Efin[t] = E[t]; p_k[t] = p[t]; q_k[t] = q[t]; s_k[t] = sech2[t]; }
+            }
+        }
+        if (G::AW > 1) {
+            __syncthreads();
+            if (aq == 0 && jfin >= 0) {
+#pragma unroll
+                for (int o = 1; o < G::AW; ++o) {
+                    const float *src = part + (((o - 1) * G::NGW * G::JW + (w % (G::NGW * G::JW))) * 64 + lane) * 8;
+                    const float4 p0 = *reinterpret_cast<const float4 *>(src);
+                    const float4 p1 = *reinterpret_cast<const float4 *>(src + 4);
+                    const float pe[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+                    Efin[C::P] += pe[0];
+#pragma unroll
+                    for (int t = 0; t < C::P; ++t) Efin[t] += pe[1 + t];
+                }
+                constexpr int ZW = C::PP;
+                float dzv[ZW];
+#pragma unroll
+                for (int t = 0; t < ZW; ++t)
+                    dzv[t] = (t < C::P) ? a.beta * (Efin[t % C::P] - Efin[C::P] * (p_k[t % C::P] - q_k[t % C::P])) * s_k[t % C::P] : 0.f;
+#pragma unroll
+                for (int t = 0; t < ZW; t += 4) {
+                    const int v = ZW * jfin + t;
+                    *reinterpret_cast<u32x2 *>(dz + ln * S::DZS + gl * 32 + 8 * (v >> 2) + 4 * h) =
+                        u32x2{pack2(dzv[t], dzv[t + 1]), pack2(dzv[t + 2], dzv[t + 3])};
+                }
             }
         }
         GRAD_PHASE(10)
