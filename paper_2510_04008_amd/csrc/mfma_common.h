@@ -239,14 +239,14 @@ __device__ __forceinline__ void store_cotangent(const CotChunks<C, ROWS> &r, bf1
 template <class C>
 __device__ __forceinline__ f32x16 project(const bf16raw *wp, const bf16raw *x, int g, int ln, int h)
 {
-    f32x16 z = {0};
+    // two accumulators halve the chain of dependent MFMAs
+    f32x16 z0 = {0}, z1 = {0};
 #pragma unroll
-    for (int s = 0; s < C::D / 16; ++s) {
-        const u32x4 a = lds128(wp + (g * 32 + ln) * C::XS + 16 * s + 8 * h);
-        const u32x4 b = lds128(x + ln * C::XS + 16 * s + 8 * h);
-        z = mma(a, b, z);
+    for (int s = 0; s < C::D / 16; s += 2) {
+        z0 = mma(lds128(wp + (g * 32 + ln) * C::XS + 16 * s + 8 * h), lds128(x + ln * C::XS + 16 * s + 8 * h), z0);
+        z1 = mma(lds128(wp + (g * 32 + ln) * C::XS + 16 * s + 16 + 8 * h), lds128(x + ln * C::XS + 16 * s + 16 + 8 * h), z1);
     }
-    return z;
+    return z0 + z1;
 }
 // projection t of the lane's j-th table inside the accumulator
 template <class C>
@@ -304,11 +304,14 @@ __device__ __forceinline__ void kron_factors(const float *p, const float *q, flo
 // valid == false writes zeros (a token past the end of the sequence must not reach the statistics).
 // Only the lane's tables j = j0, j0 + jstep, ... and the high-bit indices a0 <= a < a1 are written, which
 // lets several wavefronts share the tables of one projection group.
+// If mass != null, returns sum_r phi[r] * mass[table*R + r] over what was written (the read-out of the
+// bucket masses A by this token, i.e. its share of the normaliser), else 0.
 template <class C>
-__device__ __forceinline__ void write_assignments(const f32x16 &z, int g, int row, int h, float beta, bool valid,
-                                                  bf16raw *ph, int j0 = 0, int jstep = 1, int a0 = 0,
-                                                  int a1 = 1 << C::PHI)
+__device__ __forceinline__ float write_assignments(const f32x16 &z, int g, int row, int h, float beta, bool valid,
+                                                   bf16raw *ph, int j0 = 0, int jstep = 1, int a0 = 0,
+                                                   int a1 = 1 << C::PHI, const float *mass = nullptr)
 {
+    float dn = 0.f;
 #pragma unroll
     for (int j = 0; j < C::TPL; ++j) {
         const int table = g * C::TPG + h * C::TPL + j;
@@ -322,12 +325,21 @@ __device__ __forceinline__ void write_assignments(const f32x16 &z, int g, int ro
             if (a < a0 || a >= a1) continue;
             const float ha = valid ? hi[a] : 0.f;
             const int r0 = table * C::R + a * (1 << C::PLO);
+            float f[8];
+#pragma unroll
+            for (int b = 0; b < 8; ++b) f[b] = ha * lo[b];
+            if (mass) {
+                const float4 m0 = *reinterpret_cast<const float4 *>(mass + r0);
+                const float4 m1 = *reinterpret_cast<const float4 *>(mass + r0 + 4);
+                dn = fmaf(f[0], m0.x, dn); dn = fmaf(f[1], m0.y, dn); dn = fmaf(f[2], m0.z, dn); dn = fmaf(f[3], m0.w, dn);
+                dn = fmaf(f[4], m1.x, dn); dn = fmaf(f[5], m1.y, dn); dn = fmaf(f[6], m1.z, dn); dn = fmaf(f[7], m1.w, dn);
+            }
             *reinterpret_cast<u32x4 *>(ph + row * C::PS + r0) =
-                u32x4{pack2(ha * lo[0], ha * lo[1]), pack2(ha * lo[2], ha * lo[3]), pack2(ha * lo[4], ha * lo[5]),
-                      pack2(ha * lo[6], ha * lo[7])};
+                u32x4{pack2(f[0], f[1]), pack2(f[2], f[3]), pack2(f[4], f[5]), pack2(f[6], f[7])};
             RACE_SCHED_FENCE();
         }
     }
+    return dn;
 }
 
 }  // namespace mfma

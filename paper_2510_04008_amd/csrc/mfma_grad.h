@@ -391,7 +391,8 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
     GRAD_PHASE_PRINT()
 }
 
-// dX = dZ . W: (N x LPP) . (LPP x d) per head, 32 tokens per workgroup of NT wavefronts.
+// dX = dZ . W: (N x LPP) . (LPP x d) per head; a workgroup of NT wavefronts takes kDzTiles tiles of 32 tokens.
+constexpr int kDzTiles = 8;
 template <class C>
 __global__ __launch_bounds__(64 * C::NT)
 void dz_matmul_kernel(KArgs a, const bf16raw *dZ, bf16raw *dX)
@@ -401,34 +402,38 @@ void dz_matmul_kernel(KArgs a, const bf16raw *dZ, bf16raw *dX)
     __shared__ __attribute__((aligned(16))) bf16raw stage[C::NT * kTile * SS];
     const int bh = blockIdx.y, head = bh % a.H;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, ln = lane & 31, h = lane >> 5;
-    const int64_t t0 = static_cast<int64_t>(blockIdx.x) * kTile;
-    const int nvalid = (a.N - t0 < kTile) ? static_cast<int>(a.N - t0) : kTile;
     dZ += static_cast<size_t>(bh) * a.N * C::LPP;
     dX += static_cast<size_t>(bh) * a.N * C::D;
-    for (int c = tid; c < kTile * (C::LPP / 8); c += 64 * C::NT) {
-        const int row = c / (C::LPP / 8), ch = c % (C::LPP / 8);
-        u32x4 v = {0, 0, 0, 0};
-        if (row < nvalid) v = *reinterpret_cast<const u32x4 *>(dZ + (t0 + row) * C::LPP + 8 * ch);
-        *reinterpret_cast<u32x4 *>(dz + row * C::ZS + 8 * ch) = v;
-    }
-    __syncthreads();
     const bf16raw *wt = a.WpT + static_cast<size_t>(head) * C::D * C::LPP;     // [d][LPP]
     const int nt = w;
-    f32x16 acc = {0};
+    u32x4 bw[C::LPP / 16];
 #pragma unroll
-    for (int s = 0; s < C::LPP / 16; ++s) {
-        const u32x4 az = lds128(dz + ln * C::ZS + 16 * s + 8 * h);
-        const u32x4 bw = *reinterpret_cast<const u32x4 *>(wt + (32 * nt + ln) * C::LPP + 16 * s + 8 * h);
-        acc = mma(az, bw, acc);
-    }
-    bf16raw *sg = stage + w * kTile * SS;
+    for (int s = 0; s < C::LPP / 16; ++s)
+        bw[s] = *reinterpret_cast<const u32x4 *>(wt + (32 * nt + ln) * C::LPP + 16 * s + 8 * h);
+    for (int k = 0; k < kDzTiles; ++k) {
+        const int64_t t0 = (static_cast<int64_t>(blockIdx.x) * kDzTiles + k) * kTile;
+        if (t0 >= a.N) break;
+        const int nvalid = (a.N - t0 < kTile) ? static_cast<int>(a.N - t0) : kTile;
+        __syncthreads();
+        for (int c = tid; c < kTile * (C::LPP / 8); c += 64 * C::NT) {
+            const int row = c / (C::LPP / 8), ch = c % (C::LPP / 8);
+            u32x4 v = {0, 0, 0, 0};
+            if (row < nvalid) v = *reinterpret_cast<const u32x4 *>(dZ + (t0 + row) * C::LPP + 8 * ch);
+            *reinterpret_cast<u32x4 *>(dz + row * C::ZS + 8 * ch) = v;
+        }
+        __syncthreads();
+        f32x16 acc = {0};
 #pragma unroll
-    for (int v = 0; v < 16; ++v) sg[acc_row(v, h) * SS + ln] = static_cast<bf16raw>(pack2(acc[v], 0.f) & 0xffffu);
+        for (int s = 0; s < C::LPP / 16; ++s) acc = mma(lds128(dz + ln * C::ZS + 16 * s + 8 * h), bw[s], acc);
+        bf16raw *sg = stage + w * kTile * SS;
 #pragma unroll
-    for (int k = 0; k < 2; ++k) {
-        const int row = (lane >> 2) + 16 * k, ch = lane & 3;
-        const u32x4 piece = *reinterpret_cast<const u32x4 *>(sg + row * SS + 8 * ch);
-        if (row < nvalid) *reinterpret_cast<u32x4 *>(dX + (t0 + row) * C::D + 32 * nt + 8 * ch) = piece;
+        for (int v = 0; v < 16; ++v) sg[acc_row(v, h) * SS + ln] = static_cast<bf16raw>(pack2(acc[v], 0.f) & 0xffffu);
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            const int row = (lane >> 2) + 16 * kk, ch = lane & 3;
+            const u32x4 piece = *reinterpret_cast<const u32x4 *>(sg + row * SS + 8 * ch);
+            if (row < nvalid) *reinterpret_cast<u32x4 *>(dX + (t0 + row) * C::D + 32 * nt + 8 * ch) = piece;
+        }
     }
 }
 

@@ -176,7 +176,8 @@ struct StreamLds {
     static constexpr int wp = 0;                                        // [LPP][XS] bf16
     static constexpr int y = wp + C::LPP * C::XS * 2;                   // [32][XS] bf16: accumulated rows
     static constexpr int mass = y + kTile * C::XS * 2;                  // [LR] fp32: bucket masses A before this tile
-    static constexpr int area = (mass + C::LR * 4 + 255) & ~255;        // start of the aliased area
+    static constexpr int dnp = mass + C::LR * 4;                        // [4][2][32] fp32: mass read-outs per reader wavefront and lane half
+    static constexpr int area = (dnp + 4 * 2 * kTile * 4 + 255) & ~255; // start of the aliased area
     // phase A (production, contraction)
     static constexpr int xr = area;                                     // [32][XS] reader rows
     static constexpr int xw = xr + kTile * C::XS * 2;                   // [32][XS] writer rows
@@ -184,7 +185,7 @@ struct StreamLds {
     static constexpr int phw = phr + kTile * C::PS * 2;                 // [32][PS] writer assignments
     static constexpr int endA = phw + kTile * C::PS * 2;
     // phase B (reduction over the four bucket-row groups) reuses the same bytes
-    static constexpr int RS = C::D + 4;                                 // fp32 row stride: D numerators, 3 normaliser parts
+    static constexpr int RS = C::D + 4;                                 // fp32 row stride: D numerators, 1 normaliser part
     static constexpr int red = area;                                    // [4][32][RS] fp32
     static constexpr int endB = red + kRowGroups * kTile * RS * 4;
     static constexpr int total = endA > endB ? endA : endB;
@@ -201,6 +202,7 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
     bf16raw *wp = reinterpret_cast<bf16raw *>(lds + S::wp);
     bf16raw *ytile = reinterpret_cast<bf16raw *>(lds + S::y);
     float *mass = reinterpret_cast<float *>(lds + S::mass);
+    float *dnp = reinterpret_cast<float *>(lds + S::dnp);
     bf16raw *xr = reinterpret_cast<bf16raw *>(lds + S::xr);
     bf16raw *xw = reinterpret_cast<bf16raw *>(lds + S::xw);
     bf16raw *phr = reinterpret_cast<bf16raw *>(lds + S::phr);
@@ -279,7 +281,9 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
             const int side = w / 4, g = w % C::NG, jq = (w % 4) / C::NG;
             if (side == 0) {
                 const f32x16 z = project<C>(wp, xr, g, ln, h);
-                write_assignments<C>(z, g, ln, h, a.beta, true, phr, jq, C::JSTEP);
+                const float dnl = write_assignments<C>(z, g, ln, h, a.beta, true, phr, jq, C::JSTEP, 0, 1 << C::PHI,
+                                                       MODE == kForward ? mass : nullptr);
+                if (MODE == kForward) dnp[w * 64 + lane] = dnl;       // this lane's tables' share of the normaliser
             } else if (intra) {
                 const f32x16 z = project<C>(wp, xw, g, ln, h);
                 write_assignments<C>(z, g, ln, h, a.beta, ln < nvalid, phw, jq, C::JSTEP);
@@ -346,24 +350,6 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
                 }
             }
         }
-        // ---- read-out of the bucket masses for the normaliser (every column of dn holds the same value);
-        //      a second pass over the reader operands so that its accumulator can reuse dead registers;
-        //      the two column groups split the row group's tiles
-        f32x16 dn = {0};
-        if (MODE == kForward) {
-#pragma unroll
-            for (int mt = 0; mt < C::MT; ++mt) {
-                if ((mt & 1) != cg) continue;
-#pragma unroll
-                for (int s = 0; s < 2; ++s) {
-                    const int rr = r_own + 32 * mt + 16 * s + 4 * h;
-                    const u32x4 ar = lds64x2(phr + ln * C::PS + rr, phr + ln * C::PS + rr + 8);
-                    const float4 m0 = *reinterpret_cast<const float4 *>(mass + rr);
-                    const float4 m1 = *reinterpret_cast<const float4 *>(mass + rr + 8);
-                    dn = mma(ar, u32x4{pack2(m0.x, m0.y), pack2(m0.z, m0.w), pack2(m1.x, m1.y), pack2(m1.z, m1.w)}, dn);
-                }
-            }
-        }
         // the next tile's loads fly during the reduction and the epilogue (few registers are live there)
         if (it + 1 < ntiles) fetch(it + 1);
         RACE_PHASE(5)
@@ -379,12 +365,8 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
                 red[rbase + (8 * (v >> 2) + (v & 3)) * S::RS + c_own + 32 * nt + ln] = out[nt][v];
         }
         if (MODE == kForward) {
-            // normaliser parts: columns D + cg (mass read-out of this column group's tiles), D + 2 (in-tile row sums)
-            if (ln == 0) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) red[rbase + (8 * (v >> 2) + (v & 3)) * S::RS + C::D + cg] = dn[v];
-            }
-            if (cg == 0 && h == 0) red[(rg * kTile + ln) * S::RS + C::D + 2] = rowsum;
+            // in-tile part of the normaliser: row sums of the masked kernel values (partial over this row group)
+            if (cg == 0 && h == 0) red[(rg * kTile + ln) * S::RS + C::D] = rowsum;
             // masses after this tile, for the next tile's read-out
 #pragma unroll
             for (int mt = 0; mt < C::MT; ++mt) {
@@ -412,7 +394,7 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
                     const float4 p4 = *reinterpret_cast<const float4 *>(src + c0 + c);
                     acc[c] += p4.x; acc[c + 1] += p4.y; acc[c + 2] += p4.z; acc[c + 3] += p4.w;
                 }
-                if (MODE == kForward) e += (src[C::D] + src[C::D + 1]) + src[C::D + 2];
+                if (MODE == kForward) e += src[C::D] + (dnp[gg * 64 + tok] + dnp[gg * 64 + 32 + tok]);
             }
             if (tok < nvalid) {
                 const float scale = (MODE == kForward) ? 1.0f / e : 1.0f;
@@ -608,7 +590,7 @@ hipError_t launch_grad(const Plan &p, KArgs a, const void *Q, const void *K, con
     }
     {
         ProfileScope prof("dz_matmul", st);
-        hipLaunchKernelGGL(dz_matmul_kernel<C>, dim3(static_cast<unsigned>((p.N + kTile - 1) / kTile), p.BH),
+        hipLaunchKernelGGL(dz_matmul_kernel<C>, dim3(static_cast<unsigned>((p.N + kTile * kDzTiles - 1) / (kTile * kDzTiles)), p.BH),
                            dim3(64 * C::NT), 0, st, a, a.dZ, static_cast<bf16raw *>(dX));
         RACE_TRY(hipGetLastError());
     }
