@@ -42,8 +42,9 @@ def kernel_shares(w):
     return {
         "stream_forward": proj + 2 * U,      # projections, accumulate, read-out
         "stream_grad_v": proj + 2 * U,       # projections again, cotangent statistics, dV read-out
-        "grad_q": proj / 2 + U,              # dphi_Q and W^T dz for Q
-        "grad_k": proj / 2 + U,              # dphi_K and W^T dz for K
+        "grad_q": U,                         # dphi_Q and the chain rule through the soft assignment
+        "grad_k": U,                         # dphi_K, same
+        "dz_matmul": proj / 2,               # dX = dZ . W, launched once for dQ and once for dK
         "stream_totals_kv": 0.0, "stream_totals_qg": 0.0, "segment_scan": 0.0,
     }
 
@@ -52,7 +53,7 @@ def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="C5")
     ap.add_argument("--tokens", type=int, default=0, help="override N of the workload")
     ap.add_argument("--cpu-sample-tokens", type=int, default=196608)
