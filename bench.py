@@ -49,6 +49,17 @@ def kernel_shares(w):
     }
 
 
+# HBM bytes per token-head and launch, measured with rocprofv3 --pmc FETCH_SIZE and --pmc WRITE_SIZE (two runs of
+# this script at C5, each counter scaled by what it reads for the library's plain copy kernel of 1 GiB: 2.000 and
+# 1.000); valid for the shape they were measured on.
+MEASURED_TRAFFIC = {
+    ("bf16", 128, 8, 6, True): {
+        "stream_totals_kv": 514.7, "segment_scan": 5.4, "stream_forward": 1030.7, "stream_totals_qg": 774.7,
+        "stream_grad_v": 1030.6, "grad_q": 2698.6, "dz_matmul": 384.2, "grad_k": 2698.6,
+    },
+}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -58,6 +69,8 @@ def main() -> int:
     ap.add_argument("--tokens", type=int, default=0, help="override N of the workload")
     ap.add_argument("--cpu-sample-tokens", type=int, default=196608)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="before the warm-up, run one plain copy kernel of this many MiB (scale for byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.stderr.write("bench.py: this build runs on one GPU; --gpus %d is not supported "
@@ -95,6 +108,13 @@ def main() -> int:
         ra.race_attn_fwd(desc, Q, K, V, seeds, O=O, den=den, workspace=ws)
         ra.race_attn_bwd(desc, Q, K, V, O, den, dO, seeds, dQ=dQ, dK=dK, dV=dV, workspace=ws)
 
+    if args.calibration_copy_mib:
+        src = torch.randint(0, 256, (args.calibration_copy_mib << 20,), dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        ra.race_attn_calibration_copy(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -125,8 +145,10 @@ def main() -> int:
         avg_s = 1e-3 * prof[name][0] / prof[name][1]
         flops = shares.get(name, 0.0) * token_heads
         achieved = flops / avg_s / 1e12
+        measured = MEASURED_TRAFFIC.get((w.dtype, w.d, w.L, w.P, bool(w.causal)), {}).get(name)
+        traffic = measured * token_heads if measured is not None else None      # bytes per launch
         roofline = {"kernel": name, "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_FLOPS / 1e12,
-                    "unit": "TFLOP/s", "frac": achieved / (PEAK_BF16_FLOPS / 1e12), "traffic": None,
+                    "unit": "TFLOP/s", "frac": achieved / (PEAK_BF16_FLOPS / 1e12), "traffic": traffic,
                     "avg_launch_ms": 1e3 * avg_s, "algorithmic_flops_per_launch": flops}
 
     cpu_baseline = None

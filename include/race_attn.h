@@ -136,6 +136,12 @@ int race_attn_kernel_family(const race_attn_desc_t *desc);
 void race_attn_profile_enable(int on);
 int race_attn_profile_read(int max_entries, const char **names, float *total_ms, int *launches);
 
+/* Benchmark aid (no passage of the paper; callers: counter calibration).  Copies `bytes` bytes (a multiple
+ * of 16) from src to dst (DEVICE pointers, 16-byte aligned, not overlapping) with one plain grid-stride kernel
+ * named calibration_copy_kernel that reads every byte once and writes every byte once: a dispatch of known HBM
+ * traffic against which hardware byte counters of the other kernels are scaled.  bytes == 0 is a no-op. */
+race_status_t race_attn_calibration_copy(void *dst, const void *src, size_t bytes, race_stream_t stream);
+
 #ifdef __cplusplus
 }
 #endif

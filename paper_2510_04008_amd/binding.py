@@ -63,6 +63,8 @@ def lib() -> ctypes.CDLL:
         L.race_attn_profile_read.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_char_p),
                                              ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int)]
         L.race_attn_profile_read.restype = ctypes.c_int
+        L.race_attn_calibration_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+        L.race_attn_calibration_copy.restype = ctypes.c_int
         L.race_status_string.argtypes = [ctypes.c_int]
         L.race_status_string.restype = ctypes.c_char_p
         L.race_attn_last_error.argtypes = []
@@ -197,6 +199,16 @@ def race_attn_debug_buckets(desc: RaceAttnDesc, K, V, proj_seeds: Sequence[int],
     if st != RACE_OK:
         raise RaceAttnError(st, "race_attn_debug_buckets")
     return A, Bsum
+
+
+def race_attn_calibration_copy(dst, src, stream=None) -> None:
+    """Plain device copy of src into dst (equal byte sizes, a multiple of 16) by one kernel of known traffic."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("dst and src differ in size")
+    st = lib().race_attn_calibration_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream(stream))
+    if st != RACE_OK:
+        raise RaceAttnError(st, "race_attn_calibration_copy")
 
 
 def race_attn_profile_enable(on: bool) -> None:

@@ -53,6 +53,9 @@ struct ProfileScope {
     hipStream_t st_;
 };
 
+// Plain copy of known size (simple_kernels.hip); bytes is a multiple of 16.
+hipError_t calibration_copy(void *dst, const void *src, size_t bytes, hipStream_t st);
+
 // ---- simple family (simple_kernels.hip)
 hipError_t simple_fwd(const Plan &p, const void *Q, const void *K, const void *V, void *O, float *den,
                       char *ws, hipStream_t st);

@@ -382,6 +382,23 @@ const char *race_status_string(race_status_t status)
 
 const char *race_attn_last_error(void) { return g_last_error.c_str(); }
 
+race_status_t race_attn_calibration_copy(void *dst, const void *src, size_t bytes, race_stream_t stream)
+{
+    if (bytes == 0) return RACE_OK;
+    if (!dst || !src || bytes % 16 != 0) return RACE_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(dst) % 16 != 0 || reinterpret_cast<uintptr_t>(src) % 16 != 0)
+        return RACE_ERR_INVALID_ARG;
+    const char *a = static_cast<const char *>(src);
+    const char *b = static_cast<const char *>(dst);
+    if (a < b + bytes && b < a + bytes) return RACE_ERR_INVALID_ARG;
+    hipError_t e = calibration_copy(dst, src, bytes, reinterpret_cast<hipStream_t>(stream));
+    if (e != hipSuccess) {
+        g_last_error = std::string("calibration_copy: ") + hipGetErrorString(e);
+        return RACE_ERR_HIP;
+    }
+    return RACE_OK;
+}
+
 void race_attn_profile_enable(int on)
 {
     g_profile_on = on != 0;

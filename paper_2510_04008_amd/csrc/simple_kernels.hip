@@ -619,4 +619,22 @@ hipError_t simple_buckets(const Plan &p, const void *K, const void *V, float *A,
     return hipGetLastError();
 }
 
+// One 16-byte load and one 16-byte store per element, grid-stride: every byte is read once and written once.
+__global__ void __launch_bounds__(256) calibration_copy_kernel(uint4 *__restrict__ dst, const uint4 *__restrict__ src,
+                                                                size_t n16)
+{
+    const size_t stride = static_cast<size_t>(gridDim.x) * blockDim.x;
+    for (size_t i = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+hipError_t calibration_copy(void *dst, const void *src, size_t bytes, hipStream_t st)
+{
+    const size_t n16 = bytes / 16;
+    const size_t want = (n16 + 255) / 256;
+    const unsigned blocks = static_cast<unsigned>(want < 16384 ? (want ? want : 1) : 16384);
+    hipLaunchKernelGGL(calibration_copy_kernel, dim3(blocks), dim3(256), 0, st, static_cast<uint4 *>(dst),
+                       static_cast<const uint4 *>(src), n16);
+    return hipGetLastError();
+}
+
 }  // namespace race

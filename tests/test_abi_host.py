@@ -116,3 +116,15 @@ def test_projection_expansion_is_bit_identical_to_the_oracle(H, L, P, d, dtype):
     for h in range(H):
         ref = ro.expand_projection(seeds[h], L, P, d, round_bf16=(dtype == ra.RACE_BF16)).astype(np.float32)
         assert np.array_equal(W[h].view(np.uint32), ref.view(np.uint32))
+
+
+def test_calibration_copy_rejects_bad_arguments_on_the_host():
+    lib = ra.lib()
+    buf = ctypes.create_string_buffer(4096 + 64)
+    base = (ctypes.addressof(buf) + 63) // 64 * 64
+    assert lib.race_attn_calibration_copy(None, None, 0, None) == ra.RACE_OK            # nothing to copy
+    assert lib.race_attn_calibration_copy(None, base, 64, None) == ra.RACE_ERR_INVALID_ARG
+    assert lib.race_attn_calibration_copy(base, None, 64, None) == ra.RACE_ERR_INVALID_ARG
+    assert lib.race_attn_calibration_copy(base + 1024, base, 24, None) == ra.RACE_ERR_INVALID_ARG   # not a multiple of 16
+    assert lib.race_attn_calibration_copy(base + 1028, base, 64, None) == ra.RACE_ERR_INVALID_ARG   # misaligned
+    assert lib.race_attn_calibration_copy(base + 32, base, 64, None) == ra.RACE_ERR_INVALID_ARG     # overlapping

@@ -126,3 +126,13 @@ def test_empty_sequence_and_error_reporting():
     x = torch.zeros((1, 1, 64, 16), device="cuda")
     with pytest.raises(ra.RaceAttnError):
         ra.race_attn_fwd(d, x, x, x, [1], workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+
+
+@pytest.mark.gpu
+def test_calibration_copy_copies():
+    import torch
+    src = torch.randint(0, 255, (3 * 1024 * 1024 + 16,), dtype=torch.uint8, device="cuda:0")
+    dst = torch.zeros_like(src)
+    ra.race_attn_calibration_copy(dst, src)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
