@@ -38,16 +38,27 @@ template <class C>
 struct GradCfg {
     static constexpr int TSPLIT = C::LR / (32 * kWaves);                // workgroups per (segment, head)
     static constexpr int NGW = C::NG / TSPLIT;                          // projection groups per workgroup
-    static constexpr int RW = kWaves / NGW;                             // wavefronts per projection group
-    static constexpr int JW = C::TPL < RW ? C::TPL : RW;                // ... split over the lane's tables
-    static constexpr int AW = RW / JW;                                  // ... and over the high-bit index
-    static constexpr int AN = (1 << C::PHI) / AW;                       // high-bit indices per wavefront
     static constexpr int ROWS = C::LR / TSPLIT;                         // bucket rows per workgroup
+    static constexpr int TABLES = NGW * C::TPG;                         // tables per workgroup
+    // a wavefront's 32 bucket rows are TW whole tables (R <= 32) or a 1/WPT share of one table (R > 32)
+    static constexpr int TW = C::R >= 32 ? 1 : 32 / C::R;               // tables per wavefront
+    static constexpr int WPT = C::R >= 32 ? C::R / 32 : 1;              // wavefronts per table
+    static constexpr int KM = (C::R >= 32 ? 32 : C::R) / 8;             // groups of 8 corners per table and wavefront
+    static constexpr int MB = KM == 4 ? 2 : (KM == 2 ? 1 : 0);          // corner bits 3.. that vary inside a wavefront
     static_assert(TSPLIT >= 1 && C::NG % TSPLIT == 0 && kWaves % NGW == 0, "table split");
-    static_assert(AW >= 1 && AN >= 1 && AN * AW == (1 << C::PHI), "assignment split");
     static_assert(NGW * C::TPG * C::R == ROWS, "a workgroup's rows are the tables of its projection groups");
-    static_assert(AW == 1 || (C::TPL == JW && C::P <= 7), "the split backward pass handles one table per wavefront");
-    static_assert(NGW * C::TPL <= kWaves && NGW + 1 <= kWaves, "production roles must fit the wavefronts");
+    static_assert(C::P >= 3 && C::P <= 7, "corner bits 0..2 are register/lane bits; a partial record is P+1 <= 8 floats");
+    // production roles.  Writer hashing: one wavefront per (projection group, table of the lane, share of the
+    // high-bit indices); reader masses: one per (projection group, table of the lane) if there is room, else one
+    // per projection group; one wavefront for the in-tile term.  If they do not all fit, the reader and in-tile
+    // roles double up on the last wavefronts.
+    static constexpr int AS = (C::PHI >= 1 && NGW * C::TPL * 2 + NGW + 1 <= kWaves) ? 2 : 1;
+    static constexpr int NW = NGW * C::TPL * AS;                        // writer wavefronts
+    static constexpr int RJ = (NW + NGW * C::TPL + 1 <= kWaves) ? C::TPL : 1;
+    static constexpr bool DISJ = NW + NGW * RJ + 1 <= kWaves;
+    static constexpr int RD0 = DISJ ? NW : kWaves - NGW * RJ;           // first reader wavefront
+    static constexpr int TT = DISJ ? NW + NGW * RJ : kWaves - 1 - NGW;  // in-tile term
+    static_assert(NW <= kWaves && NGW * RJ + 1 <= kWaves, "production roles must fit the wavefronts");
 };
 
 template <class C>
@@ -58,22 +69,16 @@ struct GradLds {
     static constexpr int dz = wp + C::LPP * C::XS * 2;                  // [32][DZS] bf16
     static constexpr int sr = dz + kTile * DZS * 2;                     // [32] fp32 extra column of reader-Y
     static constexpr int sw = sr + kTile * 4;                           // [32] fp32 extra column of writer-Y
-    static constexpr int zl = (sw + kTile * 4 + 15) & ~15;              // [NGW][64][16] fp32: reader projections
-    static constexpr int yr = zl + G::NGW * 64 * 16 * 4;                // [32][XS] reader-Y rows
+    static constexpr int PMS = 3 * C::PP;                               // floats per (table, token): p, q, sech^2, each padded
+    static constexpr int pm = (sw + kTile * 4 + 15) & ~15;              // [TABLES][32][PMS] fp32: per-bit masses of the reader
+    static constexpr int part = pm + G::TABLES * kTile * PMS * 4;       // [kWaves][32][8] fp32: partial (m, E_t) of table shares
+    static constexpr int yr = part + (G::WPT > 1 ? kWaves * kTile * 8 * 4 : 0);   // [32][XS] reader-Y rows
     static constexpr int ttop = yr + kTile * C::XS * 2;                 // [2][64] x 16 B: masked in-tile term as MFMA operands
-    static constexpr int area = (ttop + 2 * 64 * 16 + 255) & ~255;
-    // phase A
-    static constexpr int xr = area;                                     // [32][XS]
+    static constexpr int xr = (ttop + 2 * 64 * 16 + 255) & ~255;        // [32][XS]
     static constexpr int xw = xr + kTile * C::XS * 2;
     static constexpr int yw = xw + kTile * C::XS * 2;                   // writer-Y rows
     static constexpr int phw = yw + kTile * C::XS * 2;                  // [32][PS] writer assignments
-    static constexpr int endA = phw + kTile * C::PS * 2;
-    // phase B
-    static constexpr int DS = G::ROWS + 4;                              // fp32 row stride
-    static constexpr int dphi = area;                                   // [32][DS] fp32
-    static constexpr int part = dphi + kTile * DS * 4;                  // [AW-1][NGW*JW][64][8] fp32: partial sums
-    static constexpr int endB = part + (G::AW - 1) * G::NGW * G::JW * 64 * 8 * 4;
-    static constexpr int total = endA > endB ? endA : endB;
+    static constexpr int total = phw + kTile * C::PS * 2;
     static_assert(total <= 160 * 1024, "LDS budget");
 };
 
@@ -89,13 +94,12 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
     bf16raw *dz = reinterpret_cast<bf16raw *>(lds + S::dz);
     float *sr = reinterpret_cast<float *>(lds + S::sr);
     float *sw = reinterpret_cast<float *>(lds + S::sw);
-    float *zl = reinterpret_cast<float *>(lds + S::zl);
+    float *pm = reinterpret_cast<float *>(lds + S::pm);
     bf16raw *yr = reinterpret_cast<bf16raw *>(lds + S::yr);
     bf16raw *xr = reinterpret_cast<bf16raw *>(lds + S::xr);
     bf16raw *xw = reinterpret_cast<bf16raw *>(lds + S::xw);
     bf16raw *yw = reinterpret_cast<bf16raw *>(lds + S::yw);
     bf16raw *phw = reinterpret_cast<bf16raw *>(lds + S::phw);
-    float *dphi = reinterpret_cast<float *>(lds + S::dphi);
     float *part = reinterpret_cast<float *>(lds + S::part);
     u32x4 *ttop = reinterpret_cast<u32x4 *>(lds + S::ttop);
 
@@ -105,9 +109,9 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
     const int th = blockIdx.z;                       // which share of the tables this workgroup owns
     const int r_base = th * G::ROWS;                 // its first bucket row
     const int r_own = r_base + w * 32;               // this wavefront's 32 bucket rows
-    // production share: projection group g; tables j = jq, jq + JW, ... of the lane; high-bit indices [a0, a0 + AN)
-    const int gl = w % G::NGW, g = th * G::NGW + gl;
-    const int jq = (w / G::NGW) % G::JW, aq = (w / G::NGW) / G::JW, a0 = aq * G::AN;
+    // backward pass through the soft assignment: the tables (or the share of one table) behind this wavefront's rows
+    const int tl0 = (w * 32) / C::R;                 // first table, counted inside the workgroup
+    const int ro = (w * 32) % C::R;                  // first corner of the share (0 unless a table spans several wavefronts)
     const bool intra = a.causal;
 
     const size_t base = static_cast<size_t>(bh) * a.N * C::D;
@@ -179,22 +183,38 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
         split_bf16(sr[ln], sr_hi, sr_lo);
         const u32x4 sr_a = (h == 0) ? u32x4{pack2(sr_hi, sr_hi), pack2(sr_lo, 0.f), 0u, 0u} : u32x4{0u, 0u, 0u, 0u};
 
-        // ---- production, by role: the first NGW*TPL wavefronts hash the writer's tables; the last NGW
-        //      project the reader (kept for the backward pass through the soft assignment); one more forms
-        //      the in-tile term T^T[b][a] = Yw_b . Yr_a + sw_b * sr_a, masked, as MFMA operands for everybody
-        if (intra && w < G::NGW * C::TPL) {
-            const int pg = w % G::NGW, pj = w / G::NGW;
+        // ---- production, by role (see GradCfg): writer wavefronts hash the writer's tables into phw; reader
+        //      wavefronts project the reader and leave its per-bit masses (p, q, sech^2) in pm for the backward
+        //      pass through the soft assignment; one more forms the in-tile term
+        //      T^T[b][a] = Yw_b . Yr_a + sw_b * sr_a, masked, as MFMA operands for everybody
+        if (intra && w < G::NW) {
+            const int pg = w % G::NGW, pj = (w / G::NGW) % C::TPL, as = w / (G::NGW * C::TPL);
+            constexpr int kShare = (1 << C::PHI) / G::AS;
             const f32x16 zw = project<C>(wp, xw, th * G::NGW + pg, ln, h);
-            write_assignments<C>(zw, th * G::NGW + pg, ln, h, a.beta, ln < nvalid, phw, pj, C::TPL);
+            write_assignments<C>(zw, th * G::NGW + pg, ln, h, a.beta, ln < nvalid, phw, pj, C::TPL, as * kShare,
+                                 (as + 1) * kShare);
         }
-        if (w >= kWaves - G::NGW) {
-            const int pg = kWaves - 1 - w;
+        if (w >= G::RD0 && w < G::RD0 + G::NGW * G::RJ) {
+            const int pg = (w - G::RD0) % G::NGW, rj = (w - G::RD0) / G::NGW;
             const f32x16 zr = project<C>(wp, xr, th * G::NGW + pg, ln, h);
-            float *zdst = zl + (pg * 64 + lane) * 16;
 #pragma unroll
-            for (int v = 0; v < 16; v += 4) *reinterpret_cast<float4 *>(zdst + v) = float4{zr[v], zr[v + 1], zr[v + 2], zr[v + 3]};
+            for (int j = 0; j < C::TPL; ++j) {
+                if ((th * G::NGW + pg) * C::TPG + h * C::TPL + j >= C::L) break;
+                if (j % G::RJ != rj) continue;
+                float p[C::PP], q[C::PP], s2[C::PP];
+#pragma unroll
+                for (int t = C::P; t < C::PP; ++t) p[t] = q[t] = s2[t] = 0.f;
+                bit_masses<C>(zr, j, a.beta, p, q, s2);
+                float *dst = pm + ((pg * C::TPG + h * C::TPL + j) * kTile + ln) * S::PMS;
+#pragma unroll
+                for (int t = 0; t < C::PP; t += 4) {
+                    *reinterpret_cast<float4 *>(dst + t) = float4{p[t], p[t + 1], p[t + 2], p[t + 3]};
+                    *reinterpret_cast<float4 *>(dst + C::PP + t) = float4{q[t], q[t + 1], q[t + 2], q[t + 3]};
+                    *reinterpret_cast<float4 *>(dst + 2 * C::PP + t) = float4{s2[t], s2[t + 1], s2[t + 2], s2[t + 3]};
+                }
+            }
         }
-        if (intra && w == kWaves - 1 - G::NGW) {
+        if (intra && w == G::TT) {
             f32x16 tt = {0};
             const int yo = opaque(ln * C::XS + 8 * h);
 #pragma unroll
@@ -216,20 +236,23 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
         GRAD_PHASE(2)
         __syncthreads();
         GRAD_PHASE(3)
+        // the next tile's loads are issued a whole step ahead and fly during everything below
+        if (it + 1 < ntiles) fetch(it + 1);
         GRAD_PHASE(4)
-        // ---- cotangent of the reader's assignments for this wavefront's 32 bucket rows
+        // ---- cotangent of the reader's assignments, transposed: lane = token, register v = bucket row
+        //      r_own + acc_row(v, h) of this wavefront
         f32x16 dP;
         {
             // extra column first: sr_a * (A or dA)[r] with the masses before this tile
             float m_hi, m_lo;
             split_bf16(macc + __shfl_xor(macc, 32, 64), m_hi, m_lo);
             const u32x4 mb = (h == 0) ? u32x4{pack2(m_hi, m_lo), pack2(m_hi, 0.f), 0u, 0u} : u32x4{0u, 0u, 0u, 0u};
-            dP = mma(sr_a, mb, f32x16{0});
+            dP = mma(mb, sr_a, f32x16{0});
         }
         if (intra) {
 #pragma unroll
             for (int s = 0; s < 2; ++s)
-                dP = mma(ttop[64 * s + lane], lds_tr_acc(phw, C::PS, 16 * s, r_own, ln, h), dP);
+                dP = mma(lds_tr_acc(phw, C::PS, 16 * s, r_own, ln, h), ttop[64 * s + lane], dP);
         }
         {
             const int yo = opaque(ln * C::XS + 4 * h);
@@ -238,11 +261,69 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
 #pragma unroll
                 for (int s = 0; s < 2; ++s) {
                     const int cc = 32 * mtc + 16 * s;
-                    dP = mma(lds64x2(yr + yo + cc, yr + yo + cc + 8), acc_operand(ST[mtc], s), dP);
+                    dP = mma(acc_operand(ST[mtc], s), lds64x2(yr + yo + cc, yr + yo + cc + 8), dP);
                 }
             }
         }
         GRAD_PHASE(5)
+
+        // ---- back through the corner softmax (Algorithm 1, step 4), in the accumulator's own registers:
+        //      with w_c = phi_c dphi_c over the corners c of a table, m = sum_c w_c and E_t = sum_c v_{c,t} w_c.
+        //      Register v of lane half h is corner  co + 8 (v/4 mod KM) + 4h + v%4  of table tl0 + v/(4 KM):
+        //      bits 0,1 come from v, bit 2 from h, bits 3.. from v, bits above from the wavefront's share.
+        //      phi_c is the product over bits of p_t (bit set) or q_t (Section 3.3: the corner softmax factorises).
+        float rec[G::TW][8];           // [m, E_0 .. E_{P-1}] of the lane's token, per table of the wavefront
+#pragma unroll
+        for (int tw = 0; tw < G::TW; ++tw) {
+            const float *src = pm + ((tl0 + tw) * kTile + ln) * S::PMS;
+            float p[C::PP], q[C::PP];
+#pragma unroll
+            for (int t = 0; t < C::PP; t += 4) {
+                const float4 p4 = *reinterpret_cast<const float4 *>(src + t);
+                const float4 q4 = *reinterpret_cast<const float4 *>(src + C::PP + t);
+                p[t] = p4.x; p[t + 1] = p4.y; p[t + 2] = p4.z; p[t + 3] = p4.w;
+                q[t] = q4.x; q[t + 1] = q4.y; q[t + 2] = q4.z; q[t + 3] = q4.w;
+            }
+            float F = h ? p[2] : q[2];
+#pragma unroll
+            for (int t = 3 + G::MB; t < C::P; ++t) F *= ((ro >> t) & 1) ? p[t] : q[t];
+            const float Fl[4] = {F * q[0] * q[1], F * p[0] * q[1], F * q[0] * p[1], F * p[0] * p[1]};
+            float m = 0.f, E0 = 0.f, E1 = 0.f, Em[2] = {0.f, 0.f};
+#pragma unroll
+            for (int k = 0; k < G::KM; ++k) {
+                float mid = 1.f;
+#pragma unroll
+                for (int b = 0; b < G::MB; ++b) mid *= ((k >> b) & 1) ? p[3 + b] : q[3 + b];
+                const int v0 = 4 * (tw * G::KM + k);
+                const float w0 = Fl[0] * dP[v0], w1 = Fl[1] * dP[v0 + 1], w2 = Fl[2] * dP[v0 + 2], w3 = Fl[3] * dP[v0 + 3];
+                const float s01 = w0 + w1, s23 = w2 + w3;
+                const float c = mid * (s01 + s23);
+                E0 = fmaf(mid, (w1 - w0) + (w3 - w2), E0);
+                E1 = fmaf(mid, s23 - s01, E1);
+                m += c;
+#pragma unroll
+                for (int b = 0; b < G::MB; ++b) Em[b] += ((k >> b) & 1) ? c : -c;
+            }
+            // the two lane halves hold the two values of bit 2
+            const float mo = __shfl_xor(m, 32, 64);
+            const float mt = m + mo;
+            rec[tw][0] = mt;
+            rec[tw][1] = E0 + __shfl_xor(E0, 32, 64);
+            rec[tw][2] = E1 + __shfl_xor(E1, 32, 64);
+            rec[tw][3] = h ? m - mo : mo - m;
+#pragma unroll
+            for (int b = 0; b < G::MB; ++b) rec[tw][4 + b] = Em[b] + __shfl_xor(Em[b], 32, 64);
+#pragma unroll
+            for (int t = 3 + G::MB; t < C::P; ++t) rec[tw][1 + t] = ((ro >> t) & 1) ? mt : -mt;
+#pragma unroll
+            for (int t = C::P + 1; t < 8; ++t) rec[tw][t] = 0.f;
+        }
+        if (G::WPT > 1 && ro != 0) {
+            // a later share of a table: hand the partial sums to the wavefront that owns the table's first share
+            float *dst = part + ((w * kTile + ln) * 8 + 4 * h);
+            *reinterpret_cast<float4 *>(dst) = float4{rec[0][4 * h], rec[0][4 * h + 1], rec[0][4 * h + 2], rec[0][4 * h + 3]};
+        }
+        GRAD_PHASE(10)
         // ---- statistics += Yw^T . phi_writer
         if (intra) {
 #pragma unroll
@@ -258,122 +339,44 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
             }
         }
         GRAD_PHASE(6)
-        __syncthreads();        // phase-A tiles are dead from here on
+        __syncthreads();        // partial sums are visible; the tiles of this step are dead from here on
         GRAD_PHASE(7)
 
-        // ---- hand the cotangents to the lanes that own (token, table)
-        {
-            const int dbase = opaque(4 * h * S::DS + (r_own - r_base) + ln);
+        // ---- finish per (token, table): du_t = beta (E_t - m (p_t - q_t)),  dz_t = du_t (1 - tanh^2 z_t);
+        //      lane half h' takes the padded projection slots 4h' .. 4h'+3
+        if (ro == 0) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) dphi[dbase + (8 * (v >> 2) + (v & 3)) * S::DS] = dP[v];
-        }
-        // the next tile's loads fly during the vector-ALU phases below (few registers are live here)
-        if (it + 1 < ntiles) fetch(it + 1);
-        GRAD_PHASE(8)
-        __syncthreads();
-        GRAD_PHASE(9)
-
-        // ---- back through the corner softmax and tanh (Algorithm 1, step 4):
-        //      with w_r = phi_r dphi_r, m = sum_r w_r, E_t = sum_r v_{r,t} w_r:
-        //      du_t = beta (E_t - m (p_t - q_t)),  dz_t = du_t (1 - tanh^2 z_t)
-        //      The R corners of a table are split over AW wavefronts by their high bits; wavefronts aq > 0
-        //      hand their partial sums (m, E_t) to wavefront aq == 0 of the same table through LDS.
-        float Efin[C::P + 1];          // aq == 0 only: E_t and m after combining (last table of the lane)
-        float p_k[C::P], q_k[C::P], s_k[C::P];
-        int jfin = -1;
+            for (int tw = 0; tw < G::TW; ++tw) {
+                if (4 * h >= C::PP) break;
+                const int tl = tl0 + tw;
 #pragma unroll
-        for (int j = 0; j < C::TPL; ++j) {
-            const int table = g * C::TPG + h * C::TPL + j;
-            if (table >= C::L) break;
-            if (j < jq || (j - jq) % G::JW != 0) continue;
-            constexpr int ZW = C::PP;                              // the table's slots are contiguous
-            f32x16 z = {0};
-            {
-                const float *zsrc = zl + (gl * 64 + lane) * 16 + ZW * j;
-#pragma unroll
-                for (int v = 0; v < ZW; v += 4) {
-                    const float4 z4 = *reinterpret_cast<const float4 *>(zsrc + v);
-                    z[ZW * j + v] = z4.x; z[ZW * j + v + 1] = z4.y; z[ZW * j + v + 2] = z4.z; z[ZW * j + v + 3] = z4.w;
-                }
-            }
-            float p[C::P], q[C::P], sech2[C::P], lo[1 << C::PLO], hi[1 << C::PHI];
-            bit_masses<C>(z, j, a.beta, p, q, sech2);
-            kron_factors<C>(p, q, lo, hi);
-            const int dsrc = opaque(ln * S::DS + (table * C::R - r_base));
-            float E[C::P];
-#pragma unroll
-            for (int t = 0; t < C::P; ++t) E[t] = 0.f;
-            float m = 0.f;
-#pragma unroll
-            for (int aa = 0; aa < (1 << C::PHI); ++aa) {
-                if (aa < a0 || aa >= a0 + G::AN) continue;
-                const float *src = dphi + dsrc + aa * 8;
-                const float4 d0 = *reinterpret_cast<const float4 *>(src);
-                const float4 d1 = *reinterpret_cast<const float4 *>(src + 4);
-                const float wv[8] = {hi[aa] * lo[0] * d0.x, hi[aa] * lo[1] * d0.y, hi[aa] * lo[2] * d0.z, hi[aa] * lo[3] * d0.w,
-                                     hi[aa] * lo[4] * d1.x, hi[aa] * lo[5] * d1.y, hi[aa] * lo[6] * d1.z, hi[aa] * lo[7] * d1.w};
-                const float s01 = wv[0] + wv[1], s23 = wv[2] + wv[3], s45 = wv[4] + wv[5], s67 = wv[6] + wv[7];
-                E[0] += ((wv[1] - wv[0]) + (wv[3] - wv[2])) + ((wv[5] - wv[4]) + (wv[7] - wv[6]));
-                if (C::PLO > 1) E[1] += (s23 - s01) + (s67 - s45);
-                const float s0123 = s01 + s23, s4567 = s45 + s67;
-                if (C::PLO > 2) E[2] += s4567 - s0123;
-                const float chunk = s0123 + s4567;
-                m += chunk;
-#pragma unroll
-                for (int t = 0; t < C::PHI; ++t) E[C::PLO + t] += ((aa >> t) & 1) ? chunk : -chunk;
-                RACE_SCHED_FENCE();
-            }
-            if (G::AW > 1 && aq > 0) {
-                float *dst = part + (((aq - 1) * G::NGW * G::JW + (w % (G::NGW * G::JW))) * 64 + lane) * 8;
-                *reinterpret_cast<float4 *>(dst) = float4{m, E[0], E[1], E[2]};
-                *reinterpret_cast<float4 *>(dst + 4) = float4{C::P > 3 ? E[3 % C::P] : 0.f, C::P > 4 ? E[4 % C::P] : 0.f,
-                                                              C::P > 5 ? E[5 % C::P] : 0.f, C::P > 6 ? E[6 % C::P] : 0.f};
-            }
-            if (G::AW == 1) {
-                // one wavefront sees the whole table: finish here
-                float dzv[ZW];
-#pragma unroll
-                for (int t = 0; t < ZW; ++t) dzv[t] = (t < C::P) ? a.beta * (E[t] - m * (p[t] - q[t])) * sech2[t] : 0.f;
-#pragma unroll
-                for (int t = 0; t < ZW; t += 4) {
-                    const int v = ZW * j + t;      // slot v of the projection accumulator is projection row acc_row(v, h)
-                    *reinterpret_cast<u32x2 *>(dz + ln * S::DZS + gl * 32 + 8 * (v >> 2) + 4 * h) =
-                        u32x2{pack2(dzv[t], dzv[t + 1]), pack2(dzv[t + 2], dzv[t + 3])};
-                }
-            } else {
-                jfin = j;
-                Efin[C::P] = m;
-#pragma unroll
-                for (int t = 0; t < C::P; ++t) { Efin[t] = E[t]; p_k[t] = p[t]; q_k[t] = q[t]; s_k[t] = sech2[t]; }
-            }
-        }
-        if (G::AW > 1) {
-            __syncthreads();
-            if (aq == 0 && jfin >= 0) {
-#pragma unroll
-                for (int o = 1; o < G::AW; ++o) {
-                    const float *src = part + (((o - 1) * G::NGW * G::JW + (w % (G::NGW * G::JW))) * 64 + lane) * 8;
+                for (int o = 1; o < G::WPT; ++o) {
+                    const float *src = part + ((w + o) * kTile + ln) * 8;
                     const float4 p0 = *reinterpret_cast<const float4 *>(src);
                     const float4 p1 = *reinterpret_cast<const float4 *>(src + 4);
-                    const float pe[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
-                    Efin[C::P] += pe[0];
-#pragma unroll
-                    for (int t = 0; t < C::P; ++t) Efin[t] += pe[1 + t];
+                    rec[tw][0] += p0.x; rec[tw][1] += p0.y; rec[tw][2] += p0.z; rec[tw][3] += p0.w;
+                    rec[tw][4] += p1.x; rec[tw][5] += p1.y; rec[tw][6] += p1.z; rec[tw][7] += p1.w;
                 }
-                constexpr int ZW = C::PP;
-                float dzv[ZW];
+                const float *src = pm + (tl * kTile + ln) * S::PMS + 4 * h;
+                const float4 p4 = *reinterpret_cast<const float4 *>(src);
+                const float4 q4 = *reinterpret_cast<const float4 *>(src + C::PP);
+                const float4 s4 = *reinterpret_cast<const float4 *>(src + 2 * C::PP);
+                const float pq[4] = {p4.x - q4.x, p4.y - q4.y, p4.z - q4.z, p4.w - q4.w};
+                const float s2[4] = {s4.x, s4.y, s4.z, s4.w};
+                float dzv[4];
 #pragma unroll
-                for (int t = 0; t < ZW; ++t)
-                    dzv[t] = (t < C::P) ? a.beta * (Efin[t % C::P] - Efin[C::P] * (p_k[t % C::P] - q_k[t % C::P])) * s_k[t % C::P] : 0.f;
-#pragma unroll
-                for (int t = 0; t < ZW; t += 4) {
-                    const int v = ZW * jfin + t;
-                    *reinterpret_cast<u32x2 *>(dz + ln * S::DZS + gl * 32 + 8 * (v >> 2) + 4 * h) =
-                        u32x2{pack2(dzv[t], dzv[t + 1]), pack2(dzv[t + 2], dzv[t + 3])};
+                for (int e = 0; e < 4; ++e) {
+                    // E of slot 4h + e is rec[1 + 4h + e]; slot 7 is padding (P <= 7) and has no entry
+                    const float Et = h ? (e < 3 ? rec[tw][e < 3 ? 5 + e : 0] : 0.f) : rec[tw][1 + e];
+                    dzv[e] = a.beta * (Et - rec[tw][0] * pq[e]) * s2[e];       // padded slots: s2 = 0
                 }
+                // slot 4c.. of the lane-half hh's j-th table is projection row 8 (slots-per-table/4 * j + c) + 4 hh of its group
+                const int gl = tl / C::TPG, tg = tl % C::TPG, hh = tg / C::TPL, j = tg % C::TPL;
+                const int col = gl * 32 + 8 * ((C::PP / 4) * j + h) + 4 * hh;
+                *reinterpret_cast<u32x2 *>(dz + ln * S::DZS + col) = u32x2{pack2(dzv[0], dzv[1]), pack2(dzv[2], dzv[3])};
             }
         }
-        GRAD_PHASE(10)
+        GRAD_PHASE(9)
         __syncthreads();
         GRAD_PHASE(11)
 
@@ -385,8 +388,8 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
                     *reinterpret_cast<const u32x4 *>(dz + row * S::DZS + 8 * ch);
         }
         GRAD_PHASE(12)
-        __syncthreads();
-        GRAD_PHASE(1)
+        // no barrier here: the next step's loads-to-LDS touch none of dz, pm or part, and its production
+        // (which rewrites pm) comes after the next barrier
     }
     GRAD_PHASE_PRINT()
 }
