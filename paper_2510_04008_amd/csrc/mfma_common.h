@@ -15,7 +15,14 @@
 //   C/D      : column n, rows 8*(v/4) + 4h + v%4 for register v = 0..15.
 // An accumulator tile is fed back as a B operand without touching LDS: registers 8s..8s+7 of the
 // tile, packed to bf16, are the B operand of k-step s if k-slot (h, e) is taken to mean row
-// 16s + 8*(e/4) + 4h + e%4; the A operand is loaded with the same permutation (two 8-byte reads).
+// 16s + 8*(e/4) + 4h + e%4.  The other operand must use the same k order; tiles that are contracted
+// against such operands keep their feature dimension "pair-interleaved" in LDS (il()): inside every
+// group of 16 features the two middle blocks of 4 are swapped, so that the 8 features a lane needs
+// are one aligned 16-byte read.
+// LDS bank arithmetic as measured on gfx950 (64 banks of 4 bytes, 256 bytes per clock for reads: 16-byte
+// accesses go 16 lanes at a time, 8-byte ones 32 lanes): rows read 16 bytes per lane want a row stride of
+// 4 mod 64 words; tiles read through the transposing 8-byte loads (per 16 lanes 4 rows x 32 bytes, the
+// next 16 lanes 32 bytes further) want 16 mod 32 words.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -55,12 +62,15 @@ struct Cfg {
     static constexpr int PLO = P < 3 ? P : 3, PHI = P - PLO;
     static constexpr int CPR = D / 8;                   // 16-byte chunks per row
     // LDS row strides, in bf16 elements (rows stay 16-byte aligned; the pad staggers banks)
-    static constexpr int XS = D + 8;                    // [token][d] tiles and W rows
-    static constexpr int PS = LR + 8;                   // [token][L*R] assignment tiles
+    static constexpr int XS = D + 8;                    // [token][d] tiles and W rows, read by rows
+    static constexpr int YS = D + 32;                   // [token][d] tiles read through transposing loads
+    static constexpr int PS = LR + 8;                   // [token][L*R] assignment tiles, read by rows
+    static constexpr int PST = LR + 16;                 // ... read through transposing loads only (a compromise:
+                                                        // 16-byte row writes and transposing reads both 2-way at most)
     static constexpr int ZS = LPP + 8;                  // [token][padded projection] tiles
     static constexpr int STATE = LR * (D + 1);          // floats per saved state: B [LR][D] then A [LR]
     static_assert(LR % (32 * kRowGroups) == 0, "bucket rows must split into 32-row tiles per row group");
-    static_assert(D % 64 == 0 && R >= 8, "shape");
+    static_assert(D % 64 == 0 && P >= 4, "shape (assignments are written for pairs of high-bit indices)");
     static_assert(4 % NG == 0 && NG <= 4, "projection groups must divide four wavefronts");
 };
 
@@ -126,6 +136,8 @@ __device__ __forceinline__ float sum8(u32x4 v)
 }
 // row of accumulator register v for lane half h
 __device__ __forceinline__ int acc_row(int v, int h) { return 8 * (v >> 2) + 4 * h + (v & 3); }
+// pair-interleaved position of feature c: bits 2 and 3 of the index swapped
+__device__ __forceinline__ constexpr int il(int c) { return (c & ~12) | ((c & 4) << 1) | ((c & 8) >> 1); }
 
 // ---------------------------------------------------------------- transposing operand reads
 // MFMA operand whose k index runs along the ROWS of a row-major LDS tile M[k][n] (stride in elements):
@@ -135,23 +147,28 @@ __device__ __forceinline__ int acc_row(int v, int h) { return 8 * (v >> 2) + 4 *
 // lane that is column i of four consecutive rows.
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef s16x4 __attribute__((address_space(3))) lds_s16x4;
+// IL: the tile's columns are pair-interleaved (the chunk of logical columns 4c.. sits at 4 * swap(c)).
+template <bool IL = false>
 __device__ __forceinline__ u32x4 lds_tr8(const bf16raw *M, int stride, int k0a, int k0b, int n0, int ln)
 {
     const int sub = ln & 15;
-    const bf16raw *p = M + (sub >> 2) * stride + n0 + 16 * (ln >> 4) + 4 * (sub & 3);
+    const int chunk = IL ? (((sub & 1) << 1) | ((sub >> 1) & 1)) : (sub & 3);
+    const bf16raw *p = M + (sub >> 2) * stride + n0 + 16 * (ln >> 4) + 4 * chunk;
     const s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + k0a * stride));
     const s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + k0b * stride));
     const u32x2 ua = __builtin_bit_cast(u32x2, a), ub = __builtin_bit_cast(u32x2, b);
     return u32x4{ua.x, ua.y, ub.x, ub.y};
 }
 // k-slots in plain order (rows k0 + 8h + 0..7) or in accumulator order (pairs with acc_operand)
+template <bool IL = false>
 __device__ __forceinline__ u32x4 lds_tr_plain(const bf16raw *M, int stride, int k0, int n0, int ln, int h)
 {
-    return lds_tr8(M, stride, k0 + 8 * h, k0 + 8 * h + 4, n0, ln);
+    return lds_tr8<IL>(M, stride, k0 + 8 * h, k0 + 8 * h + 4, n0, ln);
 }
+template <bool IL = false>
 __device__ __forceinline__ u32x4 lds_tr_acc(const bf16raw *M, int stride, int k0, int n0, int ln, int h)
 {
-    return lds_tr8(M, stride, k0 + 4 * h, k0 + 8 + 4 * h, n0, ln);
+    return lds_tr8<IL>(M, stride, k0 + 4 * h, k0 + 8 + 4 * h, n0, ln);
 }
 
 // ---------------------------------------------------------------- global -> registers -> LDS tiles
@@ -174,13 +191,27 @@ __device__ __forceinline__ void fetch_rows(const bf16raw *X, int64_t t0, int nva
     }
 }
 
-template <class C, int ROWS>
+// One 16-byte chunk (columns 8ch .. 8ch+7) into row-major tile `dst` with row stride STRIDE; IL: pair-interleaved
+// columns (the chunk's two blocks of 4 land 8 positions apart).
+template <int STRIDE, bool IL>
+__device__ __forceinline__ void store_chunk(bf16raw *dst, int row, int ch, u32x4 v)
+{
+    if (IL) {
+        bf16raw *p = dst + row * STRIDE + 16 * (ch >> 1) + 4 * (ch & 1);
+        *reinterpret_cast<u32x2 *>(p) = u32x2{v.x, v.y};
+        *reinterpret_cast<u32x2 *>(p + 8) = u32x2{v.z, v.w};
+    } else {
+        *reinterpret_cast<u32x4 *>(dst + row * STRIDE + ch * 8) = v;
+    }
+}
+
+template <class C, int ROWS, int STRIDE = C::XS, bool IL = false>
 __device__ __forceinline__ void store_rows(const RowChunks<C, ROWS> &r, bf16raw *dst)
 {
 #pragma unroll
     for (int k = 0; k < RowChunks<C, ROWS>::N; ++k) {
         const int c = threadIdx.x + k * kThreads, row = c / C::CPR, ch = c % C::CPR;
-        if (row < ROWS) *reinterpret_cast<u32x4 *>(dst + row * C::XS + ch * 8) = r.v[k];
+        if (row < ROWS) store_chunk<STRIDE, IL>(dst, row, ch, r.v[k]);
     }
 }
 
@@ -204,7 +235,7 @@ __device__ __forceinline__ void fetch_cotangent(const bf16raw *dO, const bf16raw
     }
 }
 
-template <class C, int ROWS>
+template <class C, int ROWS, int STRIDE = C::XS, bool IL = false>
 __device__ __forceinline__ void store_cotangent(const CotChunks<C, ROWS> &r, bf16raw *dst, float *ge)
 {
 #pragma unroll
@@ -222,7 +253,7 @@ __device__ __forceinline__ void store_cotangent(const CotChunks<C, ROWS> &r, bf1
             dot = fmaf(g1, bf_hi(ow[e]), dot);
             out[e] = pack2(g0 * inv, g1 * inv);
         }
-        if (row < ROWS) *reinterpret_cast<u32x4 *>(dst + row * C::XS + ch * 8) = u32x4{out[0], out[1], out[2], out[3]};
+        if (row < ROWS) store_chunk<STRIDE, IL>(dst, row, ch, u32x4{out[0], out[1], out[2], out[3]});
         if (ge) {
             // the CPR threads of one row are consecutive lanes
 #pragma unroll
@@ -300,17 +331,20 @@ __device__ __forceinline__ void kron_factors(const float *p, const float *q, flo
     }
 }
 
-// Writes the assignment of the lane's token as bf16 into row `row` of ph [token][L*R].
+// Writes the assignment of the lane's token as bf16 into row `row` of ph [token][L*R] (row stride STRIDE),
+// corners pair-interleaved: the 16 corners of high-bit indices (a, a+1), a even, are stored as
+// [a: b 0..3 | a+1: b 0..3 | a: b 4..7 | a+1: b 4..7].
 // valid == false writes zeros (a token past the end of the sequence must not reach the statistics).
-// Only the lane's tables j = j0, j0 + jstep, ... and the high-bit indices a0 <= a < a1 are written, which
-// lets several wavefronts share the tables of one projection group.
-// If mass != null, returns sum_r phi[r] * mass[table*R + r] over what was written (the read-out of the
-// bucket masses A by this token, i.e. its share of the normaliser), else 0.
-template <class C>
+// Only the lane's tables j = j0, j0 + jstep, ... and the high-bit indices a0 <= a < a1 (both even) are
+// written, which lets several wavefronts share the tables of one projection group.
+// If mass != null (bucket masses in the same pair-interleaved order), returns sum_r phi[r] * mass[r] over
+// what was written (the read-out of the bucket masses A by this token, i.e. its share of the normaliser).
+template <class C, int STRIDE = C::PS>
 __device__ __forceinline__ float write_assignments(const f32x16 &z, int g, int row, int h, float beta, bool valid,
                                                    bf16raw *ph, int j0 = 0, int jstep = 1, int a0 = 0,
                                                    int a1 = 1 << C::PHI, const float *mass = nullptr)
 {
+    static_assert(C::PLO == 3 && C::PHI >= 1, "eight low corners per high-bit index, indices in pairs");
     float dn = 0.f;
 #pragma unroll
     for (int j = 0; j < C::TPL; ++j) {
@@ -321,21 +355,24 @@ __device__ __forceinline__ float write_assignments(const f32x16 &z, int g, int r
         bit_masses<C>(z, j, beta, p, q, nullptr);
         kron_factors<C>(p, q, lo, hi);
 #pragma unroll
-        for (int a = 0; a < (1 << C::PHI); ++a) {
+        for (int a = 0; a < (1 << C::PHI); a += 2) {
             if (a < a0 || a >= a1) continue;
-            const float ha = valid ? hi[a] : 0.f;
-            const int r0 = table * C::R + a * (1 << C::PLO);
-            float f[8];
+            const float ha = valid ? hi[a] : 0.f, hb = valid ? hi[a + 1] : 0.f;
 #pragma unroll
-            for (int b = 0; b < 8; ++b) f[b] = ha * lo[b];
-            if (mass) {
-                const float4 m0 = *reinterpret_cast<const float4 *>(mass + r0);
-                const float4 m1 = *reinterpret_cast<const float4 *>(mass + r0 + 4);
-                dn = fmaf(f[0], m0.x, dn); dn = fmaf(f[1], m0.y, dn); dn = fmaf(f[2], m0.z, dn); dn = fmaf(f[3], m0.w, dn);
-                dn = fmaf(f[4], m1.x, dn); dn = fmaf(f[5], m1.y, dn); dn = fmaf(f[6], m1.z, dn); dn = fmaf(f[7], m1.w, dn);
+            for (int half = 0; half < 2; ++half) {
+                const int pos = table * C::R + a * 8 + 8 * half;
+                float f[8];
+#pragma unroll
+                for (int b = 0; b < 4; ++b) { f[b] = ha * lo[4 * half + b]; f[4 + b] = hb * lo[4 * half + b]; }
+                if (mass) {
+                    const float4 m0 = *reinterpret_cast<const float4 *>(mass + pos);
+                    const float4 m1 = *reinterpret_cast<const float4 *>(mass + pos + 4);
+                    dn = fmaf(f[0], m0.x, dn); dn = fmaf(f[1], m0.y, dn); dn = fmaf(f[2], m0.z, dn); dn = fmaf(f[3], m0.w, dn);
+                    dn = fmaf(f[4], m1.x, dn); dn = fmaf(f[5], m1.y, dn); dn = fmaf(f[6], m1.z, dn); dn = fmaf(f[7], m1.w, dn);
+                }
+                *reinterpret_cast<u32x4 *>(ph + row * STRIDE + pos) =
+                    u32x4{pack2(f[0], f[1]), pack2(f[2], f[3]), pack2(f[4], f[5]), pack2(f[6], f[7])};
             }
-            *reinterpret_cast<u32x4 *>(ph + row * C::PS + r0) =
-                u32x4{pack2(f[0], f[1]), pack2(f[2], f[3]), pack2(f[4], f[5]), pack2(f[6], f[7])};
             RACE_SCHED_FENCE();
         }
     }

@@ -72,13 +72,13 @@ struct GradLds {
     static constexpr int PMS = 3 * C::PP;                               // floats per (table, token): p, q, sech^2, each padded
     static constexpr int pm = (sw + kTile * 4 + 15) & ~15;              // [TABLES][32][PMS] fp32: per-bit masses of the reader
     static constexpr int part = pm + G::TABLES * kTile * PMS * 4;       // [kWaves][32][8] fp32: partial (m, E_t) of table shares
-    static constexpr int yr = part + (G::WPT > 1 ? kWaves * kTile * 8 * 4 : 0);   // [32][XS] reader-Y rows
+    static constexpr int yr = part + (G::WPT > 1 ? kWaves * kTile * 8 * 4 : 0);   // [32][XS] reader-Y rows, pair-interleaved columns
     static constexpr int ttop = yr + kTile * C::XS * 2;                 // [2][64] x 16 B: masked in-tile term as MFMA operands
     static constexpr int xr = (ttop + 2 * 64 * 16 + 255) & ~255;        // [32][XS]
     static constexpr int xw = xr + kTile * C::XS * 2;
-    static constexpr int yw = xw + kTile * C::XS * 2;                   // writer-Y rows
-    static constexpr int phw = yw + kTile * C::XS * 2;                  // [32][PS] writer assignments
-    static constexpr int total = phw + kTile * C::PS * 2;
+    static constexpr int yw = xw + kTile * C::XS * 2;                   // [32][YS] writer-Y rows, pair-interleaved columns
+    static constexpr int phw = yw + kTile * C::YS * 2;                  // [32][PST] writer assignments
+    static constexpr int total = phw + kTile * C::PST * 2;
     static_assert(total <= 160 * 1024, "LDS budget");
 };
 
@@ -166,12 +166,12 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
         store_rows<C, kTile>(pre_r, xr);
         if (intra) store_rows<C, kTile>(pre_w, xw);
         if (SIDE == 0) {
-            store_cotangent<C, kTile>(pre_c, yr, sr);
-            if (intra) store_rows<C, kTile>(pre_v, yw);
+            store_cotangent<C, kTile, C::XS, true>(pre_c, yr, sr);
+            if (intra) store_rows<C, kTile, C::YS, true>(pre_v, yw);
             if (tid < kTile) sw[tid] = 1.f;
         } else {
-            store_rows<C, kTile>(pre_v, yr);
-            if (intra) store_cotangent<C, kTile>(pre_c, yw, sw);
+            store_rows<C, kTile, C::XS, true>(pre_v, yr);
+            if (intra) store_cotangent<C, kTile, C::YS, true>(pre_c, yw, sw);
             if (tid < kTile) sr[tid] = 1.f;
         }
         GRAD_PHASE(0)
@@ -191,7 +191,7 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
             const int pg = w % G::NGW, pj = (w / G::NGW) % C::TPL, as = w / (G::NGW * C::TPL);
             constexpr int kShare = (1 << C::PHI) / G::AS;
             const f32x16 zw = project<C>(wp, xw, th * G::NGW + pg, ln, h);
-            write_assignments<C>(zw, th * G::NGW + pg, ln, h, a.beta, ln < nvalid, phw, pj, C::TPL, as * kShare,
+            write_assignments<C, C::PST>(zw, th * G::NGW + pg, ln, h, a.beta, ln < nvalid, phw, pj, C::TPL, as * kShare,
                                  (as + 1) * kShare);
         }
         if (w >= G::RD0 && w < G::RD0 + G::NGW * G::RJ) {
@@ -216,9 +216,10 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
         }
         if (intra && w == G::TT) {
             f32x16 tt = {0};
-            const int yo = opaque(ln * C::XS + 8 * h);
+            // both tiles keep their columns in the same (pair-interleaved) order, which is all a contraction needs
+            const int yo = opaque(ln * C::XS + 8 * h), ywo = opaque(ln * C::YS + 8 * h);
 #pragma unroll
-            for (int s = 0; s < C::D / 16; ++s) tt = mma(lds128(yw + yo + 16 * s), lds128(yr + yo + 16 * s), tt);
+            for (int s = 0; s < C::D / 16; ++s) tt = mma(lds128(yw + ywo + 16 * s), lds128(yr + yo + 16 * s), tt);
             float sw_hi, sw_lo;
             split_bf16(sw[ln], sw_hi, sw_lo);
             const u32x4 sw_a = (h == 0) ? u32x4{pack2(sw_hi, sw_hi), pack2(sw_lo, 0.f), 0u, 0u} : u32x4{0u, 0u, 0u, 0u};
@@ -252,16 +253,16 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
         if (intra) {
 #pragma unroll
             for (int s = 0; s < 2; ++s)
-                dP = mma(lds_tr_acc(phw, C::PS, 16 * s, r_own, ln, h), ttop[64 * s + lane], dP);
+                dP = mma(lds_tr_acc<true>(phw, C::PST, 16 * s, r_own, ln, h), ttop[64 * s + lane], dP);
         }
         {
-            const int yo = opaque(ln * C::XS + 4 * h);
+            const int yo = opaque(ln * C::XS + 8 * h);       // pair-interleaved columns: one 16-byte read per k-step
 #pragma unroll
             for (int mtc = 0; mtc < C::NT; ++mtc) {
 #pragma unroll
                 for (int s = 0; s < 2; ++s) {
                     const int cc = 32 * mtc + 16 * s;
-                    dP = mma(acc_operand(ST[mtc], s), lds64x2(yr + yo + cc, yr + yo + cc + 8), dP);
+                    dP = mma(acc_operand(ST[mtc], s), lds128(yr + yo + cc), dP);
                 }
             }
         }
@@ -273,6 +274,7 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
         //      bits 0,1 come from v, bit 2 from h, bits 3.. from v, bits above from the wavefront's share.
         //      phi_c is the product over bits of p_t (bit set) or q_t (Section 3.3: the corner softmax factorises).
         float rec[G::TW][8];           // [m, E_0 .. E_{P-1}] of the lane's token, per table of the wavefront
+        auto soft_backward = [&]() {
 #pragma unroll
         for (int tw = 0; tw < G::TW; ++tw) {
             const float *src = pm + ((tl0 + tw) * kTile + ln) * S::PMS;
@@ -323,21 +325,26 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
             float *dst = part + ((w * kTile + ln) * 8 + 4 * h);
             *reinterpret_cast<float4 *>(dst) = float4{rec[0][4 * h], rec[0][4 * h + 1], rec[0][4 * h + 2], rec[0][4 * h + 3]};
         }
-        GRAD_PHASE(10)
+        };
+        auto update_statistics = [&]() {
         // ---- statistics += Yw^T . phi_writer
         if (intra) {
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
                 const float4 g0 = *reinterpret_cast<const float4 *>(sw + 16 * s + 8 * h);
                 const float4 g1 = *reinterpret_cast<const float4 *>(sw + 16 * s + 8 * h + 4);
-                const u32x4 bp = lds_tr_plain(phw, C::PS, 16 * s, r_own, ln, h);
+                const u32x4 bp = lds_tr_plain<true>(phw, C::PST, 16 * s, r_own, ln, h);
                 macc += bf_lo(bp.x) * g0.x + bf_hi(bp.x) * g0.y + bf_lo(bp.y) * g0.z + bf_hi(bp.y) * g0.w +
                         bf_lo(bp.z) * g1.x + bf_hi(bp.z) * g1.y + bf_lo(bp.w) * g1.z + bf_hi(bp.w) * g1.w;
 #pragma unroll
                 for (int mtc = 0; mtc < C::NT; ++mtc)
-                    ST[mtc] = mma(lds_tr_plain(yw, C::XS, 16 * s, 32 * mtc, ln, h), bp, ST[mtc]);
+                    ST[mtc] = mma(lds_tr_plain<true>(yw, C::YS, 16 * s, 32 * mtc, ln, h), bp, ST[mtc]);
             }
         }
+        };
+        soft_backward();
+        update_statistics();
+        GRAD_PHASE(10)
         GRAD_PHASE(6)
         __syncthreads();        // partial sums are visible; the tiles of this step are dead from here on
         GRAD_PHASE(7)

@@ -61,9 +61,9 @@ struct TotalsLds {
     static constexpr int TT = 64;
     static constexpr int wp = 0;                                        // [LPP][XS] bf16
     static constexpr int x = wp + C::LPP * C::XS * 2;                   // [64][XS] hashed rows
-    static constexpr int y = x + TT * C::XS * 2;                        // [64][XS] accumulated rows
-    static constexpr int ph = y + TT * C::XS * 2;                       // [64][PS] assignments
-    static constexpr int ge = ph + TT * C::PS * 2;                      // [64] fp32
+    static constexpr int y = x + TT * C::XS * 2;                        // [64][YS] accumulated rows
+    static constexpr int ph = y + TT * C::YS * 2;                       // [64][PST] assignments
+    static constexpr int ge = ph + TT * C::PST * 2;                     // [64] fp32
     static constexpr int total = ge + TT * 4;
     static_assert(total <= 160 * 1024, "LDS budget");
 };
@@ -119,22 +119,22 @@ void totals_kernel(KArgs a, const bf16raw *X, const bf16raw *Y, const bf16raw *O
         const int64_t t0 = t_begin + static_cast<int64_t>(it) * TT;
         const int nvalid = step_nv(t0);
         store_rows<C, TT>(pre_x, xs);
-        if (QG) store_cotangent<C, TT>(pre_c, ys, ge_lds);
-        else store_rows<C, TT>(pre_y, ys);
+        if (QG) store_cotangent<C, TT, C::YS>(pre_c, ys, ge_lds);
+        else store_rows<C, TT, C::YS>(pre_y, ys);
         if (it + 1 < nsteps) fetch(it + 1);
         __syncthreads();
         {
             // wavefront = (token half, projection group, share of the group's tables)
             const int half = w / 4, g = w % C::NG, jq = (w % 4) / C::NG;
             const f32x16 z = project<C>(wp, xs + half * 32 * C::XS, g, ln, h);
-            write_assignments<C>(z, g, half * 32 + ln, h, a.beta, half * 32 + ln < nvalid, ph, jq, C::JSTEP);
+            write_assignments<C, C::PST>(z, g, half * 32 + ln, h, a.beta, half * 32 + ln < nvalid, ph, jq, C::JSTEP);
         }
         __syncthreads();
 #pragma unroll
         for (int s = 0; s < TT / 16; ++s) {
             u32x4 by[C::NTW];
 #pragma unroll
-            for (int nt = 0; nt < C::NTW; ++nt) by[nt] = lds_tr_plain(ys, C::XS, 16 * s, c_own + 32 * nt, ln, h);
+            for (int nt = 0; nt < C::NTW; ++nt) by[nt] = lds_tr_plain(ys, C::YS, 16 * s, c_own + 32 * nt, ln, h);
             float4 g0 = {1.f, 1.f, 1.f, 1.f}, g1 = g0;
             if (QG && cg == 0) {
                 g0 = *reinterpret_cast<const float4 *>(ge_lds + 16 * s + 8 * h);
@@ -142,7 +142,7 @@ void totals_kernel(KArgs a, const bf16raw *X, const bf16raw *Y, const bf16raw *O
             }
 #pragma unroll
             for (int mt = 0; mt < C::MT; ++mt) {
-                const u32x4 ap = lds_tr_plain(ph, C::PS, 16 * s, r_own + 32 * mt, ln, h);
+                const u32x4 ap = lds_tr_plain<true>(ph, C::PST, 16 * s, r_own + 32 * mt, ln, h);
                 if (cg == 0)      // the extra column (bucket mass, or its cotangent) is carried by column group 0
                     macc[mt] += bf_lo(ap.x) * g0.x + bf_hi(ap.x) * g0.y + bf_lo(ap.y) * g0.z + bf_hi(ap.y) * g0.w +
                                 bf_lo(ap.z) * g1.x + bf_hi(ap.z) * g1.y + bf_lo(ap.w) * g1.z + bf_hi(ap.w) * g1.w;
@@ -174,8 +174,8 @@ void totals_kernel(KArgs a, const bf16raw *X, const bf16raw *Y, const bf16raw *O
 template <class C>
 struct StreamLds {
     static constexpr int wp = 0;                                        // [LPP][XS] bf16
-    static constexpr int y = wp + C::LPP * C::XS * 2;                   // [32][XS] bf16: accumulated rows
-    static constexpr int mass = y + kTile * C::XS * 2;                  // [LR] fp32: bucket masses A before this tile
+    static constexpr int y = wp + C::LPP * C::XS * 2;                   // [32][YS] bf16: accumulated rows
+    static constexpr int mass = y + kTile * C::YS * 2;                  // [LR] fp32: bucket masses A before this tile, pair-interleaved
     static constexpr int dnp = mass + C::LR * 4;                        // [4][2][32] fp32: mass read-outs per reader wavefront and lane half
     static constexpr int area = (dnp + 4 * 2 * kTile * 4 + 255) & ~255; // start of the aliased area
     // phase A (production, contraction)
@@ -236,7 +236,7 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
         }
         // the bucket masses of tile mt are carried by column group mt % 2 (balances the vector work)
         macc[mt] = (MODE == kForward && (mt & 1) == cg && h == 0) ? st[state_a<C>(r_own + 32 * mt + ln)] : 0.f;
-        if (MODE == kForward && (mt & 1) == cg && h == 0) mass[r_own + 32 * mt + ln] = macc[mt];
+        if (MODE == kForward && (mt & 1) == cg && h == 0) mass[r_own + 32 * mt + il(ln)] = macc[mt];
     }
 
     const int64_t t_begin = seg * a.seg_len;
@@ -269,8 +269,8 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
         store_rows<C, kTile>(pre_r, xr);
         if (intra) {
             store_rows<C, kTile>(pre_w, xw);
-            if (MODE == kGradV) store_cotangent<C, kTile>(pre_c, ytile, nullptr);
-            else store_rows<C, kTile>(pre_y, ytile);
+            if (MODE == kGradV) store_cotangent<C, kTile, C::YS>(pre_c, ytile, nullptr);
+            else store_rows<C, kTile, C::YS>(pre_y, ytile);
         }
         RACE_PHASE(0)
         __syncthreads();
@@ -303,12 +303,12 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
         for (int mt = 0; mt < C::MT; ++mt) {
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
-                const int rr = r_own + 32 * mt + 16 * s + 4 * h;
-                const u32x4 ar = lds64x2(phr + ln * C::PS + rr, phr + ln * C::PS + rr + 8);
+                const int rr = r_own + 32 * mt + 16 * s + 8 * h;      // pair-interleaved corners: one 16-byte read
+                const u32x4 ar = lds128(phr + ln * C::PS + rr);
 #pragma unroll
                 for (int nt = 0; nt < C::NTW; ++nt) out[nt] = mma(ar, acc_operand(Sacc[mt][nt], s), out[nt]);
                 if (intra) {
-                    const u32x4 aw = lds64x2(phw + ln * C::PS + rr, phw + ln * C::PS + rr + 8);
+                    const u32x4 aw = lds128(phw + ln * C::PS + rr);
                     sct = mma(aw, ar, sct);
                 }
                 RACE_SCHED_FENCE();
@@ -329,7 +329,7 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
                 const u32x4 ak = acc_operand(sct, s);
 #pragma unroll
                 for (int nt = 0; nt < C::NTW; ++nt)
-                    out[nt] = mma(ak, lds_tr_acc(ytile, C::XS, 16 * s, c_own + 32 * nt, ln, h), out[nt]);
+                    out[nt] = mma(ak, lds_tr_acc(ytile, C::YS, 16 * s, c_own + 32 * nt, ln, h), out[nt]);
             }
         }
         if (intra) {
@@ -339,10 +339,10 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
             for (int s = 0; s < 2; ++s) {
                 u32x4 by[C::NTW];
 #pragma unroll
-                for (int nt = 0; nt < C::NTW; ++nt) by[nt] = lds_tr_plain(ytile, C::XS, 16 * s, c_own + 32 * nt, ln, h);
+                for (int nt = 0; nt < C::NTW; ++nt) by[nt] = lds_tr_plain(ytile, C::YS, 16 * s, c_own + 32 * nt, ln, h);
 #pragma unroll
                 for (int mt = 0; mt < C::MT; ++mt) {
-                    const u32x4 ap = lds_tr_plain(phw, C::PS, 16 * s, r_own + 32 * mt, ln, h);
+                    const u32x4 ap = lds_tr_plain<true>(phw, C::PS, 16 * s, r_own + 32 * mt, ln, h);
                     if (MODE == kForward && (mt & 1) == cg) macc[mt] += sum8(ap);
 #pragma unroll
                     for (int nt = 0; nt < C::NTW; ++nt) Sacc[mt][nt] = mma(ap, by[nt], Sacc[mt][nt]);
@@ -372,39 +372,38 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
             for (int mt = 0; mt < C::MT; ++mt) {
                 if ((mt & 1) != cg) continue;
                 const float tot = macc[mt] + __shfl_xor(macc[mt], 32, 64);
-                if (h == 0) mass[r_own + 32 * mt + ln] = tot;
+                if (h == 0) mass[r_own + 32 * mt + il(ln)] = tot;
             }
         }
         RACE_PHASE(7)
         __syncthreads();
         RACE_PHASE(8)
-        // ---- epilogue: thread = (token, D/16 consecutive columns): sum the partials, normalise, store rows
+        // ---- epilogue: thread = (token, pieces of 4 columns: 4i.. and, for d = 128, 64 + 4i..; consecutive
+        //      threads read consecutive 16-byte pieces of the partials): sum, normalise, store
         {
-            constexpr int CW = C::D / 16;                // columns per thread (8 or 4)
-            const int tok = tid >> 4, c0 = (tid & 15) * CW;
-            float acc[CW];
+            constexpr int NP = C::D / 64;                // pieces of 4 columns per thread
+            const int tok = tid >> 4, c0 = (tid & 15) * 4;
+            float acc[NP][4];
 #pragma unroll
-            for (int c = 0; c < CW; ++c) acc[c] = 0.f;
+            for (int c = 0; c < NP; ++c) acc[c][0] = acc[c][1] = acc[c][2] = acc[c][3] = 0.f;
             float e = 0.f;
 #pragma unroll
             for (int gg = 0; gg < kRowGroups; ++gg) {
                 const float *src = red + (gg * kTile + tok) * S::RS;
 #pragma unroll
-                for (int c = 0; c < CW; c += 4) {
-                    const float4 p4 = *reinterpret_cast<const float4 *>(src + c0 + c);
-                    acc[c] += p4.x; acc[c + 1] += p4.y; acc[c + 2] += p4.z; acc[c + 3] += p4.w;
+                for (int c = 0; c < NP; ++c) {
+                    const float4 p4 = *reinterpret_cast<const float4 *>(src + c0 + 64 * c);
+                    acc[c][0] += p4.x; acc[c][1] += p4.y; acc[c][2] += p4.z; acc[c][3] += p4.w;
                 }
                 if (MODE == kForward) e += src[C::D] + (dnp[gg * 64 + tok] + dnp[gg * 64 + 32 + tok]);
             }
             if (tok < nvalid) {
                 const float scale = (MODE == kForward) ? 1.0f / e : 1.0f;
                 bf16raw *dst = Out + (t0 + tok) * C::D + c0;
-                if (CW == 8) {
-                    *reinterpret_cast<u32x4 *>(dst) = u32x4{pack2(acc[0] * scale, acc[1] * scale), pack2(acc[2] * scale, acc[3] * scale),
-                                                            pack2(acc[4 % CW] * scale, acc[5 % CW] * scale), pack2(acc[6 % CW] * scale, acc[7 % CW] * scale)};
-                } else {
-                    *reinterpret_cast<u32x2 *>(dst) = u32x2{pack2(acc[0] * scale, acc[1] * scale), pack2(acc[2] * scale, acc[3] * scale)};
-                }
+#pragma unroll
+                for (int c = 0; c < NP; ++c)
+                    *reinterpret_cast<u32x2 *>(dst + 64 * c) =
+                        u32x2{pack2(acc[c][0] * scale, acc[c][1] * scale), pack2(acc[c][2] * scale, acc[c][3] * scale)};
                 if (MODE == kForward && (tid & 15) == 0) den_out[t0 + tok] = e * (1.0f / C::L);
             }
         }
@@ -490,7 +489,7 @@ __global__ __launch_bounds__(kThreads) void hash_tap_kernel(KArgs a, const bf16r
     if (phi) {
         for (int i = tid; i < nvalid * C::LR; i += kThreads) {
             const int row = i / C::LR, r = i % C::LR;
-            phi[(static_cast<size_t>(bh) * a.N + t0 + row) * C::LR + r] = __uint_as_float(static_cast<uint32_t>(ph[row * C::PS + r]) << 16);
+            phi[(static_cast<size_t>(bh) * a.N + t0 + row) * C::LR + r] = __uint_as_float(static_cast<uint32_t>(ph[row * C::PS + il(r)]) << 16);
         }
     }
 }
