@@ -52,13 +52,15 @@ struct GradCfg {
     // high-bit indices); reader masses: one per (projection group, table of the lane) if there is room, else one
     // per projection group; one wavefront for the in-tile term.  If they do not all fit, the reader and in-tile
     // roles double up on the last wavefronts.
-    static constexpr int AS = (C::PHI >= 1 && NGW * C::TPL * 2 + NGW + 1 <= kWaves) ? 2 : 1;
+    static constexpr int AS = (C::PHI >= 2 && NGW * C::TPL * 2 + NGW + 1 <= kWaves) ? 2 : 1;     // shares hold pairs of indices
     static constexpr int NW = NGW * C::TPL * AS;                        // writer wavefronts
     static constexpr int RJ = (NW + NGW * C::TPL + 1 <= kWaves) ? C::TPL : 1;
     static constexpr bool DISJ = NW + NGW * RJ + 1 <= kWaves;
     static constexpr int RD0 = DISJ ? NW : kWaves - NGW * RJ;           // first reader wavefront
-    static constexpr int TT = DISJ ? NW + NGW * RJ : kWaves - 1 - NGW;  // in-tile term
-    static_assert(NW <= kWaves && NGW * RJ + 1 <= kWaves, "production roles must fit the wavefronts");
+    static constexpr int NR = NGW * RJ;                                 // reader wavefronts
+    // in-tile term: a wavefront of its own if one is left, else the last reader
+    static constexpr int TT = DISJ ? (NW + NR < kWaves ? NW + NR : kWaves - 1) : kWaves - 1 - NGW;
+    static_assert(NW <= kWaves && RD0 + NR <= kWaves, "production roles must fit the wavefronts");
 };
 
 template <class C>
@@ -194,7 +196,7 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
             write_assignments<C, C::PST>(zw, th * G::NGW + pg, ln, h, a.beta, ln < nvalid, phw, pj, C::TPL, as * kShare,
                                  (as + 1) * kShare);
         }
-        if (w >= G::RD0 && w < G::RD0 + G::NGW * G::RJ) {
+        if (w >= G::RD0 && w < G::RD0 + G::NR) {
             const int pg = (w - G::RD0) % G::NGW, rj = (w - G::RD0) / G::NGW;
             const f32x16 zr = project<C>(wp, xr, th * G::NGW + pg, ln, h);
 #pragma unroll
@@ -203,9 +205,9 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
                 if (j % G::RJ != rj) continue;
                 float p[C::PP], q[C::PP], s2[C::PP];
 #pragma unroll
-                for (int t = C::P; t < C::PP; ++t) p[t] = q[t] = s2[t] = 0.f;
-                bit_masses<C>(zr, j, a.beta, p, q, s2);
+                for (int t = 0; t < C::PP; ++t) p[t] = q[t] = s2[t] = 0.f;
                 float *dst = pm + ((pg * C::TPG + h * C::TPL + j) * kTile + ln) * S::PMS;
+                bit_masses<C>(zr, j, a.beta, p, q, s2);
 #pragma unroll
                 for (int t = 0; t < C::PP; t += 4) {
                     *reinterpret_cast<float4 *>(dst + t) = float4{p[t], p[t + 1], p[t + 2], p[t + 3]};

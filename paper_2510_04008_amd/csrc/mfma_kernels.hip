@@ -294,7 +294,7 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
         RACE_PHASE(3)
 
         // ---- contraction with the register-resident statistics (own bucket rows x own columns)
-        f32x16 out[C::NTW];
+        f32x16 out[C::NTW];     // read-out, transposed: lane = reader token, register v = column acc_row(v, h) of the tile
         f32x16 sct = {0};       // in-tile kernel values, transposed: row = writer token, lane = reader token
         float rowsum = 0.f;     // in-tile part of the normaliser, reader token = ln
 #pragma unroll
@@ -306,7 +306,7 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
                 const int rr = r_own + 32 * mt + 16 * s + 8 * h;      // pair-interleaved corners: one 16-byte read
                 const u32x4 ar = lds128(phr + ln * C::PS + rr);
 #pragma unroll
-                for (int nt = 0; nt < C::NTW; ++nt) out[nt] = mma(ar, acc_operand(Sacc[mt][nt], s), out[nt]);
+                for (int nt = 0; nt < C::NTW; ++nt) out[nt] = mma(acc_operand(Sacc[mt][nt], s), ar, out[nt]);
                 if (intra) {
                     const u32x4 aw = lds128(phw + ln * C::PS + rr);
                     sct = mma(aw, ar, sct);
@@ -329,7 +329,7 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
                 const u32x4 ak = acc_operand(sct, s);
 #pragma unroll
                 for (int nt = 0; nt < C::NTW; ++nt)
-                    out[nt] = mma(ak, lds_tr_acc(ytile, C::YS, 16 * s, c_own + 32 * nt, ln, h), out[nt]);
+                    out[nt] = mma(lds_tr_acc(ytile, C::YS, 16 * s, c_own + 32 * nt, ln, h), ak, out[nt]);
             }
         }
         if (intra) {
@@ -356,13 +356,15 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
         __syncthreads();        // every wavefront is done with the tiles of this step
         RACE_PHASE(6)
 
-        // ---- reduction over the four bucket-row groups: partial read-outs through LDS
-        const int rbase = opaque((rg * kTile + 4 * h) * S::RS);          // + (8 * (v / 4) + v % 4) rows per register
+        // ---- reduction over the four bucket-row groups: partial read-outs through LDS, 16 bytes per store
+        //      (a lane holds four consecutive columns of its token in registers 4k .. 4k+3)
+        const int rbase = opaque((rg * kTile + ln) * S::RS + c_own + 4 * h);
 #pragma unroll
         for (int nt = 0; nt < C::NTW; ++nt) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v)
-                red[rbase + (8 * (v >> 2) + (v & 3)) * S::RS + c_own + 32 * nt + ln] = out[nt][v];
+            for (int k = 0; k < 4; ++k)
+                *reinterpret_cast<float4 *>(red + rbase + 32 * nt + 8 * k) =
+                    float4{out[nt][4 * k], out[nt][4 * k + 1], out[nt][4 * k + 2], out[nt][4 * k + 3]};
         }
         if (MODE == kForward) {
             // in-tile part of the normaliser: row sums of the masked kernel values (partial over this row group)
@@ -421,14 +423,27 @@ __global__ void scan_kernel(float *state, int nseg, int elems, int mode)
     const int e = blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= elems) return;
     float *base = state + static_cast<size_t>(blockIdx.y) * nseg * elems + e;
+    const size_t stride = static_cast<size_t>(elems);
+    constexpr int U = 8;                 // segments in flight per thread: the loads of a group do not depend on the running sum
     float run = 0.f;
-    if (mode == 0) {
-        for (int s = 0; s < nseg; ++s) { const float v = base[static_cast<size_t>(s) * elems]; base[static_cast<size_t>(s) * elems] = run; run += v; }
-    } else if (mode == 1) {
-        for (int s = nseg - 1; s >= 0; --s) { const float v = base[static_cast<size_t>(s) * elems]; base[static_cast<size_t>(s) * elems] = run; run += v; }
-    } else {
-        for (int s = 0; s < nseg; ++s) run += base[static_cast<size_t>(s) * elems];
-        for (int s = 0; s < nseg; ++s) base[static_cast<size_t>(s) * elems] = run;
+    if (mode == 2) {
+        for (int s = 0; s < nseg; ++s) run += base[s * stride];
+        for (int s = 0; s < nseg; ++s) base[s * stride] = run;
+        return;
+    }
+    for (int s0 = 0; s0 < nseg; s0 += U) {
+        float v[U];
+#pragma unroll
+        for (int k = 0; k < U; ++k) {
+            const int s = mode == 0 ? s0 + k : nseg - 1 - (s0 + k);
+            v[k] = (s0 + k < nseg) ? base[s * stride] : 0.f;
+        }
+#pragma unroll
+        for (int k = 0; k < U; ++k) {
+            const int s = mode == 0 ? s0 + k : nseg - 1 - (s0 + k);
+            if (s0 + k < nseg) base[s * stride] = run;
+            run += v[k];
+        }
     }
 }
 
