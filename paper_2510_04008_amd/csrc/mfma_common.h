@@ -208,9 +208,10 @@ __device__ __forceinline__ void store_chunk(bf16raw *dst, int row, int ch, u32x4
 template <class C, int ROWS, int STRIDE = C::XS, bool IL = false>
 __device__ __forceinline__ void store_rows(const RowChunks<C, ROWS> &r, bf16raw *dst)
 {
+    const int tid = opaque(static_cast<int>(threadIdx.x));       // keeps the tile addresses out of long-lived registers
 #pragma unroll
     for (int k = 0; k < RowChunks<C, ROWS>::N; ++k) {
-        const int c = threadIdx.x + k * kThreads, row = c / C::CPR, ch = c % C::CPR;
+        const int c = tid + k * kThreads, row = c / C::CPR, ch = c % C::CPR;
         if (row < ROWS) store_chunk<STRIDE, IL>(dst, row, ch, r.v[k]);
     }
 }
@@ -238,9 +239,10 @@ __device__ __forceinline__ void fetch_cotangent(const bf16raw *dO, const bf16raw
 template <class C, int ROWS, int STRIDE = C::XS, bool IL = false>
 __device__ __forceinline__ void store_cotangent(const CotChunks<C, ROWS> &r, bf16raw *dst, float *ge)
 {
+    const int tid = opaque(static_cast<int>(threadIdx.x));
 #pragma unroll
     for (int k = 0; k < RowChunks<C, ROWS>::N; ++k) {
-        const int c = threadIdx.x + k * kThreads, row = c / C::CPR, ch = c % C::CPR;
+        const int c = tid + k * kThreads, row = c / C::CPR, ch = c % C::CPR;
         const float inv = r.den[k] > 0.f ? 1.0f / (r.den[k] * static_cast<float>(C::L)) : 0.f;
         const uint32_t gw[4] = {r.g.v[k].x, r.g.v[k].y, r.g.v[k].z, r.g.v[k].w};
         const uint32_t ow[4] = {r.o.v[k].x, r.o.v[k].y, r.o.v[k].z, r.o.v[k].w};
@@ -354,13 +356,15 @@ __device__ __forceinline__ float write_assignments(const f32x16 &z, int g, int r
         float p[C::P], q[C::P], lo[1 << C::PLO], hi[1 << C::PHI];
         bit_masses<C>(z, j, beta, p, q, nullptr);
         kron_factors<C>(p, q, lo, hi);
+        const int tbase = opaque(table * C::R);                   // one base register, constants folded into offsets
+        bf16raw *prow = ph + opaque(row * STRIDE);
 #pragma unroll
         for (int a = 0; a < (1 << C::PHI); a += 2) {
             if (a < a0 || a >= a1) continue;
             const float ha = valid ? hi[a] : 0.f, hb = valid ? hi[a + 1] : 0.f;
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
-                const int pos = table * C::R + a * 8 + 8 * half;
+                const int pos = tbase + a * 8 + 8 * half;
                 float f[8];
 #pragma unroll
                 for (int b = 0; b < 4; ++b) { f[b] = ha * lo[4 * half + b]; f[4 + b] = hb * lo[4 * half + b]; }
@@ -370,7 +374,7 @@ __device__ __forceinline__ float write_assignments(const f32x16 &z, int g, int r
                     dn = fmaf(f[0], m0.x, dn); dn = fmaf(f[1], m0.y, dn); dn = fmaf(f[2], m0.z, dn); dn = fmaf(f[3], m0.w, dn);
                     dn = fmaf(f[4], m1.x, dn); dn = fmaf(f[5], m1.y, dn); dn = fmaf(f[6], m1.z, dn); dn = fmaf(f[7], m1.w, dn);
                 }
-                *reinterpret_cast<u32x4 *>(ph + row * STRIDE + pos) =
+                *reinterpret_cast<u32x4 *>(prow + pos) =
                     u32x4{pack2(f[0], f[1]), pack2(f[2], f[3]), pack2(f[4], f[5]), pack2(f[6], f[7])};
             }
             RACE_SCHED_FENCE();

@@ -1,8 +1,8 @@
 // grad_kernel: the two backward passes that contract the bucket statistics over the head dimension.
-// Register budget: with eight wavefronts of 256 registers a wavefront can carry 32 bucket rows x d
-// columns of fp32 statistics next to its working set, i.e. 256 bucket rows per workgroup.  Shapes with
-// more rows are split over TSPLIT workgroups by tables (blockIdx.z): each computes dz for its own
-// tables and writes it to the workspace; dz_matmul_kernel then forms dX = dZ . W for all tables.
+// Register budget: with eight wavefronts of 256 registers a wavefront can carry up to 64 bucket rows x 128
+// columns of fp32 statistics (128 registers) next to its working set, i.e. 512 bucket rows per workgroup.
+// Shapes with more rows are split over TSPLIT workgroups by tables (blockIdx.z): each computes dz for its
+// own tables and writes it to the workspace; dz_matmul_kernel then forms dX = dZ . W for all tables.
 //
 //   SIDE 0 (dQ), left to right, statistics S = (B | A) of (phi_K, [V | 1]) before/with token i:
 //       dphi_Q(i)[r] = S[r,:] . [dO_i/e_i | -(dO_i.O_i)/e_i]
@@ -34,18 +34,27 @@ namespace mfma {
 #define GRAD_PHASE_PRINT()
 #endif
 
+// Row tiles per wavefront: all of LR / 256 if that is at most two (128 registers of statistics per lane is what
+// fits next to the working set); beyond that the bucket rows are split over TSPLIT workgroups by tables.
+template <class C> constexpr int grad_row_tiles() { return C::LR / (32 * kWaves) <= 2 ? C::LR / (32 * kWaves) : 2; }
+
 template <class C>
 struct GradCfg {
-    static constexpr int TSPLIT = C::LR / (32 * kWaves);                // workgroups per (segment, head)
+    static constexpr int MTG = grad_row_tiles<C>();                     // 32-row tiles of bucket rows per wavefront
+    static constexpr int RW = 32 * MTG;                                 // bucket rows per wavefront
+    static constexpr int TSPLIT = C::LR / (RW * kWaves);                // workgroups per (segment, head)
     static constexpr int NGW = C::NG / TSPLIT;                          // projection groups per workgroup
     static constexpr int ROWS = C::LR / TSPLIT;                         // bucket rows per workgroup
     static constexpr int TABLES = NGW * C::TPG;                         // tables per workgroup
-    // a wavefront's 32 bucket rows are TW whole tables (R <= 32) or a 1/WPT share of one table (R > 32)
-    static constexpr int TW = C::R >= 32 ? 1 : 32 / C::R;               // tables per wavefront
-    static constexpr int WPT = C::R >= 32 ? C::R / 32 : 1;              // wavefronts per table
-    static constexpr int KM = (C::R >= 32 ? 32 : C::R) / 8;             // groups of 8 corners per table and wavefront
-    static constexpr int MB = KM == 4 ? 2 : (KM == 2 ? 1 : 0);          // corner bits 3.. that vary inside a wavefront
-    static_assert(TSPLIT >= 1 && C::NG % TSPLIT == 0 && kWaves % NGW == 0, "table split");
+    // a wavefront's rows are TWW whole tables (R <= RW) or a 1/WPT share of one table (R > RW);
+    // a 32-row tile holds TW whole tables (R <= 32) or part of one
+    static constexpr int TWW = C::R >= RW ? 1 : RW / C::R;              // tables per wavefront
+    static constexpr int WPT = C::R >= RW ? C::R / RW : 1;              // wavefronts per table
+    static constexpr int TW = C::R >= 32 ? 1 : 32 / C::R;               // tables per tile
+    static constexpr int KM = (C::R >= 32 ? 32 : C::R) / 8;             // groups of 8 corners per table and tile
+    static constexpr int MB = KM == 4 ? 2 : (KM == 2 ? 1 : 0);          // corner bits 3.. that vary inside a tile
+    static_assert(MTG >= 1 && TSPLIT >= 1 && TSPLIT * RW * kWaves == C::LR, "bucket rows over wavefronts");
+    static_assert(C::NG % TSPLIT == 0 && kWaves % NGW == 0, "table split");
     static_assert(NGW * C::TPG * C::R == ROWS, "a workgroup's rows are the tables of its projection groups");
     static_assert(C::P >= 3 && C::P <= 7, "corner bits 0..2 are register/lane bits; a partial record is P+1 <= 8 floats");
     // production roles.  Writer hashing: one wavefront per (projection group, table of the lane, share of the
@@ -110,10 +119,10 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
     const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, ln = lane & 31, h = lane >> 5;
     const int th = blockIdx.z;                       // which share of the tables this workgroup owns
     const int r_base = th * G::ROWS;                 // its first bucket row
-    const int r_own = r_base + w * 32;               // this wavefront's 32 bucket rows
+    const int r_own = r_base + w * G::RW;            // this wavefront's bucket rows
     // backward pass through the soft assignment: the tables (or the share of one table) behind this wavefront's rows
-    const int tl0 = (w * 32) / C::R;                 // first table, counted inside the workgroup
-    const int ro = (w * 32) % C::R;                  // first corner of the share (0 unless a table spans several wavefronts)
+    const int tl0 = (w * G::RW) / C::R;              // first table, counted inside the workgroup
+    const int ro = (w * G::RW) % C::R;               // first corner of the share (0 unless a table spans several wavefronts)
     const bool intra = a.causal;
 
     const size_t base = static_cast<size_t>(bh) * a.N * C::D;
@@ -130,15 +139,18 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
             *reinterpret_cast<u32x4 *>(wp + row * C::XS + ch * 8) = *reinterpret_cast<const u32x4 *>(src + row * C::D + ch * 8);
         }
     }
-    // statistics at the start of the segment, transposed tiles: ST[column tile][bucket-row tile]
-    f32x16 ST[C::NT];         // ST[column tile]: columns x this wavefront's 32 bucket rows
-    float macc;               // extra column (A or dA): per-half partial sum, lane n <-> row r_own + n
+    // statistics at the start of the segment, transposed tiles ST[row tile][column tile]: columns x 32 bucket rows
+    f32x16 ST[G::MTG][C::NT];
+    float macc[G::MTG];       // extra column (A or dA): per-half partial sum, lane n <-> row r_own + 32 mr + n
 #pragma unroll
-    for (int mtc = 0; mtc < C::NT; ++mtc) {
+    for (int mr = 0; mr < G::MTG; ++mr) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) ST[mtc][v] = st[(r_own + ln) * C::D + 32 * mtc + acc_row(v, h)];
+        for (int mtc = 0; mtc < C::NT; ++mtc) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) ST[mr][mtc][v] = st[(r_own + 32 * mr + ln) * C::D + 32 * mtc + acc_row(v, h)];
+        }
+        macc[mr] = (h == 0) ? st[C::LR * C::D + r_own + 32 * mr + ln] : 0.f;
     }
-    macc = (h == 0) ? st[C::LR * C::D + r_own + ln] : 0.f;
 
     const int64_t t_begin = seg * a.seg_len;
     const int64_t t_end = (t_begin + a.seg_len < a.N) ? t_begin + a.seg_len : a.N;
@@ -146,7 +158,7 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
     auto tile_t0 = [&](int it) { return t_begin + static_cast<int64_t>(kReverse ? ntiles - 1 - it : it) * kTile; };
     auto tile_nv = [&](int64_t t0) { return (t_end - t0 < kTile) ? static_cast<int>(t_end - t0) : kTile; };
 
-    // loads run ahead of the arithmetic: issued when few registers are live, written to LDS at the next tile's start
+    // loads run ahead of the arithmetic: issued a step ahead, written to LDS at the next tile's start
     RowChunks<C, kTile> pre_r, pre_w, pre_v;
     CotChunks<C, kTile> pre_c;
     auto fetch = [&](int it) {
@@ -242,110 +254,122 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
         // the next tile's loads are issued a whole step ahead and fly during everything below
         if (it + 1 < ntiles) fetch(it + 1);
         GRAD_PHASE(4)
-        // ---- cotangent of the reader's assignments, transposed: lane = token, register v = bucket row
-        //      r_own + acc_row(v, h) of this wavefront
-        f32x16 dP;
-        {
-            // extra column first: sr_a * (A or dA)[r] with the masses before this tile
-            float m_hi, m_lo;
-            split_bf16(macc + __shfl_xor(macc, 32, 64), m_hi, m_lo);
-            const u32x4 mb = (h == 0) ? u32x4{pack2(m_hi, m_lo), pack2(m_hi, 0.f), 0u, 0u} : u32x4{0u, 0u, 0u, 0u};
-            dP = mma(mb, sr_a, f32x16{0});
+
+        // ---- per 32-row tile of this wavefront: cotangent of the reader's assignments, transposed (lane = token,
+        //      register v = bucket row r_own + 32 mr + acc_row(v, h)), then straight back through the corner
+        //      softmax (Algorithm 1, step 4) in those registers: with w_c = phi_c dphi_c over the corners c of a
+        //      table, m = sum_c w_c and E_t = sum_c v_{c,t} w_c.  Register v of lane half h is corner
+        //      co + 8 (v/4 mod KM) + 4h + v%4 of table tl0 + (32 mr + 8 (v/4)) / R: bits 0,1 come from v, bit 2
+        //      from h, bits 3.. from v, the bits above from the tile and the wavefront's share.  phi_c is the
+        //      product over bits of p_t (bit set) or q_t (Section 3.3: the corner softmax factorises).
+        float rec[G::TWW][8];          // [m, E_0 .. E_{P-1}] of the lane's token per table of the wavefront (lane partials)
+#pragma unroll
+        for (int i = 0; i < G::TWW; ++i) {
+#pragma unroll
+            for (int t = 0; t < 8; ++t) rec[i][t] = 0.f;
         }
-        if (intra) {
 #pragma unroll
-            for (int s = 0; s < 2; ++s)
-                dP = mma(lds_tr_acc<true>(phw, C::PST, 16 * s, r_own, ln, h), ttop[64 * s + lane], dP);
-        }
-        {
-            const int yo = opaque(ln * C::XS + 8 * h);       // pair-interleaved columns: one 16-byte read per k-step
+        for (int mr = 0; mr < G::MTG; ++mr) {
+            f32x16 dP;
+            {
+                // extra column first: sr_a * (A or dA)[r] with the masses before this tile
+                float m_hi, m_lo;
+                split_bf16(macc[mr] + __shfl_xor(macc[mr], 32, 64), m_hi, m_lo);
+                const u32x4 mb = (h == 0) ? u32x4{pack2(m_hi, m_lo), pack2(m_hi, 0.f), 0u, 0u} : u32x4{0u, 0u, 0u, 0u};
+                dP = mma(mb, sr_a, f32x16{0});
+            }
+            if (intra) {
 #pragma unroll
-            for (int mtc = 0; mtc < C::NT; ++mtc) {
+                for (int s = 0; s < 2; ++s)
+                    dP = mma(lds_tr_acc<true>(phw, C::PST, 16 * s, r_own + 32 * mr, ln, h), ttop[64 * s + lane], dP);
+            }
+            {
+                const int yo = opaque(ln * C::XS + 8 * h);       // pair-interleaved columns: one 16-byte read per k-step
 #pragma unroll
-                for (int s = 0; s < 2; ++s) {
-                    const int cc = 32 * mtc + 16 * s;
-                    dP = mma(acc_operand(ST[mtc], s), lds128(yr + yo + cc), dP);
+                for (int mtc = 0; mtc < C::NT; ++mtc) {
+#pragma unroll
+                    for (int s = 0; s < 2; ++s) {
+                        const int cc = 32 * mtc + 16 * s;
+                        dP = mma(acc_operand(ST[mr][mtc], s), lds128(yr + yo + cc), dP);
+                    }
                 }
             }
+#pragma unroll
+            for (int tw = 0; tw < G::TW; ++tw) {
+                constexpr int kTilesPerTable = C::R >= 32 ? C::R / 32 : 1;
+                const int ti = C::R >= 32 ? mr / kTilesPerTable : mr * G::TW + tw;   // table of the wavefront
+                const int co = C::R >= 32 ? ro + 32 * (mr % kTilesPerTable) : 0;     // first corner of the tile in its table
+                const float *src = pm + ((tl0 + ti) * kTile + ln) * S::PMS;
+                float p[C::PP], q[C::PP];
+#pragma unroll
+                for (int t = 0; t < C::PP; t += 4) {
+                    const float4 p4 = *reinterpret_cast<const float4 *>(src + t);
+                    const float4 q4 = *reinterpret_cast<const float4 *>(src + C::PP + t);
+                    p[t] = p4.x; p[t + 1] = p4.y; p[t + 2] = p4.z; p[t + 3] = p4.w;
+                    q[t] = q4.x; q[t + 1] = q4.y; q[t + 2] = q4.z; q[t + 3] = q4.w;
+                }
+                float F = h ? p[2] : q[2];
+#pragma unroll
+                for (int t = 3 + G::MB; t < C::P; ++t) F *= ((co >> t) & 1) ? p[t] : q[t];
+                const float Fl[4] = {F * q[0] * q[1], F * p[0] * q[1], F * q[0] * p[1], F * p[0] * p[1]};
+                float m = 0.f, E0 = 0.f, E1 = 0.f, Em[2] = {0.f, 0.f};
+#pragma unroll
+                for (int k = 0; k < G::KM; ++k) {
+                    float mid = 1.f;
+#pragma unroll
+                    for (int b = 0; b < G::MB; ++b) mid *= ((k >> b) & 1) ? p[3 + b] : q[3 + b];
+                    const int v0 = 4 * (tw * G::KM + k);
+                    const float w0 = Fl[0] * dP[v0], w1 = Fl[1] * dP[v0 + 1], w2 = Fl[2] * dP[v0 + 2], w3 = Fl[3] * dP[v0 + 3];
+                    const float s01 = w0 + w1, s23 = w2 + w3;
+                    const float c = mid * (s01 + s23);
+                    E0 = fmaf(mid, (w1 - w0) + (w3 - w2), E0);
+                    E1 = fmaf(mid, s23 - s01, E1);
+                    m += c;
+#pragma unroll
+                    for (int b = 0; b < G::MB; ++b) Em[b] += ((k >> b) & 1) ? c : -c;
+                }
+                // lane partials; bit 2 is the lane half, the bits above the tile's are uniform
+                rec[ti][0] += m;
+                rec[ti][1] += E0;
+                rec[ti][2] += E1;
+                rec[ti][3] += h ? m : -m;
+#pragma unroll
+                for (int b = 0; b < G::MB; ++b) rec[ti][4 + b] += Em[b];
+#pragma unroll
+                for (int t = 3 + G::MB; t < C::P; ++t) rec[ti][1 + t] += ((co >> t) & 1) ? m : -m;
+            }
         }
-        GRAD_PHASE(5)
-
-        // ---- back through the corner softmax (Algorithm 1, step 4), in the accumulator's own registers:
-        //      with w_c = phi_c dphi_c over the corners c of a table, m = sum_c w_c and E_t = sum_c v_{c,t} w_c.
-        //      Register v of lane half h is corner  co + 8 (v/4 mod KM) + 4h + v%4  of table tl0 + v/(4 KM):
-        //      bits 0,1 come from v, bit 2 from h, bits 3.. from v, bits above from the wavefront's share.
-        //      phi_c is the product over bits of p_t (bit set) or q_t (Section 3.3: the corner softmax factorises).
-        float rec[G::TW][8];           // [m, E_0 .. E_{P-1}] of the lane's token, per table of the wavefront
-        auto soft_backward = [&]() {
+        // the two lane halves hold the two values of bit 2: add them up
 #pragma unroll
-        for (int tw = 0; tw < G::TW; ++tw) {
-            const float *src = pm + ((tl0 + tw) * kTile + ln) * S::PMS;
-            float p[C::PP], q[C::PP];
+        for (int i = 0; i < G::TWW; ++i) {
 #pragma unroll
-            for (int t = 0; t < C::PP; t += 4) {
-                const float4 p4 = *reinterpret_cast<const float4 *>(src + t);
-                const float4 q4 = *reinterpret_cast<const float4 *>(src + C::PP + t);
-                p[t] = p4.x; p[t + 1] = p4.y; p[t + 2] = p4.z; p[t + 3] = p4.w;
-                q[t] = q4.x; q[t + 1] = q4.y; q[t + 2] = q4.z; q[t + 3] = q4.w;
-            }
-            float F = h ? p[2] : q[2];
-#pragma unroll
-            for (int t = 3 + G::MB; t < C::P; ++t) F *= ((ro >> t) & 1) ? p[t] : q[t];
-            const float Fl[4] = {F * q[0] * q[1], F * p[0] * q[1], F * q[0] * p[1], F * p[0] * p[1]};
-            float m = 0.f, E0 = 0.f, E1 = 0.f, Em[2] = {0.f, 0.f};
-#pragma unroll
-            for (int k = 0; k < G::KM; ++k) {
-                float mid = 1.f;
-#pragma unroll
-                for (int b = 0; b < G::MB; ++b) mid *= ((k >> b) & 1) ? p[3 + b] : q[3 + b];
-                const int v0 = 4 * (tw * G::KM + k);
-                const float w0 = Fl[0] * dP[v0], w1 = Fl[1] * dP[v0 + 1], w2 = Fl[2] * dP[v0 + 2], w3 = Fl[3] * dP[v0 + 3];
-                const float s01 = w0 + w1, s23 = w2 + w3;
-                const float c = mid * (s01 + s23);
-                E0 = fmaf(mid, (w1 - w0) + (w3 - w2), E0);
-                E1 = fmaf(mid, s23 - s01, E1);
-                m += c;
-#pragma unroll
-                for (int b = 0; b < G::MB; ++b) Em[b] += ((k >> b) & 1) ? c : -c;
-            }
-            // the two lane halves hold the two values of bit 2
-            const float mo = __shfl_xor(m, 32, 64);
-            const float mt = m + mo;
-            rec[tw][0] = mt;
-            rec[tw][1] = E0 + __shfl_xor(E0, 32, 64);
-            rec[tw][2] = E1 + __shfl_xor(E1, 32, 64);
-            rec[tw][3] = h ? m - mo : mo - m;
-#pragma unroll
-            for (int b = 0; b < G::MB; ++b) rec[tw][4 + b] = Em[b] + __shfl_xor(Em[b], 32, 64);
-#pragma unroll
-            for (int t = 3 + G::MB; t < C::P; ++t) rec[tw][1 + t] = ((ro >> t) & 1) ? mt : -mt;
-#pragma unroll
-            for (int t = C::P + 1; t < 8; ++t) rec[tw][t] = 0.f;
+            for (int t = 0; t <= C::P; ++t) rec[i][t] += __shfl_xor(rec[i][t], 32, 64);
         }
         if (G::WPT > 1 && ro != 0) {
             // a later share of a table: hand the partial sums to the wavefront that owns the table's first share
             float *dst = part + ((w * kTile + ln) * 8 + 4 * h);
             *reinterpret_cast<float4 *>(dst) = float4{rec[0][4 * h], rec[0][4 * h + 1], rec[0][4 * h + 2], rec[0][4 * h + 3]};
         }
-        };
-        auto update_statistics = [&]() {
+        GRAD_PHASE(5)
         // ---- statistics += Yw^T . phi_writer
         if (intra) {
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
                 const float4 g0 = *reinterpret_cast<const float4 *>(sw + 16 * s + 8 * h);
                 const float4 g1 = *reinterpret_cast<const float4 *>(sw + 16 * s + 8 * h + 4);
-                const u32x4 bp = lds_tr_plain<true>(phw, C::PST, 16 * s, r_own, ln, h);
-                macc += bf_lo(bp.x) * g0.x + bf_hi(bp.x) * g0.y + bf_lo(bp.y) * g0.z + bf_hi(bp.y) * g0.w +
-                        bf_lo(bp.z) * g1.x + bf_hi(bp.z) * g1.y + bf_lo(bp.w) * g1.z + bf_hi(bp.w) * g1.w;
+                u32x4 ay[C::NT];
 #pragma unroll
-                for (int mtc = 0; mtc < C::NT; ++mtc)
-                    ST[mtc] = mma(lds_tr_plain<true>(yw, C::YS, 16 * s, 32 * mtc, ln, h), bp, ST[mtc]);
+                for (int mtc = 0; mtc < C::NT; ++mtc) ay[mtc] = lds_tr_plain<true>(yw, C::YS, 16 * s, 32 * mtc, ln, h);
+#pragma unroll
+                for (int mr = 0; mr < G::MTG; ++mr) {
+                    const u32x4 bp = lds_tr_plain<true>(phw, C::PST, 16 * s, r_own + 32 * mr, ln, h);
+                    macc[mr] += bf_lo(bp.x) * g0.x + bf_hi(bp.x) * g0.y + bf_lo(bp.y) * g0.z + bf_hi(bp.y) * g0.w +
+                                bf_lo(bp.z) * g1.x + bf_hi(bp.z) * g1.y + bf_lo(bp.w) * g1.z + bf_hi(bp.w) * g1.w;
+#pragma unroll
+                    for (int mtc = 0; mtc < C::NT; ++mtc) ST[mr][mtc] = mma(ay[mtc], bp, ST[mr][mtc]);
+                }
             }
         }
-        };
-        soft_backward();
-        update_statistics();
         GRAD_PHASE(10)
         GRAD_PHASE(6)
         __syncthreads();        // partial sums are visible; the tiles of this step are dead from here on
@@ -355,16 +379,16 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
         //      lane half h' takes the padded projection slots 4h' .. 4h'+3
         if (ro == 0) {
 #pragma unroll
-            for (int tw = 0; tw < G::TW; ++tw) {
+            for (int ti = 0; ti < G::TWW; ++ti) {
                 if (4 * h >= C::PP) break;
-                const int tl = tl0 + tw;
+                const int tl = tl0 + ti;
 #pragma unroll
                 for (int o = 1; o < G::WPT; ++o) {
                     const float *src = part + ((w + o) * kTile + ln) * 8;
                     const float4 p0 = *reinterpret_cast<const float4 *>(src);
                     const float4 p1 = *reinterpret_cast<const float4 *>(src + 4);
-                    rec[tw][0] += p0.x; rec[tw][1] += p0.y; rec[tw][2] += p0.z; rec[tw][3] += p0.w;
-                    rec[tw][4] += p1.x; rec[tw][5] += p1.y; rec[tw][6] += p1.z; rec[tw][7] += p1.w;
+                    rec[ti][0] += p0.x; rec[ti][1] += p0.y; rec[ti][2] += p0.z; rec[ti][3] += p0.w;
+                    rec[ti][4] += p1.x; rec[ti][5] += p1.y; rec[ti][6] += p1.z; rec[ti][7] += p1.w;
                 }
                 const float *src = pm + (tl * kTile + ln) * S::PMS + 4 * h;
                 const float4 p4 = *reinterpret_cast<const float4 *>(src);
@@ -376,8 +400,8 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     // E of slot 4h + e is rec[1 + 4h + e]; slot 7 is padding (P <= 7) and has no entry
-                    const float Et = h ? (e < 3 ? rec[tw][e < 3 ? 5 + e : 0] : 0.f) : rec[tw][1 + e];
-                    dzv[e] = a.beta * (Et - rec[tw][0] * pq[e]) * s2[e];       // padded slots: s2 = 0
+                    const float Et = h ? (e < 3 ? rec[ti][e < 3 ? 5 + e : 0] : 0.f) : rec[ti][1 + e];
+                    dzv[e] = a.beta * (Et - rec[ti][0] * pq[e]) * s2[e];       // padded slots: s2 = 0
                 }
                 // slot 4c.. of the lane-half hh's j-th table is projection row 8 (slots-per-table/4 * j + c) + 4 hh of its group
                 const int gl = tl / C::TPG, tg = tl % C::TPG, hh = tg / C::TPL, j = tg % C::TPL;
