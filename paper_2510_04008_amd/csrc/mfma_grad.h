@@ -1,8 +1,9 @@
 // grad_kernel: the two backward passes that contract the bucket statistics over the head dimension.
 // Register budget: with eight wavefronts of 256 registers a wavefront can carry up to 64 bucket rows x 128
 // columns of fp32 statistics (128 registers) next to its working set, i.e. 512 bucket rows per workgroup.
-// Shapes with more rows are split over TSPLIT workgroups by tables (blockIdx.z): each computes dz for its
-// own tables and writes it to the workspace; dz_matmul_kernel then forms dX = dZ . W for all tables.
+// The workgroup then also forms dX = dz . W for its tile.  Shapes with more rows are split over TSPLIT
+// workgroups by tables (blockIdx.z): each computes dz for its own tables and writes it to the workspace;
+// dz_matmul_kernel then forms dX = dZ . W for all tables.
 //
 //   SIDE 0 (dQ), left to right, statistics S = (B | A) of (phi_K, [V | 1]) before/with token i:
 //       dphi_Q(i)[r] = S[r,:] . [dO_i/e_i | -(dO_i.O_i)/e_i]
@@ -89,14 +90,16 @@ struct GradLds {
     static constexpr int xw = xr + kTile * C::XS * 2;
     static constexpr int yw = xw + kTile * C::XS * 2;                   // [32][YS] writer-Y rows, pair-interleaved columns
     static constexpr int phw = yw + kTile * C::YS * 2;                  // [32][PST] writer assignments
-    static constexpr int total = phw + kTile * C::PST * 2;
+    static constexpr int SS = 40;                                       // bf16 row stride of the output staging tiles
+    static constexpr int stg = phw + kTile * C::PST * 2;                // [NT][32][SS] bf16: dX tiles on their way out
+    static constexpr int total = stg + (G::TSPLIT == 1 ? C::NT * kTile * SS * 2 : 0);
     static_assert(total <= 160 * 1024, "LDS budget");
 };
 
 template <class C, int SIDE>
 __global__ __launch_bounds__(kThreads)
 void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, const bf16raw *O,
-                 const float *den, const bf16raw *dO, bf16raw *dZ)
+                 const float *den, const bf16raw *dO, bf16raw *dZ, bf16raw *dX)
 {
     using S = GradLds<C>;
     using G = GradCfg<C>;
@@ -113,6 +116,7 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
     bf16raw *phw = reinterpret_cast<bf16raw *>(lds + S::phw);
     float *part = reinterpret_cast<float *>(lds + S::part);
     u32x4 *ttop = reinterpret_cast<u32x4 *>(lds + S::ttop);
+    bf16raw *stg = reinterpret_cast<bf16raw *>(lds + S::stg);
 
     constexpr bool kReverse = (SIDE == 1);
     const int seg = blockIdx.x, bh = blockIdx.y, head = bh % a.H;
@@ -128,6 +132,7 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
     const size_t base = static_cast<size_t>(bh) * a.N * C::D;
     Q += base; K += base; V += base; O += base; dO += base;
     dZ += static_cast<size_t>(bh) * a.N * C::LPP;
+    dX += base;
     den += static_cast<size_t>(bh) * a.N;
     const bf16raw *Xr = SIDE == 0 ? Q : K, *Xw = SIDE == 0 ? K : Q;
     const float *st = a.state + (static_cast<size_t>(bh) * a.nseg + seg) * C::STATE;
@@ -413,16 +418,43 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
         __syncthreads();
         GRAD_PHASE(11)
 
-        // ---- this workgroup's columns of dZ (projection rows of its groups) -> workspace, 16-byte pieces
-        if (tid < kTile * G::NGW * 4) {
-            const int row = tid / (G::NGW * 4), ch = tid % (G::NGW * 4);
-            if (row < nvalid)
-                *reinterpret_cast<u32x4 *>(dZ + (t0 + row) * C::LPP + th * G::NGW * 32 + 8 * ch) =
-                    *reinterpret_cast<const u32x4 *>(dz + row * S::DZS + 8 * ch);
+        if constexpr (G::TSPLIT == 1) {
+            // ---- dX = dz . W for this tile (the chain rule through W): wavefront nt forms the transposed 32 x 32 tile
+            //      (lane = token, registers = columns 32 nt + acc_row(v, h)), stages it in its own corner of
+            //      LDS and stores 16-byte row pieces; nobody else touches that corner, so no barrier is needed
+            static_assert(C::NT <= kWaves, "one wavefront per column tile");
+            if (w < C::NT) {
+                const int nt = w;
+                const int lo = opaque(lane);                     // addresses below are rebuilt per tile, not kept in registers
+                const int lno = lo & 31, ho = lo >> 5;
+                f32x16 acc = {0};
+#pragma unroll
+                for (int s = 0; s < C::LPP / 16; ++s)
+                    acc = mma(lds_tr_plain(wp, C::XS, 16 * s, 32 * nt, lno, ho), lds128(dz + lno * S::DZS + 16 * s + 8 * ho), acc);
+                bf16raw *sg = stg + nt * kTile * S::SS;
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    *reinterpret_cast<u32x2 *>(sg + lno * S::SS + 8 * k + 4 * ho) =
+                        u32x2{pack2(acc[4 * k], acc[4 * k + 1]), pack2(acc[4 * k + 2], acc[4 * k + 3])};
+#pragma unroll
+                for (int kk = 0; kk < 2; ++kk) {
+                    const int row = (lo >> 2) + 16 * kk, ch = lo & 3;
+                    const u32x4 piece = *reinterpret_cast<const u32x4 *>(sg + row * S::SS + 8 * ch);
+                    if (row < nvalid) *reinterpret_cast<u32x4 *>(dX + (t0 + row) * C::D + 32 * nt + 8 * ch) = piece;
+                }
+            }
+        } else {
+            // ---- this workgroup's columns of dZ (projection rows of its groups) -> workspace, 16-byte pieces
+            if (tid < kTile * G::NGW * 4) {
+                const int row = tid / (G::NGW * 4), ch = tid % (G::NGW * 4);
+                if (row < nvalid)
+                    *reinterpret_cast<u32x4 *>(dZ + (t0 + row) * C::LPP + th * G::NGW * 32 + 8 * ch) =
+                        *reinterpret_cast<const u32x4 *>(dz + row * S::DZS + 8 * ch);
+            }
         }
         GRAD_PHASE(12)
-        // no barrier here: the next step's loads-to-LDS touch none of dz, pm or part, and its production
-        // (which rewrites pm) comes after the next barrier
+        // no barrier here: the next step's loads-to-LDS touch none of dz, pm, part or the staging tiles, and its
+        // production (which rewrites pm) comes after the next barrier
     }
     GRAD_PHASE_PRINT()
 }

@@ -586,8 +586,8 @@ hipError_t fwd_t(const Plan &p, const void *Q, const void *K, const void *V, voi
     return hipSuccess;
 }
 
-// dphi and the chain rule through the soft assignment (grad_kernel, one workgroup per share of the
-// tables), then dX = dZ . W for all tables
+// dphi and the chain rule through the soft assignment and W (grad_kernel).  Shapes whose bucket rows are
+// split over several workgroups by tables leave dZ in the workspace and finish with dX = dZ . W for all tables.
 template <class C, int SIDE>
 hipError_t launch_grad(const Plan &p, KArgs a, const void *Q, const void *K, const void *V, const void *O,
                        const float *den, const void *dO, void *dX, hipStream_t st)
@@ -599,10 +599,10 @@ hipError_t launch_grad(const Plan &p, KArgs a, const void *Q, const void *K, con
         hipLaunchKernelGGL(kern, dim3(p.nseg, p.BH, GradCfg<C>::TSPLIT), dim3(kThreads), GradLds<C>::total, st, a,
                            static_cast<const bf16raw *>(Q), static_cast<const bf16raw *>(K),
                            static_cast<const bf16raw *>(V), static_cast<const bf16raw *>(O), den,
-                           static_cast<const bf16raw *>(dO), a.dZ);
+                           static_cast<const bf16raw *>(dO), a.dZ, static_cast<bf16raw *>(dX));
         RACE_TRY(hipGetLastError());
     }
-    {
+    if (GradCfg<C>::TSPLIT > 1) {
         ProfileScope prof("dz_matmul", st);
         hipLaunchKernelGGL(dz_matmul_kernel<C>, dim3(static_cast<unsigned>((p.N + kTile * kDzTiles - 1) / (kTile * kDzTiles)), p.BH),
                            dim3(64 * C::NT), 0, st, a, a.dZ, static_cast<bf16raw *>(dX));
@@ -701,7 +701,8 @@ bool mfma_supported(int d, int L, int P)
 
 size_t mfma_scratch_bytes(const Plan &p)
 {
-#define X(DD, PP_, LL) if (p.d == DD && p.P == PP_ && p.L == LL) return static_cast<size_t>(p.BH) * static_cast<size_t>(p.N) * Cfg<DD, PP_, LL>::LPP * 2;
+#define X(DD, PP_, LL) if (p.d == DD && p.P == PP_ && p.L == LL) \
+        return GradCfg<Cfg<DD, PP_, LL>>::TSPLIT == 1 ? 0 : static_cast<size_t>(p.BH) * static_cast<size_t>(p.N) * Cfg<DD, PP_, LL>::LPP * 2;
     RACE_SHAPES(X)
 #undef X
     return 0;
