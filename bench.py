@@ -42,9 +42,8 @@ def kernel_shares(w):
     return {
         "stream_forward": proj + 2 * U,      # projections, accumulate, read-out
         "stream_grad_v": proj + 2 * U,       # projections again, cotangent statistics, dV read-out
-        "grad_q": U,                         # dphi_Q and the chain rule through the soft assignment
-        "grad_k": U,                         # dphi_K, same
-        "dz_matmul": proj / 2,               # dX = dZ . W, launched once for dQ and once for dK
+        "grad_q": U + proj / 2,              # dphi_Q, the chain rule through the soft assignment, dQ = dz . W
+        "grad_k": U + proj / 2,              # dphi_K, same
         "stream_totals_kv": 0.0, "stream_totals_qg": 0.0, "segment_scan": 0.0,
     }
 
@@ -55,7 +54,7 @@ def kernel_shares(w):
 MEASURED_TRAFFIC = {
     ("bf16", 128, 8, 6, True): {
         "stream_totals_kv": 514.7, "segment_scan": 5.4, "stream_forward": 1030.7, "stream_totals_qg": 774.7,
-        "stream_grad_v": 1030.6, "grad_q": 2698.6, "dz_matmul": 384.2, "grad_k": 2698.6,
+        "stream_grad_v": 1030.6, "grad_q": 1542.7, "grad_k": 1542.7,
     },
 }
 
