@@ -20,6 +20,8 @@ Readings of the paper taken here (each is listed with its reason in the design n
   * The causal variant is inclusive (j <= i): Algorithm 2 adds key/value t to the
     running bucket statistics before query t reads them.
   * Den keeps the 1/L of Algorithm 1, step 7 (it cancels in O).
+  * beta is trained in the paper's experiments (Section 4), so the backward functions can also
+    return its cotangent; with W fixed and random it is the layer's only parameter gradient.
 """
 from __future__ import annotations
 
@@ -216,8 +218,18 @@ def _soft_hash_vjp(X, W, beta, L, P, dphi):
     return dz.reshape(X.shape[0], L * P) @ W                         # z = W x
 
 
-def backward_quadratic(Q, K, V, W, beta, L, P, causal, dO):
-    """Gradients of sum(dO * O) through the explicit N x N form.  Returns dQ, dK, dV."""
+def _soft_hash_vjp_beta(X, W, beta, L, P, dphi) -> float:
+    """Cotangent of the temperature beta (trained in the paper's experiments, Section 4): the corner
+    logits are beta * (u . v_r), so d(beta) = sum over tokens, tables and corners of ds_r (u . v_r)."""
+    u = np.tanh(project(X, W, L, P))
+    phi = soft_hash(X, W, beta, L, P)
+    ds = phi * (dphi - (phi * dphi).sum(axis=2, keepdims=True))
+    return float(np.einsum("nlr,rt,nlt->", ds, corners(P), u))
+
+
+def backward_quadratic(Q, K, V, W, beta, L, P, causal, dO, with_beta: bool = False):
+    """Gradients of sum(dO * O) through the explicit N x N form.  Returns dQ, dK, dV
+    (and d(beta) if with_beta)."""
     pq = soft_hash(Q, W, beta, L, P)
     pk = soft_hash(K, W, beta, L, P)
     S = np.einsum("ilr,jlr->ij", pq, pk) / L
@@ -233,10 +245,12 @@ def backward_quadratic(Q, K, V, W, beta, L, P, causal, dO):
     dpk = np.einsum("ij,ilr->jlr", dS, pq) / L
     dQ = _soft_hash_vjp(Q, W, beta, L, P, dpq)
     dK = _soft_hash_vjp(K, W, beta, L, P, dpk)
+    if with_beta:
+        return dQ, dK, dV, _soft_hash_vjp_beta(Q, W, beta, L, P, dpq) + _soft_hash_vjp_beta(K, W, beta, L, P, dpk)
     return dQ, dK, dV
 
 
-def backward_streaming(Q, K, V, W, beta, L, P, causal, dO):
+def backward_streaming(Q, K, V, W, beta, L, P, causal, dO, with_beta: bool = False):
     """Gradients in linear time with bucket-sized state only (nothing N x N, nothing N x R kept
     beyond phi itself).  Pass 1 runs left to right with the prefix statistics (A, B) and gives
     the cotangent of phi_Q; pass 2 runs right to left with the suffix statistics (dA, dB) of
@@ -279,7 +293,17 @@ def backward_streaming(Q, K, V, W, beta, L, P, causal, dO):
             dpk[:, l] = V @ dB.T + dA[None, :]
     dQ = _soft_hash_vjp(Q, W, beta, L, P, dpq)
     dK = _soft_hash_vjp(K, W, beta, L, P, dpk)
+    if with_beta:
+        return dQ, dK, dV, _soft_hash_vjp_beta(Q, W, beta, L, P, dpq) + _soft_hash_vjp_beta(K, W, beta, L, P, dpk)
     return dQ, dK, dV
+
+
+def finite_difference_beta(Q, K, V, W, beta, L, P, causal, dO, h: float = 1e-6) -> float:
+    """Central difference of loss = sum(dO * O) with respect to the temperature beta."""
+    def loss(b):
+        o, _ = forward_quadratic(Q, K, V, W, b, L, P, causal)
+        return float((dO * o).sum())
+    return (loss(beta + h) - loss(beta - h)) / (2 * h)
 
 
 def finite_difference(Q, K, V, W, beta, L, P, causal, dO, which: str, index, h: float = 1e-6) -> float:
@@ -313,11 +337,14 @@ def forward(Q, K, V, Ws, beta, L, P, causal):
     return O, den
 
 
-def backward(Q, K, V, Ws, beta, L, P, causal, dO):
+def backward(Q, K, V, Ws, beta, L, P, causal, dO, with_beta: bool = False):
+    """Returns dQ, dK, dV (and, if with_beta, d(beta) per (batch, head): shape (B, H); the derivative
+    with respect to one beta shared by everything is their sum)."""
     Bn, H, N, d = Q.shape
     dQ, dK, dV = np.empty_like(Q), np.empty_like(Q), np.empty_like(Q)
+    dbeta = np.zeros((Bn, H))
     for b in range(Bn):
         for h in range(H):
-            dQ[b, h], dK[b, h], dV[b, h] = backward_streaming(
-                Q[b, h], K[b, h], V[b, h], Ws[h], beta, L, P, causal, dO[b, h])
-    return dQ, dK, dV
+            dQ[b, h], dK[b, h], dV[b, h], dbeta[b, h] = backward_streaming(
+                Q[b, h], K[b, h], V[b, h], Ws[h], beta, L, P, causal, dO[b, h], with_beta=True)
+    return (dQ, dK, dV, dbeta) if with_beta else (dQ, dK, dV)

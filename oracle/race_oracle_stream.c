@@ -57,9 +57,10 @@ static void soft_hash(const double *x, const double *Wl, int d, int P, double be
     for (int r = 0; r < R; ++r) phi[r] /= sum;
 }
 
-/* cotangent of phi -> cotangent of x, added into dx: softmax, corner logits, tanh, W */
+/* cotangent of phi -> cotangent of x, added into dx: softmax, corner logits, tanh, W.
+ * The corner logits are beta * (u . v_r): the cotangent of beta, sum_r ds_r (u . v_r), is added to *dbeta. */
 static void soft_hash_vjp(const double *Wl, int d, int P, double beta, const double *u,
-                          const double *phi, const double *dphi, double *dx)
+                          const double *phi, const double *dphi, double *dx, double *dbeta)
 {
     const int R = 1 << P;
     double mean = 0.0;
@@ -70,6 +71,7 @@ static void soft_hash_vjp(const double *Wl, int d, int P, double beta, const dou
             double ds = phi[r] * (dphi[r] - mean);
             du += ((r >> t) & 1) ? ds : -ds;
         }
+        *dbeta += du * u[t];
         double dz = beta * du * (1.0 - u[t] * u[t]);
         for (int c = 0; c < d; ++c) dx[c] += dz * Wl[(size_t)t * d + c];
     }
@@ -164,11 +166,12 @@ int race_oracle_forward(int B, int H, long N, int d, int L, int P, double beta, 
     return fail;
 }
 
-/* Backward of loss = sum(dO * O).  O and den are the oracle's own forward results. */
+/* Backward of loss = sum(dO * O).  O and den are the oracle's own forward results.
+ * dbeta: (B*H) cotangents of the temperature, one per (batch, head). */
 int race_oracle_backward(int B, int H, long N, int d, int L, int P, double beta, int causal,
                          const double *Q, const double *K, const double *V, const double *W,
                          const double *O, const double *den, const double *dO,
-                         double *dQ, double *dK, double *dV)
+                         double *dQ, double *dK, double *dV, double *dbeta)
 {
     const int R = 1 << P;
     const int BH = B * H;
@@ -178,7 +181,8 @@ int race_oracle_backward(int B, int H, long N, int d, int L, int P, double beta,
     const size_t per_tab = (size_t)N * d;
     double *part = (double *)malloc(sizeof(double) * per_tab * 3 * (size_t)L * group);
     double *gn = (double *)malloc(sizeof(double) * (size_t)N * (d + 1) * group);
-    if (!part || !gn) { free(part); free(gn); return 1; }
+    double *pbeta = (double *)malloc(sizeof(double) * (size_t)L * group);      /* per (head of the group, table) */
+    if (!part || !gn || !pbeta) { free(part); free(gn); free(pbeta); return 1; }
     int fail = 0;
 
     for (int bh0 = 0; bh0 < BH; bh0 += group) {
@@ -218,6 +222,7 @@ int race_oracle_backward(int B, int H, long N, int d, int L, int P, double beta,
                     continue;
                 }
                 double *dphi = phi + R, *u = phi + 2 * R;
+                double db = 0.0;
                 if (!causal) {
                     for (long j = 0; j < N; ++j) {
                         soft_hash(k + j * d, Wl, d, P, beta, u, phi);
@@ -250,7 +255,7 @@ int race_oracle_backward(int B, int H, long N, int d, int L, int P, double beta,
                         for (int c = 0; c <= d; ++c) acc += row[c] * gt[i * (d + 1) + c];
                         dphi[r] = acc;
                     }
-                    soft_hash_vjp(Wl, d, P, beta, u, phi, dphi, pQ + i * d);
+                    soft_hash_vjp(Wl, d, P, beta, u, phi, dphi, pQ + i * d, &db);
                 }
                 /* pass 2, right to left: suffix statistics of the read-out cotangents -> dV, dK */
                 for (long j = N - 1; j >= 0; --j) {
@@ -271,8 +276,9 @@ int race_oracle_backward(int B, int H, long N, int d, int L, int P, double beta,
                         }
                         dphi[r] = acc;
                     }
-                    soft_hash_vjp(Wl, d, P, beta, u, phi, dphi, pK + j * d);
+                    soft_hash_vjp(Wl, d, P, beta, u, phi, dphi, pK + j * d, &db);
                 }
+                pbeta[(size_t)gi * L + l] = db;
                 free(S); free(dS); free(phi);
             }
         }
@@ -290,7 +296,14 @@ int race_oracle_backward(int B, int H, long N, int d, int L, int P, double beta,
                 }
             }
         }
+        if (dbeta) {                    /* tables added up in table order: independent of the thread count */
+            for (int gi = 0; gi < g; ++gi) {
+                double sb = 0.0;
+                for (int l = 0; l < L; ++l) sb += pbeta[(size_t)gi * L + l];
+                dbeta[bh0 + gi] = sb;
+            }
+        }
     }
-    free(part); free(gn);
+    free(part); free(gn); free(pbeta);
     return fail;
 }

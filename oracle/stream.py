@@ -21,7 +21,7 @@ def _load():
                   ctypes.c_double, ctypes.c_int]
         lib.race_oracle_forward.argtypes = common + [dp] * 6
         lib.race_oracle_forward.restype = ctypes.c_int
-        lib.race_oracle_backward.argtypes = common + [dp] * 10
+        lib.race_oracle_backward.argtypes = common + [dp] * 11
         lib.race_oracle_backward.restype = ctypes.c_int
         lib.race_oracle_threads.restype = ctypes.c_int
         _lib = lib
@@ -54,13 +54,15 @@ def forward(Q, K, V, W, beta, L, P, causal):
     return O, den
 
 
-def backward(Q, K, V, W, beta, L, P, causal, O, den, dO):
+def backward(Q, K, V, W, beta, L, P, causal, O, den, dO, with_beta: bool = False):
+    """Returns dQ, dK, dV and, if with_beta, the cotangent of the temperature per (batch, head), shape (B, H)."""
     Q, K, V, W, O, den, dO = map(_c, (Q, K, V, W, O, den, dO))
     B, H, N, d = Q.shape
     dQ, dK, dV = np.empty_like(Q), np.empty_like(Q), np.empty_like(Q)
+    dbeta = np.zeros((B, H))
     rc = _load().race_oracle_backward(B, H, N, d, L, P, float(beta), int(bool(causal)),
                                       _p(Q), _p(K), _p(V), _p(W), _p(O), _p(den), _p(dO),
-                                      _p(dQ), _p(dK), _p(dV))
+                                      _p(dQ), _p(dK), _p(dV), _p(dbeta))
     if rc:
         raise MemoryError("race_oracle_backward")
-    return dQ, dK, dV
+    return (dQ, dK, dV, dbeta) if with_beta else (dQ, dK, dV)

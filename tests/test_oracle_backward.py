@@ -89,3 +89,57 @@ def test_a_planted_mistake_is_caught():
     bad = ro._soft_hash_vjp(Q, W, beta, L, P, np.einsum("ij,jlr->ilr", dS_wrong, pk) / L)
     fd = ro.finite_difference(Q, K, V, W, beta, L, P, True, dO, "Q", (3, 1))
     assert abs(fd - good[3, 1]) < 1e-7 and abs(fd - bad[3, 1]) > 1e-4
+
+
+# ---------------------------------------------------------------- cotangent of the temperature beta
+@pytest.mark.parametrize("causal", [False, True])
+def test_beta_gradient_matches_central_differences(causal):
+    rng = np.random.default_rng(11)
+    N, d, L, P, beta = 9, 6, 3, 3, 1.7
+    Q, K, V, dO = (rng.standard_normal((N, d)) * 0.6 for _ in range(4))
+    W = rng.standard_normal((L * P, d))
+    *_, db = ro.backward_quadratic(Q, K, V, W, beta, L, P, causal, dO, with_beta=True)
+    fd = ro.finite_difference_beta(Q, K, V, W, beta, L, P, causal, dO)
+    assert abs(db - fd) <= 1e-7 * max(1.0, abs(fd))
+    *_, db_s = ro.backward_streaming(Q, K, V, W, beta, L, P, causal, dO, with_beta=True)
+    assert abs(db_s - db) <= 1e-12 * max(1.0, abs(db))
+
+
+def test_beta_gradient_by_hand_for_one_hyperplane():
+    # P = 1, L = 1: phi = (sigma(-2 beta u), sigma(2 beta u)); with two tokens, non-causal, everything is explicit
+    rng = np.random.default_rng(5)
+    d, beta = 3, 0.9
+    Q, K, V, dO = (rng.standard_normal((2, d)) for _ in range(4))
+    W = rng.standard_normal((1, d))
+    sig = lambda t: 1.0 / (1.0 + np.exp(-t))
+    def loss(b):
+        uq, uk = np.tanh(Q @ W[0]), np.tanh(K @ W[0])
+        pq = np.stack([sig(-2 * b * uq), sig(2 * b * uq)], axis=1)
+        pk = np.stack([sig(-2 * b * uk), sig(2 * b * uk)], axis=1)
+        S = pq @ pk.T
+        O = (S / S.sum(axis=1, keepdims=True)) @ V
+        return float((dO * O).sum())
+    h = 1e-6
+    fd = (loss(beta + h) - loss(beta - h)) / (2 * h)
+    *_, db = ro.backward_quadratic(Q, K, V, W, beta, 1, 1, False, dO, with_beta=True)
+    assert abs(db - fd) <= 1e-7 * max(1.0, abs(fd))
+
+
+def test_beta_gradient_c_oracle_matches_numpy_and_sums_over_heads():
+    from oracle import stream as oracle_stream
+    rng = np.random.default_rng(3)
+    B, H, N, d, L, P, beta = 2, 2, 40, 8, 3, 3, 2.5
+    Q, K, V, dO = (rng.standard_normal((B, H, N, d)) * 0.5 for _ in range(4))
+    Ws = [rng.standard_normal((L * P, d)) for _ in range(H)]
+    for causal in (False, True):
+        O, den = ro.forward(Q, K, V, Ws, beta, L, P, causal)
+        *_, db = ro.backward(Q, K, V, Ws, beta, L, P, causal, dO, with_beta=True)
+        *_, dbc = oracle_stream.backward(Q, K, V, np.stack(Ws), beta, L, P, causal, O, den, dO, with_beta=True)
+        assert db.shape == (B, H) and np.allclose(dbc, db, rtol=1e-10, atol=1e-12)
+        # one beta for the whole layer: the loss is a sum over (batch, head), so is its derivative
+        def loss(b):
+            o, _ = ro.forward(Q, K, V, Ws, b, L, P, causal)
+            return float((dO * o).sum())
+        h = 1e-6
+        fd = (loss(beta + h) - loss(beta - h)) / (2 * h)
+        assert abs(db.sum() - fd) <= 1e-6 * max(1.0, abs(fd))
