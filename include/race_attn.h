@@ -92,6 +92,19 @@ race_status_t race_attn_bwd(const race_attn_desc_t *desc, const void *Q, const v
                             const uint64_t *proj_seeds, void *dQ, void *dK, void *dV,
                             void *workspace, size_t workspace_bytes, race_stream_t stream);
 
+/* The same backward pass, which also returns the cotangent of the temperature: the paper trains beta
+ * (Section 4, "we treat beta ... as a trainable parameter"), and with W fixed and random it is the layer's only
+ * parameter.  The corner logits of Algorithm 1, step 4 are beta * (tanh(W x) . v_r), so
+ * d(loss)/d(beta) = sum over Q and K tokens, tables and corners of dlogit_r * (tanh(W x) . v_r).
+ * dbeta: DEVICE float (B, H), one partial derivative per (batch, head), written (not accumulated); the
+ * derivative with respect to a beta shared by all of them is the sum of the entries.  NULL = not wanted, which
+ * makes this call identical to race_attn_bwd.  Sums are formed in a fixed order (bit-reproducible).  Needs no
+ * more workspace than race_attn_bwd.  N == 0 writes nothing. */
+race_status_t race_attn_bwd_beta(const race_attn_desc_t *desc, const void *Q, const void *K, const void *V,
+                                 const void *O, const float *den, const void *dO,
+                                 const uint64_t *proj_seeds, void *dQ, void *dK, void *dV, float *dbeta,
+                                 void *workspace, size_t workspace_bytes, race_stream_t stream);
+
 /* Host-only: expands the seeds into W_host (HOST, float, (H, L*P, d)), the values the kernels
  * multiply with (Algorithm 1, step 2).  Generator: element e = row*d + col of head h is Gaussian
  * number (e mod 4) of block e/4 of Philox-4x32-10 with key = (low, high) 32 bits of the head's

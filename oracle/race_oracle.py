@@ -298,6 +298,25 @@ def backward_streaming(Q, K, V, W, beta, L, P, causal, dO, with_beta: bool = Fal
     return dQ, dK, dV
 
 
+def beta_cotangent_l1(Q, K, V, W, beta, L, P, causal, dO) -> float:
+    """Sum of the absolute values of the terms ds_r (u . v_r) whose sum is d(beta) (N x N form): the scale
+    against which rounding errors of an implementation add up when the terms cancel."""
+    pq = soft_hash(Q, W, beta, L, P)
+    pk = soft_hash(K, W, beta, L, P)
+    S = np.einsum("ilr,jlr->ij", pq, pk) / L
+    M = np.tril(np.ones_like(S)) if causal else np.ones_like(S)
+    S = S * M
+    den = S.sum(axis=1)
+    O = (S / den[:, None]) @ V
+    dS = M * ((dO @ V.T) - (dO * O).sum(axis=1)[:, None]) / den[:, None]
+    total = 0.0
+    for X, phi, dphi in ((Q, pq, np.einsum("ij,jlr->ilr", dS, pk) / L), (K, pk, np.einsum("ij,ilr->jlr", dS, pq) / L)):
+        u = np.tanh(project(X, W, L, P))
+        ds = phi * (dphi - (phi * dphi).sum(axis=2, keepdims=True))
+        total += float(np.abs(np.einsum("nlr,rt->nlt", ds, corners(P)) * u).sum())
+    return total
+
+
 def finite_difference_beta(Q, K, V, W, beta, L, P, causal, dO, h: float = 1e-6) -> float:
     """Central difference of loss = sum(dO * O) with respect to the temperature beta."""
     def loss(b):

@@ -52,6 +52,8 @@ def lib() -> ctypes.CDLL:
         L.race_attn_fwd.restype = ctypes.c_int
         L.race_attn_bwd.argtypes = [dp, vp, vp, vp, vp, fp, vp, u64p, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.race_attn_bwd.restype = ctypes.c_int
+        L.race_attn_bwd_beta.argtypes = [dp, vp, vp, vp, vp, fp, vp, u64p, vp, vp, vp, fp, vp, ctypes.c_size_t, vp]
+        L.race_attn_bwd_beta.restype = ctypes.c_int
         L.race_attn_expand_projection.argtypes = [dp, u64p, ctypes.POINTER(ctypes.c_float)]
         L.race_attn_expand_projection.restype = ctypes.c_int
         L.race_attn_debug_hash.argtypes = [dp, vp, u64p, u8p, fp, vp, ctypes.c_size_t, vp]
@@ -168,6 +170,29 @@ def race_attn_bwd(desc: RaceAttnDesc, Q, K, V, O, den, dO, proj_seeds: Sequence[
     if st != RACE_OK:
         raise RaceAttnError(st, "race_attn_bwd")
     return dQ, dK, dV
+
+
+def race_attn_bwd_beta(desc: RaceAttnDesc, Q, K, V, O, den, dO, proj_seeds: Sequence[int], dQ=None, dK=None, dV=None,
+                       dbeta=None, workspace=None, stream=None):
+    """race_attn_bwd plus the cotangent of the temperature per (batch, head): returns dQ, dK, dV, dbeta (B, H)."""
+    torch = _torch()
+    for t, n in ((Q, "Q"), (K, "K"), (V, "V"), (O, "O"), (dO, "dO")):
+        _check_tensor(t, desc, n)
+    _check_tensor(den, desc, "den", (desc.B, desc.H, desc.N), torch.float32)
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(K) if dK is None else dK
+    dV = torch.empty_like(V) if dV is None else dV
+    for t, n in ((dQ, "dQ"), (dK, "dK"), (dV, "dV")):
+        _check_tensor(t, desc, n)
+    dbeta = torch.empty((desc.B, desc.H), dtype=torch.float32, device=V.device) if dbeta is None else dbeta
+    _check_tensor(dbeta, desc, "dbeta", (desc.B, desc.H), torch.float32)
+    workspace, nbytes = _workspace(desc, workspace, V.device)
+    st = lib().race_attn_bwd_beta(ctypes.byref(desc), Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(),
+                                  den.data_ptr(), dO.data_ptr(), _seeds(proj_seeds), dQ.data_ptr(), dK.data_ptr(),
+                                  dV.data_ptr(), dbeta.data_ptr(), workspace.data_ptr(), nbytes, _stream(stream))
+    if st != RACE_OK:
+        raise RaceAttnError(st, "race_attn_bwd_beta")
+    return dQ, dK, dV, dbeta
 
 
 def race_attn_debug_hash(desc: RaceAttnDesc, X, proj_seeds: Sequence[int], want_phi: bool = False,

@@ -33,6 +33,9 @@ struct Plan {
     size_t bytes_state;
     size_t off_part;    // per-table partial results (simple family only)
     size_t bytes_part;
+    size_t off_dbeta;   // partial cotangents of beta: (2 sides, BH, dbeta_parts) fp32, backward only
+    size_t bytes_dbeta;
+    int dbeta_parts;    // partial sums per (side, batch*head): one per workgroup of the gradient kernels
     size_t total;
 };
 
@@ -53,6 +56,9 @@ struct ProfileScope {
     hipStream_t st_;
 };
 
+// dbeta[bh] = sum over the two sides and the dbeta_parts partial sums of part, in index order (simple_kernels.hip).
+hipError_t reduce_dbeta(const Plan &p, const float *part, float *dbeta, hipStream_t st);
+
 // Plain copy of known size (simple_kernels.hip); bytes is a multiple of 16.
 hipError_t calibration_copy(void *dst, const void *src, size_t bytes, hipStream_t st);
 
@@ -60,7 +66,8 @@ hipError_t calibration_copy(void *dst, const void *src, size_t bytes, hipStream_
 hipError_t simple_fwd(const Plan &p, const void *Q, const void *K, const void *V, void *O, float *den,
                       char *ws, hipStream_t st);
 hipError_t simple_bwd(const Plan &p, const void *Q, const void *K, const void *V, const void *O,
-                      const float *den, const void *dO, void *dQ, void *dK, void *dV, char *ws, hipStream_t st);
+                      const float *den, const void *dO, void *dQ, void *dK, void *dV, float *dbeta, char *ws,
+                      hipStream_t st);
 hipError_t simple_hash(const Plan &p, const void *X, uint8_t *codes, float *phi, char *ws, hipStream_t st);
 hipError_t simple_buckets(const Plan &p, const void *K, const void *V, float *A, float *Bsum, char *ws,
                           hipStream_t st);
@@ -74,7 +81,9 @@ void mfma_pack_projection(const Plan &p, const float *W, void *image);   // host
 hipError_t mfma_fwd(const Plan &p, const void *Q, const void *K, const void *V, void *O, float *den,
                     char *ws, hipStream_t st);
 hipError_t mfma_bwd(const Plan &p, const void *Q, const void *K, const void *V, const void *O,
-                    const float *den, const void *dO, void *dQ, void *dK, void *dV, char *ws, hipStream_t st);
+                    const float *den, const void *dO, void *dQ, void *dK, void *dV, float *dbeta, char *ws,
+                    hipStream_t st);
+int mfma_dbeta_parts(const Plan &p);           // workgroups per (side, batch*head) of the gradient kernels
 hipError_t mfma_hash(const Plan &p, const void *X, uint8_t *codes, float *phi, char *ws, hipStream_t st);
 hipError_t mfma_buckets(const Plan &p, const void *K, const void *V, float *A, float *Bsum, char *ws,
                         hipStream_t st);

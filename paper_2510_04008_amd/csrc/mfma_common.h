@@ -96,6 +96,7 @@ struct KArgs {
     const bf16raw *WpT;    // (H, D, LPP) bf16
     float *state;          // (BH, nseg, STATE) fp32
     bf16raw *dZ;           // (BH, N, LPP) bf16: cotangents of the projections (backward only)
+    float *dbeta_part;     // (2, BH, workgroups per head-batch) fp32: partial cotangents of beta (backward only)
 };
 
 // ---------------------------------------------------------------- small helpers
@@ -289,9 +290,10 @@ __device__ __forceinline__ constexpr int zslot(int j, int t)
 }
 
 // Per-bit masses of one table: p[t] = sigmoid(2 beta tanh z_t) (mass on the +1 side), q[t] = 1 - p[t],
-// computed without cancellation; sech2[t] = 1 - tanh^2 z_t.
+// computed without cancellation; sech2[t] = 1 - tanh^2 z_t; u[t] = tanh z_t.
 template <class C>
-__device__ __forceinline__ void bit_masses(const f32x16 &z, int j, float beta, float *p, float *q, float *sech2)
+__device__ __forceinline__ void bit_masses(const f32x16 &z, int j, float beta, float *p, float *q, float *sech2,
+                                           float *u = nullptr)
 {
 #pragma unroll
     for (int t = 0; t < C::P; ++t) {
@@ -305,6 +307,7 @@ __device__ __forceinline__ void bit_masses(const f32x16 &z, int j, float beta, f
         p[t] = pos ? big : small;
         q[t] = pos ? small : big;
         if (sech2) sech2[t] = 4.0f * e2 * inv * inv;
+        if (u) u[t] = pos ? ua : -ua;
     }
 }
 

@@ -81,7 +81,8 @@ struct GradLds {
     static constexpr int dz = wp + C::LPP * C::XS * 2;                  // [32][DZS] bf16
     static constexpr int sr = dz + kTile * DZS * 2;                     // [32] fp32 extra column of reader-Y
     static constexpr int sw = sr + kTile * 4;                           // [32] fp32 extra column of writer-Y
-    static constexpr int PMS = 3 * C::PP;                               // floats per (table, token): p, q, sech^2, each padded
+    static constexpr int PMS = 4 * C::PP + 4;                           // floats per (table, token): p, q, sech^2, tanh, each padded
+                                                                        // to PP; + 4 keeps 16-byte reads of 16 tokens on distinct banks
     static constexpr int pm = (sw + kTile * 4 + 15) & ~15;              // [TABLES][32][PMS] fp32: per-bit masses of the reader
     static constexpr int part = pm + G::TABLES * kTile * PMS * 4;       // [kWaves][32][8] fp32: partial (m, E_t) of table shares
     static constexpr int yr = part + (G::WPT > 1 ? kWaves * kTile * 8 * 4 : 0);   // [32][XS] reader-Y rows, pair-interleaved columns
@@ -176,6 +177,7 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
     };
     if (ntiles > 0) fetch(0);
 
+    float dbeta_acc = 0.f;    // this lane's share of the cotangent of beta: sum of (E_t - m (p_t - q_t)) tanh z_t
     GRAD_PHASE_DECL
     for (int it = 0; it < ntiles; ++it) {
         const int64_t t0 = tile_t0(it);
@@ -220,16 +222,17 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
             for (int j = 0; j < C::TPL; ++j) {
                 if ((th * G::NGW + pg) * C::TPG + h * C::TPL + j >= C::L) break;
                 if (j % G::RJ != rj) continue;
-                float p[C::PP], q[C::PP], s2[C::PP];
+                float p[C::PP], q[C::PP], s2[C::PP], u[C::PP];
 #pragma unroll
-                for (int t = 0; t < C::PP; ++t) p[t] = q[t] = s2[t] = 0.f;
+                for (int t = 0; t < C::PP; ++t) p[t] = q[t] = s2[t] = u[t] = 0.f;
                 float *dst = pm + ((pg * C::TPG + h * C::TPL + j) * kTile + ln) * S::PMS;
-                bit_masses<C>(zr, j, a.beta, p, q, s2);
+                bit_masses<C>(zr, j, a.beta, p, q, s2, u);
 #pragma unroll
                 for (int t = 0; t < C::PP; t += 4) {
                     *reinterpret_cast<float4 *>(dst + t) = float4{p[t], p[t + 1], p[t + 2], p[t + 3]};
                     *reinterpret_cast<float4 *>(dst + C::PP + t) = float4{q[t], q[t + 1], q[t + 2], q[t + 3]};
                     *reinterpret_cast<float4 *>(dst + 2 * C::PP + t) = float4{s2[t], s2[t + 1], s2[t + 2], s2[t + 3]};
+                    *reinterpret_cast<float4 *>(dst + 3 * C::PP + t) = float4{u[t], u[t + 1], u[t + 2], u[t + 3]};
                 }
             }
         }
@@ -263,11 +266,15 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
         // ---- per 32-row tile of this wavefront: cotangent of the reader's assignments, transposed (lane = token,
         //      register v = bucket row r_own + 32 mr + acc_row(v, h)), then straight back through the corner
         //      softmax (Algorithm 1, step 4) in those registers: with w_c = phi_c dphi_c over the corners c of a
-        //      table, m = sum_c w_c and E_t = sum_c v_{c,t} w_c.  Register v of lane half h is corner
+        //      table, m = sum_c w_c and, per bit t, G_t = sum of w_c over the corners on the bit's MINOR side
+        //      (the side with the smaller mass min(p_t, q_t)).  The cotangent of u_t = tanh z_t is
+        //      beta (E_t - m (p_t - q_t)) with E_t = sum_c v_{c,t} w_c; written as
+        //      +-2 beta (small_t (m - G_t) - big_t G_t) it has no cancellation when the bit is saturated
+        //      (small_t ~ 1e-7 at beta = 8), which the cotangent of beta needs.  Register v of lane half h is corner
         //      co + 8 (v/4 mod KM) + 4h + v%4 of table tl0 + (32 mr + 8 (v/4)) / R: bits 0,1 come from v, bit 2
         //      from h, bits 3.. from v, the bits above from the tile and the wavefront's share.  phi_c is the
         //      product over bits of p_t (bit set) or q_t (Section 3.3: the corner softmax factorises).
-        float rec[G::TWW][8];          // [m, E_0 .. E_{P-1}] of the lane's token per table of the wavefront (lane partials)
+        float rec[G::TWW][8];          // [m, G_0 .. G_{P-1}] of the lane's token per table of the wavefront (lane partials)
 #pragma unroll
         for (int i = 0; i < G::TWW; ++i) {
 #pragma unroll
@@ -317,7 +324,10 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
 #pragma unroll
                 for (int t = 3 + G::MB; t < C::P; ++t) F *= ((co >> t) & 1) ? p[t] : q[t];
                 const float Fl[4] = {F * q[0] * q[1], F * p[0] * q[1], F * q[0] * p[1], F * p[0] * p[1]};
-                float m = 0.f, E0 = 0.f, E1 = 0.f, Em[2] = {0.f, 0.f};
+                bool mn[C::PP];                    // the minor side of bit t is the value 1 (else the value 0)
+#pragma unroll
+                for (int t = 0; t < C::PP; ++t) mn[t] = p[t] < q[t];
+                float m = 0.f, G0 = 0.f, G1 = 0.f, Gm[2] = {0.f, 0.f};
 #pragma unroll
                 for (int k = 0; k < G::KM; ++k) {
                     float mid = 1.f;
@@ -327,21 +337,21 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
                     const float w0 = Fl[0] * dP[v0], w1 = Fl[1] * dP[v0 + 1], w2 = Fl[2] * dP[v0 + 2], w3 = Fl[3] * dP[v0 + 3];
                     const float s01 = w0 + w1, s23 = w2 + w3;
                     const float c = mid * (s01 + s23);
-                    E0 = fmaf(mid, (w1 - w0) + (w3 - w2), E0);
-                    E1 = fmaf(mid, s23 - s01, E1);
+                    G0 = fmaf(mid, mn[0] ? w1 + w3 : w0 + w2, G0);
+                    G1 = fmaf(mid, mn[1] ? s23 : s01, G1);
                     m += c;
 #pragma unroll
-                    for (int b = 0; b < G::MB; ++b) Em[b] += ((k >> b) & 1) ? c : -c;
+                    for (int b = 0; b < G::MB; ++b) Gm[b] += (mn[3 + b] == (((k >> b) & 1) != 0)) ? c : 0.f;
                 }
                 // lane partials; bit 2 is the lane half, the bits above the tile's are uniform
                 rec[ti][0] += m;
-                rec[ti][1] += E0;
-                rec[ti][2] += E1;
-                rec[ti][3] += h ? m : -m;
+                rec[ti][1] += G0;
+                rec[ti][2] += G1;
+                rec[ti][3] += (mn[2] == (h != 0)) ? m : 0.f;
 #pragma unroll
-                for (int b = 0; b < G::MB; ++b) rec[ti][4 + b] += Em[b];
+                for (int b = 0; b < G::MB; ++b) rec[ti][4 + b] += Gm[b];
 #pragma unroll
-                for (int t = 3 + G::MB; t < C::P; ++t) rec[ti][1 + t] += ((co >> t) & 1) ? m : -m;
+                for (int t = 3 + G::MB; t < C::P; ++t) rec[ti][1 + t] += (mn[t] == (((co >> t) & 1) != 0)) ? m : 0.f;
             }
         }
         // the two lane halves hold the two values of bit 2: add them up
@@ -380,7 +390,7 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
         __syncthreads();        // partial sums are visible; the tiles of this step are dead from here on
         GRAD_PHASE(7)
 
-        // ---- finish per (token, table): du_t = beta (E_t - m (p_t - q_t)),  dz_t = du_t (1 - tanh^2 z_t);
+        // ---- finish per (token, table): du_t = +-2 beta (small_t (m - G_t) - big_t G_t),  dz_t = du_t (1 - tanh^2 z_t);
         //      lane half h' takes the padded projection slots 4h' .. 4h'+3
         if (ro == 0) {
 #pragma unroll
@@ -399,14 +409,21 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
                 const float4 p4 = *reinterpret_cast<const float4 *>(src);
                 const float4 q4 = *reinterpret_cast<const float4 *>(src + C::PP);
                 const float4 s4 = *reinterpret_cast<const float4 *>(src + 2 * C::PP);
-                const float pq[4] = {p4.x - q4.x, p4.y - q4.y, p4.z - q4.z, p4.w - q4.w};
+                const float4 u4 = *reinterpret_cast<const float4 *>(src + 3 * C::PP);
+                const float pp[4] = {p4.x, p4.y, p4.z, p4.w}, qq[4] = {q4.x, q4.y, q4.z, q4.w};
                 const float s2[4] = {s4.x, s4.y, s4.z, s4.w};
+                const float uu[4] = {u4.x, u4.y, u4.z, u4.w};
                 float dzv[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    // E of slot 4h + e is rec[1 + 4h + e]; slot 7 is padding (P <= 7) and has no entry
-                    const float Et = h ? (e < 3 ? rec[ti][e < 3 ? 5 + e : 0] : 0.f) : rec[ti][1 + e];
-                    dzv[e] = a.beta * (Et - rec[ti][0] * pq[e]) * s2[e];       // padded slots: s2 = 0
+                    // G of slot 4h + e is rec[1 + 4h + e]; slot 7 is padding (P <= 7) and has no entry
+                    const float Gt = h ? (e < 3 ? rec[ti][e < 3 ? 5 + e : 0] : 0.f) : rec[ti][1 + e];
+                    const bool minor1 = pp[e] < qq[e];                          // same predicate as where G was summed
+                    const float small = minor1 ? pp[e] : qq[e], big = minor1 ? qq[e] : pp[e];
+                    const float half = small * (rec[ti][0] - Gt) - big * Gt;
+                    const float du = minor1 ? -2.f * half : 2.f * half;         // cotangent of u_t up to the factor beta
+                    dzv[e] = a.beta * du * s2[e];                               // padded slots: p = q = s2 = 0
+                    dbeta_acc = fmaf(du, uu[e], dbeta_acc);                     // ... and tanh = 0
                 }
                 // slot 4c.. of the lane-half hh's j-th table is projection row 8 (slots-per-table/4 * j + c) + 4 hh of its group
                 const int gl = tl / C::TPG, tg = tl % C::TPG, hh = tg / C::TPL, j = tg % C::TPL;
@@ -455,6 +472,20 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
         GRAD_PHASE(12)
         // no barrier here: the next step's loads-to-LDS touch none of dz, pm, part or the staging tiles, and its
         // production (which rewrites pm) comes after the next barrier
+    }
+    // ---- cotangent of beta: lanes -> wavefront (shuffles) -> workgroup (LDS, wavefront order) -> one workspace slot
+    {
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) dbeta_acc += __shfl_xor(dbeta_acc, m, 64);
+        __syncthreads();
+        if (lane == 0) sr[w] = dbeta_acc;
+        __syncthreads();
+        if (tid == 0) {
+            float s = 0.f;
+            for (int i = 0; i < kWaves; ++i) s += sr[i];
+            const int wgs = gridDim.x * gridDim.z;      // workgroups per (side, batch*head)
+            a.dbeta_part[(static_cast<size_t>(SIDE) * gridDim.y + bh) * wgs + seg * gridDim.z + th] = s;
+        }
     }
     GRAD_PHASE_PRINT()
 }

@@ -538,6 +538,7 @@ KArgs make_kargs(const Plan &p, char *ws)
     a.WpT = a.Wp + static_cast<size_t>(p.H) * C::LPP * C::D;
     a.state = reinterpret_cast<float *>(ws + p.off_stateA);
     a.dZ = reinterpret_cast<bf16raw *>(ws + p.off_part);
+    a.dbeta_part = reinterpret_cast<float *>(ws + p.off_dbeta);
     return a;
 }
 
@@ -613,7 +614,7 @@ hipError_t launch_grad(const Plan &p, KArgs a, const void *Q, const void *K, con
 
 template <class C>
 hipError_t bwd_t(const Plan &p, const void *Q, const void *K, const void *V, const void *O, const float *den,
-                 const void *dO, void *dQ, void *dK, void *dV, char *ws, hipStream_t st)
+                 const void *dO, void *dQ, void *dK, void *dV, float *dbeta, char *ws, hipStream_t st)
 {
     KArgs a = make_kargs<C>(p, ws);
     KArgs b = a;
@@ -626,6 +627,7 @@ hipError_t bwd_t(const Plan &p, const void *Q, const void *K, const void *V, con
     RACE_TRY((launch_stream<C, kGradV>(p, b, K, Q, dO, O, den, dV, nullptr, st)));
     RACE_TRY((launch_grad<C, 0>(p, a, Q, K, V, O, den, dO, dQ, st)));
     RACE_TRY((launch_grad<C, 1>(p, b, Q, K, V, O, den, dO, dK, st)));
+    if (dbeta) RACE_TRY(reduce_dbeta(p, a.dbeta_part, dbeta, st));
     return hipSuccess;
 }
 
@@ -731,10 +733,18 @@ hipError_t mfma_fwd(const Plan &p, const void *Q, const void *K, const void *V, 
     return hipErrorNotSupported;
 }
 
-hipError_t mfma_bwd(const Plan &p, const void *Q, const void *K, const void *V, const void *O, const float *den,
-                    const void *dO, void *dQ, void *dK, void *dV, char *ws, hipStream_t st)
+int mfma_dbeta_parts(const Plan &p)
 {
-#define X(DD, PP_, LL) if (p.d == DD && p.P == PP_ && p.L == LL) return bwd_t<Cfg<DD, PP_, LL>>(p, Q, K, V, O, den, dO, dQ, dK, dV, ws, st);
+#define X(DD, PP_, LL) if (p.d == DD && p.P == PP_ && p.L == LL) return p.nseg * GradCfg<Cfg<DD, PP_, LL>>::TSPLIT;
+    RACE_SHAPES(X)
+#undef X
+    return 0;
+}
+
+hipError_t mfma_bwd(const Plan &p, const void *Q, const void *K, const void *V, const void *O, const float *den,
+                    const void *dO, void *dQ, void *dK, void *dV, float *dbeta, char *ws, hipStream_t st)
+{
+#define X(DD, PP_, LL) if (p.d == DD && p.P == PP_ && p.L == LL) return bwd_t<Cfg<DD, PP_, LL>>(p, Q, K, V, O, den, dO, dQ, dK, dV, dbeta, ws, st);
     RACE_SHAPES(X)
 #undef X
     return hipErrorNotSupported;

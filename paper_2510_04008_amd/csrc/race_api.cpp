@@ -205,6 +205,7 @@ race_status_t make_plan(const race_attn_desc_t *desc, Plan *pl)
         const size_t fwd_part = static_cast<size_t>(p.BH) * p.L * n * (p.d + 1) * sizeof(float);
         const size_t bwd_part = static_cast<size_t>(p.BH) * p.L * n * p.d * sizeof(float) * 3;
         p.bytes_part = align256(fwd_part > bwd_part ? fwd_part : bwd_part);
+        p.dbeta_parts = p.L * p.nseg;
     } else {
         // two workgroups' worth of segments per CU and head-batch; multiples of the 32-token tile
         int64_t want = (512 + p.BH - 1) / p.BH;
@@ -217,12 +218,15 @@ race_status_t make_plan(const race_attn_desc_t *desc, Plan *pl)
         p.bytes_W = align256(mfma_projection_bytes(p));
         p.bytes_state = align256(static_cast<size_t>(p.BH) * p.nseg * p.LR * (p.d + 1) * sizeof(float));
         p.bytes_part = align256(mfma_scratch_bytes(p));
+        p.dbeta_parts = mfma_dbeta_parts(p);
     }
+    p.bytes_dbeta = align256(static_cast<size_t>(2) * p.BH * p.dbeta_parts * sizeof(float));
     p.off_W = 0;
     p.off_stateA = p.off_W + p.bytes_W;
     p.off_stateB = p.off_stateA + p.bytes_state;
     p.off_part = p.off_stateB + p.bytes_state;
-    p.total = p.off_part + p.bytes_part;
+    p.off_dbeta = p.off_part + p.bytes_part;
+    p.total = p.off_dbeta + p.bytes_dbeta;
     *pl = p;
     return RACE_OK;
 }
@@ -307,18 +311,28 @@ race_status_t race_attn_bwd(const race_attn_desc_t *desc, const void *Q, const v
                             void *dQ, void *dK, void *dV, void *workspace, size_t workspace_bytes,
                             race_stream_t stream)
 {
+    return race_attn_bwd_beta(desc, Q, K, V, O, den, dO, proj_seeds, dQ, dK, dV, nullptr, workspace, workspace_bytes,
+                              stream);
+}
+
+race_status_t race_attn_bwd_beta(const race_attn_desc_t *desc, const void *Q, const void *K, const void *V,
+                                 const void *O, const float *den, const void *dO, const uint64_t *proj_seeds,
+                                 void *dQ, void *dK, void *dV, float *dbeta, void *workspace,
+                                 size_t workspace_bytes, race_stream_t stream)
+{
     Plan p;
     race_status_t s = make_plan(desc, &p);
     if (s != RACE_OK) return s;
     if (p.N == 0) return RACE_OK;      // nothing to do, pointers may be null
     if (!Q || !K || !V || !O || !den || !dO || !proj_seeds || !dQ || !dK || !dV) return RACE_ERR_INVALID_ARG;
     if (any_equal({dQ, dK, dV}, {Q, K, V, O, den, dO, dQ, dK, dV})) return RACE_ERR_INVALID_ARG;
+    if (dbeta && any_equal({dbeta}, {Q, K, V, O, den, dO, dQ, dK, dV, dbeta})) return RACE_ERR_INVALID_ARG;
     if ((s = check_workspace(p, workspace, workspace_bytes, p.total)) != RACE_OK) return s;
     char *ws = static_cast<char *>(workspace);
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     if ((s = upload_projection(p, proj_seeds, ws, st)) != RACE_OK) return s;
-    hipError_t e = (p.family == kFamilyMfma) ? mfma_bwd(p, Q, K, V, O, den, dO, dQ, dK, dV, ws, st)
-                                             : simple_bwd(p, Q, K, V, O, den, dO, dQ, dK, dV, ws, st);
+    hipError_t e = (p.family == kFamilyMfma) ? mfma_bwd(p, Q, K, V, O, den, dO, dQ, dK, dV, dbeta, ws, st)
+                                             : simple_bwd(p, Q, K, V, O, den, dO, dQ, dK, dV, dbeta, ws, st);
     return e == hipSuccess ? RACE_OK : hip_failed(e, "race_attn_bwd launch");
 }
 

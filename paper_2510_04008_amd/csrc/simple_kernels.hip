@@ -159,8 +159,10 @@ __device__ __forceinline__ void accumulate_token(const Args &a, float *S, const 
 }
 
 // Cotangent of phi -> cotangent of z (softmax over corners, corner logits, tanh).  dphi in LDS.
-// Leaves dz[P] in LDS (followed by a barrier).
-__device__ void soft_hash_vjp(const Args &a, const float *phi, const float *sech2, const float *dphi, float *dz)
+// Leaves dz[P] in LDS (followed by a barrier).  Thread t < P also adds its bit's share of the cotangent of
+// beta, du_t * u_t (the corner logits are beta * (u . v_r)), to dbeta_acc.
+__device__ void soft_hash_vjp(const Args &a, const float *phi, const float *sech2, const float *u, const float *dphi,
+                              float *dz, float &dbeta_acc)
 {
     if (threadIdx.x < a.P) {
         const int t = threadIdx.x;
@@ -172,8 +174,22 @@ __device__ void soft_hash_vjp(const Args &a, const float *phi, const float *sech
             du += ((r >> t) & 1) ? ds : -ds;
         }
         dz[t] = a.beta * du * sech2[t];
+        dbeta_acc = fmaf(du, u[t], dbeta_acc);
     }
     __syncthreads();
+}
+
+// Sum of the first P threads' dbeta_acc, in thread order, to one workspace slot (end of a gradient kernel).
+__device__ void store_dbeta_partial(const Args &a, float dbeta_acc, float *scratch, float *slot)
+{
+    __syncthreads();
+    if (threadIdx.x < a.P) scratch[threadIdx.x] = dbeta_acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float s = 0.f;
+        for (int t = 0; t < a.P; ++t) s += scratch[t];
+        *slot = s;
+    }
 }
 
 __device__ __forceinline__ size_t state_index(const Args &a, int bh, int l, int seg)
@@ -300,7 +316,7 @@ __global__ void simple_fwd_combine(Args a, int BH, const float *part, T *O, floa
 template <typename T>
 __global__ __launch_bounds__(kThreads) void simple_bwd_query(Args a, const T *Q, const T *K, const T *V,
                                                              const T *O, const float *den, const T *dO,
-                                                             const float *state, float *partQ)
+                                                             const float *state, float *partQ, float *dbeta_part)
 {
     extern __shared__ float lds[];
     Smem sm(lds, a);
@@ -312,6 +328,7 @@ __global__ __launch_bounds__(kThreads) void simple_bwd_query(Args a, const T *Q,
     const int64_t t_begin = seg * a.seg_len;
     const int64_t t_end = (t_begin + a.seg_len < a.N) ? t_begin + a.seg_len : a.N;
     HashView hk(sm.ha, a), hq(sm.hb, a);
+    float dbeta_acc = 0.f;          // threads t < P: this workgroup's share of the cotangent of beta, bit t
     float *out = partQ + (static_cast<size_t>(bh) * a.L + l) * a.N * a.d;
     for (int64_t t0 = t_begin; t0 < t_end; t0 += a.TT) {
         const int nt = (t_end - t0 < a.TT) ? static_cast<int>(t_end - t0) : a.TT;
@@ -337,7 +354,7 @@ __global__ __launch_bounds__(kThreads) void simple_bwd_query(Args a, const T *Q,
                 sm.dphi[r] = acc;
             }
             __syncthreads();
-            soft_hash_vjp(a, hq.phi + tok * a.R, hq.s + tok * a.P, sm.dphi, sm.dz);
+            soft_hash_vjp(a, hq.phi + tok * a.R, hq.s + tok * a.P, hq.u + tok * a.P, sm.dphi, sm.dz, dbeta_acc);
             for (int c = threadIdx.x; c < a.d; c += kThreads) {
                 float acc = 0.f;
                 for (int t = 0; t < a.P; ++t) acc = fmaf(sm.dz[t], Wl[t * a.d + c], acc);
@@ -346,6 +363,8 @@ __global__ __launch_bounds__(kThreads) void simple_bwd_query(Args a, const T *Q,
             __syncthreads();
         }
     }
+    // side 0 (queries) of the (2, BH, L * nseg) partial cotangents of beta
+    store_dbeta_partial(a, dbeta_acc, sm.dphi, dbeta_part + (static_cast<size_t>(bh) * a.L + l) * a.nseg + seg);
 }
 
 // Backward, key/value side, one segment of one table, right to left: with the suffix statistics
@@ -354,7 +373,8 @@ __global__ __launch_bounds__(kThreads) void simple_bwd_query(Args a, const T *Q,
 template <typename T>
 __global__ __launch_bounds__(kThreads) void simple_bwd_keyvalue(Args a, const T *Q, const T *K, const T *V,
                                                                 const T *O, const float *den, const T *dO,
-                                                                const float *state, float *partK, float *partV)
+                                                                const float *state, float *partK, float *partV,
+                                                                float *dbeta_part)
 {
     extern __shared__ float lds[];
     Smem sm(lds, a);
@@ -366,6 +386,7 @@ __global__ __launch_bounds__(kThreads) void simple_bwd_keyvalue(Args a, const T 
     const int64_t t_begin = seg * a.seg_len;
     const int64_t t_end = (t_begin + a.seg_len < a.N) ? t_begin + a.seg_len : a.N;
     HashView hk(sm.ha, a), hq(sm.hb, a);
+    float dbeta_acc = 0.f;          // threads t < P: this workgroup's share of the cotangent of beta, bit t
     float *outK = partK + (static_cast<size_t>(bh) * a.L + l) * a.N * a.d;
     float *outV = partV + (static_cast<size_t>(bh) * a.L + l) * a.N * a.d;
     const int64_t ntiles = (t_end - t_begin + a.TT - 1) / a.TT;
@@ -398,7 +419,7 @@ __global__ __launch_bounds__(kThreads) void simple_bwd_keyvalue(Args a, const T 
                 sm.dphi[r] = acc;
             }
             __syncthreads();
-            soft_hash_vjp(a, phi, hk.s + tok * a.P, sm.dphi, sm.dz);
+            soft_hash_vjp(a, phi, hk.s + tok * a.P, hk.u + tok * a.P, sm.dphi, sm.dz, dbeta_acc);
             for (int c = threadIdx.x; c < a.d; c += kThreads) {
                 float acc = 0.f;
                 for (int t = 0; t < a.P; ++t) acc = fmaf(sm.dz[t], Wl[t * a.d + c], acc);
@@ -407,6 +428,9 @@ __global__ __launch_bounds__(kThreads) void simple_bwd_keyvalue(Args a, const T 
             __syncthreads();
         }
     }
+    // side 1 (keys)
+    store_dbeta_partial(a, dbeta_acc, sm.dphi,
+                        dbeta_part + ((static_cast<size_t>(gridDim.z) + bh) * a.L + l) * a.nseg + seg);
 }
 
 template <typename T>
@@ -534,10 +558,11 @@ hipError_t fwd_impl(const Plan &p, const T *Q, const T *K, const T *V, T *O, flo
 
 template <typename T>
 hipError_t bwd_impl(const Plan &p, const T *Q, const T *K, const T *V, const T *O, const float *den, const T *dO,
-                    T *dQ, T *dK, T *dV, char *ws, hipStream_t st)
+                    T *dQ, T *dK, T *dV, float *dbeta, char *ws, hipStream_t st)
 {
     const Args a = make_args(p, ws);
     const size_t lds = smem_floats(p.R, p.d, p.P, a.TT) * sizeof(float);
+    float *dbeta_part = reinterpret_cast<float *>(ws + p.off_dbeta);
     float *stateS = reinterpret_cast<float *>(ws + p.off_stateA);
     float *stateD = reinterpret_cast<float *>(ws + p.off_stateB);
     float *pQ = reinterpret_cast<float *>(ws + p.off_part);
@@ -555,15 +580,38 @@ hipError_t bwd_impl(const Plan &p, const T *Q, const T *K, const T *V, const T *
     hipLaunchKernelGGL(simple_scan, sgrid, dim3(256), 0, st, stateS, p.nseg, elems, p.causal ? 0 : 2);
     hipLaunchKernelGGL((simple_totals<T, 1>), grid, dim3(kThreads), lds, st, a, Q, dO, O, den, stateD);
     hipLaunchKernelGGL(simple_scan, sgrid, dim3(256), 0, st, stateD, p.nseg, elems, p.causal ? 1 : 2);
-    hipLaunchKernelGGL((simple_bwd_query<T>), grid, dim3(kThreads), lds, st, a, Q, K, V, O, den, dO, stateS, pQ);
-    hipLaunchKernelGGL((simple_bwd_keyvalue<T>), grid, dim3(kThreads), lds, st, a, Q, K, V, O, den, dO, stateD, pK, pV);
+    hipLaunchKernelGGL((simple_bwd_query<T>), grid, dim3(kThreads), lds, st, a, Q, K, V, O, den, dO, stateS, pQ,
+                       dbeta_part);
+    hipLaunchKernelGGL((simple_bwd_keyvalue<T>), grid, dim3(kThreads), lds, st, a, Q, K, V, O, den, dO, stateD, pK, pV,
+                       dbeta_part);
     const size_t total = static_cast<size_t>(p.BH) * p.N * p.d;
     hipLaunchKernelGGL((simple_bwd_combine<T>), dim3(blocks_for(total, 256)), dim3(256), 0, st, a, p.BH, pQ, pK, pV,
                        dQ, dK, dV);
+    if (dbeta) RACE_TRY(reduce_dbeta(p, dbeta_part, dbeta, st));
     return hipGetLastError();
 }
 
+// One thread per (batch, head): both sides' partial sums in index order.
+__global__ void dbeta_reduce_kernel(const float *part, int BH, int parts, float *dbeta)
+{
+    const int bh = blockIdx.x * blockDim.x + threadIdx.x;
+    if (bh >= BH) return;
+    float s = 0.f;
+    for (int side = 0; side < 2; ++side) {
+        const float *src = part + (static_cast<size_t>(side) * BH + bh) * parts;
+        for (int i = 0; i < parts; ++i) s += src[i];
+    }
+    dbeta[bh] = s;
+}
+
 }  // namespace
+
+hipError_t reduce_dbeta(const Plan &p, const float *part, float *dbeta, hipStream_t st)
+{
+    hipLaunchKernelGGL(dbeta_reduce_kernel, dim3(blocks_for(static_cast<size_t>(p.BH), 64)), dim3(64), 0, st, part,
+                       p.BH, p.dbeta_parts, dbeta);
+    return hipGetLastError();
+}
 
 bool simple_supported(int R, int d, int P) { return pick_tile(R, d, P) > 0; }
 
@@ -576,13 +624,13 @@ hipError_t simple_fwd(const Plan &p, const void *Q, const void *K, const void *V
 }
 
 hipError_t simple_bwd(const Plan &p, const void *Q, const void *K, const void *V, const void *O, const float *den,
-                      const void *dO, void *dQ, void *dK, void *dV, char *ws, hipStream_t st)
+                      const void *dO, void *dQ, void *dK, void *dV, float *dbeta, char *ws, hipStream_t st)
 {
     if (p.dtype == RACE_F32)
         return bwd_impl<float>(p, (const float *)Q, (const float *)K, (const float *)V, (const float *)O, den,
-                               (const float *)dO, (float *)dQ, (float *)dK, (float *)dV, ws, st);
+                               (const float *)dO, (float *)dQ, (float *)dK, (float *)dV, dbeta, ws, st);
     return bwd_impl<bf16_t>(p, (const bf16_t *)Q, (const bf16_t *)K, (const bf16_t *)V, (const bf16_t *)O, den,
-                            (const bf16_t *)dO, (bf16_t *)dQ, (bf16_t *)dK, (bf16_t *)dV, ws, st);
+                            (const bf16_t *)dO, (bf16_t *)dQ, (bf16_t *)dK, (bf16_t *)dV, dbeta, ws, st);
 }
 
 hipError_t simple_hash(const Plan &p, const void *X, uint8_t *codes, float *phi, char *ws, hipStream_t st)

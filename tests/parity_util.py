@@ -67,3 +67,37 @@ def check_case(w: synth.Workload, tensors=None, tol=None, verbose=True, floors=N
     for n, e in errs.items():
         assert e < tol, "%s: %s rel err %.3e >= %.1e" % (w.name, n, e, tol)
     return g, r, errs
+
+
+def check_dbeta(w: synth.Workload, tol=None, verbose=True, scale="max"):
+    """Cotangent of the temperature per (batch, head) from race_attn_bwd_beta against the oracle; also checks
+    that asking for it leaves dQ, dK, dV bit-identical.  scale "max": the error measure of the tensors,
+    max |gpu - oracle| / max |oracle|, for inputs whose terms do not cancel much.  scale "l1": relative to
+    the sum of the absolute values of the terms (per batch and head), for inputs where tens of thousands of
+    terms of both signs cancel to a small sum and every term carries the path's rounding."""
+    tol = tol or TOL[w.dtype]
+    g = run_gpu(w)
+    d = desc_of(w)
+    dQ, dK, dV, dbeta = ra.race_attn_bwd_beta(d, g["Q"], g["K"], g["V"], g["O"], g["den"], g["dO"], g["seeds"])
+    torch.cuda.synchronize()
+    for a, b in ((dQ, g["dQ"]), (dK, g["dK"]), (dV, g["dV"])):
+        assert torch.equal(a, b)
+    W = oracle_w(w, g["seeds"])
+    Q, K, V, dO = (to_f64(g[n]) for n in ("Q", "K", "V", "dO"))
+    O, den = oracle_stream.forward(Q, K, V, W, w.sharpening, w.L, w.P, w.causal)
+    *_, ref = oracle_stream.backward(Q, K, V, W, w.sharpening, w.L, w.P, w.causal, O, den, dO, with_beta=True)
+    got = to_f64(dbeta)
+    assert np.isfinite(got).all()
+    if scale == "l1":
+        l1 = np.array([[ro.beta_cotangent_l1(Q[b, h], K[b, h], V[b, h], W[h], w.sharpening, w.L, w.P, w.causal, dO[b, h])
+                        for h in range(w.H)] for b in range(w.B)])
+        assert (l1 >= np.abs(ref) * (1 - 1e-9)).all()
+        err = float((np.abs(got - ref) / l1).max())
+        note = "relative to the terms' l1 norm %.3e (|dbeta| %.3e)" % (l1.max(), np.abs(ref).max())
+    else:
+        err = float(np.abs(got - ref).max() / np.abs(ref).max())
+        note = "relative to max |dbeta| %.3e" % np.abs(ref).max()
+    if verbose:
+        print("%s: dbeta err %.2e %s" % (w.name, err, note), flush=True)
+    assert err < tol, "%s: dbeta err %.3e >= %.1e (%s)" % (w.name, err, tol, note)
+    return dbeta, ref

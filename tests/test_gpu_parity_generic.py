@@ -136,3 +136,14 @@ def test_calibration_copy_copies():
     ra.race_attn_calibration_copy(dst, src)
     torch.cuda.synchronize()
     assert torch.equal(dst, src)
+
+
+def test_beta_cotangent_fp32():
+    from parity_util import check_dbeta
+    check_dbeta(synth.C1)
+    check_dbeta(Workload("g-beta-causal", 2, 2, 300, 32, 3, 3, 2.0, True, "f32", chunk=64))
+
+
+def test_beta_cotangent_bf16_generic_shape():
+    from parity_util import check_dbeta
+    check_dbeta(Workload("g-beta-bf16", 1, 2, 500, 64, 4, 3, 4.0, True, "bf16", chunk=128))

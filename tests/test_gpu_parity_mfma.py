@@ -175,3 +175,17 @@ def test_config4_causal_4m_tokens_sampled():
 
 def test_config5_causal_12m_tokens_sampled():
     _long_context(synth.C5, 16384)
+
+
+def test_beta_cotangent_headline_shape():
+    from parity_util import check_dbeta
+    check_dbeta(Workload("m-beta-1", 1, 2, 1000, 128, 8, 6, 8.0, True, "bf16", normalize_qk=True, chunk=256))
+    # raw N(0,1) rows saturate three quarters of the bits: ~75 000 terms of both signs cancel to a sum of order one
+    check_dbeta(Workload("m-beta-2", 1, 2, 777, 128, 8, 6, 8.0, True, "bf16", chunk=256), scale="l1")
+    check_dbeta(Workload("m-beta-3", 1, 2, 1000, 128, 8, 6, 8.0, False, "bf16", normalize_qk=True, chunk=256))
+
+
+def test_beta_cotangent_encoder_shape():
+    from parity_util import check_dbeta
+    check_dbeta(Workload("m-beta-c3", 2, 2, 900, 64, 16, 4, 4.0, True, "bf16", chunk=128))
+    check_dbeta(Workload("m-beta-c3n", 2, 2, 900, 64, 16, 4, 4.0, False, "bf16"))

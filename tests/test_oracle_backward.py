@@ -143,3 +143,14 @@ def test_beta_gradient_c_oracle_matches_numpy_and_sums_over_heads():
         h = 1e-6
         fd = (loss(beta + h) - loss(beta - h)) / (2 * h)
         assert abs(db.sum() - fd) <= 1e-6 * max(1.0, abs(fd))
+
+
+def test_beta_l1_scale_bounds_the_cotangent():
+    rng = np.random.default_rng(2)
+    N, d, L, P, beta = 12, 5, 2, 3, 3.0
+    Q, K, V, dO = (rng.standard_normal((N, d)) for _ in range(4))
+    W = rng.standard_normal((L * P, d))
+    for causal in (False, True):
+        *_, db = ro.backward_quadratic(Q, K, V, W, beta, L, P, causal, dO, with_beta=True)
+        l1 = ro.beta_cotangent_l1(Q, K, V, W, beta, L, P, causal, dO)
+        assert l1 >= abs(db) and l1 > 0
