@@ -68,6 +68,7 @@ def main() -> int:
     ap.add_argument("--tokens", type=int, default=0, help="override N of the workload")
     ap.add_argument("--cpu-sample-tokens", type=int, default=196608)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-attainable", action="store_true", help="skip the copy / MFMA-loop calibration launches")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="before the warm-up, run one plain copy kernel of this many MiB (scale for byte counters)")
     args = ap.parse_args()
@@ -113,6 +114,24 @@ def main() -> int:
         ra.race_attn_calibration_copy(dst, src)
         torch.cuda.synchronize()
         del src, dst
+
+    attainable = None
+    if not args.no_attainable:
+        # what this machine reaches on a plain copy and on a dense MFMA loop, next to the published peaks
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 256)
+        dst = torch.empty_like(src)
+        sink = torch.empty(8192 * 256, dtype=torch.float32, device=dev)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        ra.race_attn_calibration_copy(dst, src)
+        ra.race_attn_calibration_mfma(8192, 64, sink)
+        ev[0].record(); ra.race_attn_calibration_copy(dst, src); ev[1].record()
+        ev[2].record(); flop = ra.race_attn_calibration_mfma(8192, 2048, sink); ev[3].record()
+        torch.cuda.synchronize()
+        attainable = {"hbm_copy_GBps": 2 * src.numel() / (1e-3 * ev[0].elapsed_time(ev[1])) / 1e9,
+                      "mfma_bf16_TFLOPs": flop / (1e-3 * ev[2].elapsed_time(ev[3])) / 1e12,
+                      "note": "1 GiB copy kernel (read + write counted) and a register-operand "
+                              "v_mfma_f32_32x32x16_bf16 loop, one launch each, HIP events"}
+        del src, dst, sink
 
     for _ in range(args.warmup):
         step()
@@ -188,6 +207,7 @@ def main() -> int:
         "step_roofline": {"algorithmic_tflop": step_flops / 1e12, "algorithmic_gb": step_bytes / 1e9,
                           "frac_of_mfma_roof": step_flops / (elapsed / args.steps) / PEAK_BF16_FLOPS,
                           "frac_of_hbm_roof": step_bytes / (elapsed / args.steps) / PEAK_HBM_BYTES},
+        "attainable": attainable,
         "kernels": kernels,
     }
     print(json.dumps(out))

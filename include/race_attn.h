@@ -155,6 +155,14 @@ int race_attn_profile_read(int max_entries, const char **names, float *total_ms,
  * traffic against which hardware byte counters of the other kernels are scaled.  bytes == 0 is a no-op. */
 race_status_t race_attn_calibration_copy(void *dst, const void *src, size_t bytes, race_stream_t stream);
 
+/* Benchmark aid (no passage of the paper; callers: benchmarks that report the attainable matrix rate next to the
+ * published peak).  Launches calibration_mfma_kernel: `workgroups` workgroups of 256 threads, each wavefront
+ * issuing `iters` rounds of four independent v_mfma_f32_32x32x16_bf16 on register operands, i.e.
+ * workgroups * 4 * iters * 4 * 32768 floating-point operations in all; every lane then stores one float to
+ * sink (DEVICE, workgroups * 256 floats) so that the work cannot be optimised away.  workgroups and iters must
+ * be in 1 .. 2^20. */
+race_status_t race_attn_calibration_mfma(int workgroups, int iters, float *sink, race_stream_t stream);
+
 #ifdef __cplusplus
 }
 #endif

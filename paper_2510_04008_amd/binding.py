@@ -67,6 +67,8 @@ def lib() -> ctypes.CDLL:
         L.race_attn_profile_read.restype = ctypes.c_int
         L.race_attn_calibration_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.race_attn_calibration_copy.restype = ctypes.c_int
+        L.race_attn_calibration_mfma.argtypes = [ctypes.c_int, ctypes.c_int, fp, vp]
+        L.race_attn_calibration_mfma.restype = ctypes.c_int
         L.race_status_string.argtypes = [ctypes.c_int]
         L.race_status_string.restype = ctypes.c_char_p
         L.race_attn_last_error.argtypes = []
@@ -234,6 +236,16 @@ def race_attn_calibration_copy(dst, src, stream=None) -> None:
     st = lib().race_attn_calibration_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream(stream))
     if st != RACE_OK:
         raise RaceAttnError(st, "race_attn_calibration_copy")
+
+
+def race_attn_calibration_mfma(workgroups: int, iters: int, sink, stream=None) -> int:
+    """Dense bf16 MFMA loop; sink: float32 device tensor of workgroups * 256 elements.  Returns the flop count."""
+    if sink.numel() < workgroups * 256:
+        raise ValueError("sink too small")
+    st = lib().race_attn_calibration_mfma(int(workgroups), int(iters), sink.data_ptr(), _stream(stream))
+    if st != RACE_OK:
+        raise RaceAttnError(st, "race_attn_calibration_mfma")
+    return workgroups * 4 * iters * 4 * 32768
 
 
 def race_attn_profile_enable(on: bool) -> None:

@@ -509,6 +509,25 @@ __global__ __launch_bounds__(kThreads) void hash_tap_kernel(KArgs a, const bf16r
     }
 }
 
+// Attainable matrix rate: four independent accumulators per wavefront, operands from registers only.
+__global__ __launch_bounds__(256) void calibration_mfma_kernel(int iters, float *sink)
+{
+    const uint32_t seed = 0x3F803F80u ^ (threadIdx.x & 1);          // bf16 values near one
+    u32x4 a = {seed, seed, seed, seed}, b = {seed, seed, seed, seed};
+    f32x16 c0 = {0}, c1 = {0}, c2 = {0}, c3 = {0};
+    for (int i = 0; i < iters; ++i) {
+        c0 = mma(a, b, c0);
+        c1 = mma(a, b, c1);
+        c2 = mma(a, b, c2);
+        c3 = mma(a, b, c3);
+    }
+    const f32x16 c = (c0 + c1) + (c2 + c3);
+    float s = 0.f;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s += c[v];
+    sink[static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x] = s;
+}
+
 }  // namespace mfma
 
 // ================================================================================ host side
@@ -692,6 +711,12 @@ void pack_t(const Plan &p, const float *W, void *image)
 #define RACE_SHAPES(X) RACE_MFMA_SHAPES(X)
 
 }  // namespace
+
+hipError_t calibration_mfma(int workgroups, int iters, float *sink, hipStream_t st)
+{
+    hipLaunchKernelGGL(mfma::calibration_mfma_kernel, dim3(workgroups), dim3(256), 0, st, iters, sink);
+    return hipGetLastError();
+}
 
 bool mfma_supported(int d, int L, int P)
 {

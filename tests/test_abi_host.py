@@ -134,3 +134,12 @@ def test_calibration_copy_rejects_bad_arguments_on_the_host():
     assert lib.race_attn_calibration_copy(base + 1024, base, 24, None) == ra.RACE_ERR_INVALID_ARG   # not a multiple of 16
     assert lib.race_attn_calibration_copy(base + 1028, base, 64, None) == ra.RACE_ERR_INVALID_ARG   # misaligned
     assert lib.race_attn_calibration_copy(base + 32, base, 64, None) == ra.RACE_ERR_INVALID_ARG     # overlapping
+
+
+def test_calibration_mfma_rejects_bad_arguments_on_the_host():
+    lib = ra.lib()
+    fake = ctypes.c_void_p(4096)
+    assert lib.race_attn_calibration_mfma(1, 1, None, None) == ra.RACE_ERR_INVALID_ARG
+    assert lib.race_attn_calibration_mfma(0, 1, fake, None) == ra.RACE_ERR_INVALID_ARG
+    assert lib.race_attn_calibration_mfma(1, 0, fake, None) == ra.RACE_ERR_INVALID_ARG
+    assert lib.race_attn_calibration_mfma((1 << 20) + 1, 1, fake, None) == ra.RACE_ERR_INVALID_ARG

@@ -147,3 +147,11 @@ def test_beta_cotangent_fp32():
 def test_beta_cotangent_bf16_generic_shape():
     from parity_util import check_dbeta
     check_dbeta(Workload("g-beta-bf16", 1, 2, 500, 64, 4, 3, 4.0, True, "bf16", chunk=128))
+
+
+def test_calibration_mfma_runs_and_fills_the_sink():
+    sink = torch.full((16 * 256,), float("nan"), dtype=torch.float32, device="cuda:0")
+    flop = ra.race_attn_calibration_mfma(16, 8, sink)
+    torch.cuda.synchronize()
+    assert flop == 16 * 4 * 8 * 4 * 32768
+    assert torch.isfinite(sink).all() and (sink > 0).all()
