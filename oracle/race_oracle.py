@@ -202,6 +202,20 @@ def bucket_statistics(K, V, W, beta, L, P):
     return A, B
 
 
+def decode_step(state, q, k, v, W, beta, L, P):
+    """One iteration of Algorithm 2's loop with the bucket statistics as the carried state (the layer's
+    counterpart of a key/value cache: its size does not grow with the context).  state: (L, R, d+1)
+    float64, [B | A] per bucket row, updated in place with (k, v); returns the output row of q and Den."""
+    d = q.shape[0]
+    pk = soft_hash(k[None, :], W, beta, L, P)[0]          # (L, R)
+    pq = soft_hash(q[None, :], W, beta, L, P)[0]
+    state[:, :, :d] += pk[:, :, None] * v[None, None, :]
+    state[:, :, d] += pk
+    num = np.einsum("lr,lrc->c", pq, state[:, :, :d]) / L
+    den = float((pq * state[:, :, d]).sum()) / L
+    return num / den, den
+
+
 # ----------------------------------------------------------------------------------
 # Backward (the paper trains through the soft assignment by automatic differentiation
 # and prints no gradient; both forms below are derived from Algorithms 1/2 and are

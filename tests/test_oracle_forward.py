@@ -246,3 +246,24 @@ def test_collision_probability_matches_the_powered_angular_kernel():
     pq2 = ro.soft_hash(q[None], W, 200.0, tables, P)[0]
     pk2 = ro.soft_hash(k[None], W, 200.0, tables, P)[0]
     assert abs((pq2 * pk2).sum(axis=1).mean() - p_hat) < 0.01
+
+
+def test_decode_steps_reproduce_the_causal_forward_and_the_state_is_the_bucket_statistics():
+    rng = np.random.default_rng(21)
+    N, d, L, P, beta = 17, 6, 3, 3, 2.0
+    Q, K, V = (rng.standard_normal((N, d)) for _ in range(3))
+    W = rng.standard_normal((L * P, d))
+    O, den = ro.forward_streaming(Q, K, V, W, beta, L, P)
+    state = np.zeros((L, 1 << P, d + 1))
+    for t in range(N):
+        o, dn = ro.decode_step(state, Q[t], K[t], V[t], W, beta, L, P)
+        assert np.allclose(o, O[t], rtol=1e-12, atol=1e-14) and abs(dn - den[t]) <= 1e-12 * den[t]
+    A, B = ro.bucket_statistics(K, V, W, beta, L, P)
+    assert np.allclose(state[:, :, :d], B, rtol=1e-12, atol=1e-14) and np.allclose(state[:, :, d], A, rtol=1e-12)
+    # resuming from the statistics of a prefix gives the same continuation
+    n0 = 9
+    A0, B0 = ro.bucket_statistics(K[:n0], V[:n0], W, beta, L, P)
+    st = np.concatenate([B0, A0[:, :, None]], axis=2)
+    for t in range(n0, N):
+        o, _ = ro.decode_step(st, Q[t], K[t], V[t], W, beta, L, P)
+        assert np.allclose(o, O[t], rtol=1e-12, atol=1e-14)
