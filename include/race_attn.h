@@ -130,6 +130,31 @@ race_status_t race_attn_debug_buckets(const race_attn_desc_t *desc, const void *
                                       const uint64_t *proj_seeds, float *A, float *Bsum,
                                       void *workspace, size_t workspace_bytes, race_stream_t stream);
 
+/* ---- Incremental decoding: the bucket statistics as the carried state (Algorithm 2, one loop iteration per
+ * call).  The state plays the part of a key/value cache whose size does not grow with the context:
+ * state = DEVICE float (B, H, L, R, d+1), row-major; per bucket row the d sums of phi_K * V (B of Algorithm 1,
+ * step 5) followed by the mass (A).  The caller owns it; a zero-filled state is the empty context. */
+
+/* Bytes of one state for this descriptor (B, H, d, L, P are used); 0 for an invalid descriptor. */
+size_t race_attn_state_bytes(const race_attn_desc_t *desc);
+
+/* Prefill: state <- statistics of the desc->N keys and values in K, V (DEVICE (B, H, N, d) of desc->dtype);
+ * N == 0 zero-fills it.  Workspace as for race_attn_fwd (race_attn_workspace_bytes; none needed for N == 0). */
+race_status_t race_attn_state_init(const race_attn_desc_t *desc, const void *K, const void *V,
+                                   const uint64_t *proj_seeds, float *state,
+                                   void *workspace, size_t workspace_bytes, race_stream_t stream);
+
+/* Bytes of device workspace race_attn_step needs (independent of desc->N). */
+size_t race_attn_step_workspace_bytes(const race_attn_desc_t *desc);
+
+/* One new token per (batch, head): q, k, v are DEVICE (B, H, d) rows of desc->dtype.  The state is updated in
+ * place with (k, v) first, then q reads it (the loop body of Algorithm 2): o (DEVICE (B, H, d), desc->dtype) and
+ * den (DEVICE float (B, H), with the 1/L of Algorithm 1 step 7).  desc->N, desc->causal and desc->chunk are
+ * ignored.  Arithmetic is fp32 on the values as given.  Cost O(L R d) per token and head. */
+race_status_t race_attn_step(const race_attn_desc_t *desc, const void *q, const void *k, const void *v,
+                             const uint64_t *proj_seeds, float *state, void *o, float *den,
+                             void *workspace, size_t workspace_bytes, race_stream_t stream);
+
 /* Static, never-null description of a status code. */
 const char *race_status_string(race_status_t status);
 

@@ -67,6 +67,14 @@ def lib() -> ctypes.CDLL:
         L.race_attn_profile_read.restype = ctypes.c_int
         L.race_attn_calibration_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.race_attn_calibration_copy.restype = ctypes.c_int
+        L.race_attn_state_bytes.argtypes = [dp]
+        L.race_attn_state_bytes.restype = ctypes.c_size_t
+        L.race_attn_state_init.argtypes = [dp, vp, vp, u64p, fp, vp, ctypes.c_size_t, vp]
+        L.race_attn_state_init.restype = ctypes.c_int
+        L.race_attn_step_workspace_bytes.argtypes = [dp]
+        L.race_attn_step_workspace_bytes.restype = ctypes.c_size_t
+        L.race_attn_step.argtypes = [dp, vp, vp, vp, u64p, fp, vp, fp, vp, ctypes.c_size_t, vp]
+        L.race_attn_step.restype = ctypes.c_int
         L.race_attn_calibration_mfma.argtypes = [ctypes.c_int, ctypes.c_int, fp, vp]
         L.race_attn_calibration_mfma.restype = ctypes.c_int
         L.race_status_string.argtypes = [ctypes.c_int]
@@ -226,6 +234,59 @@ def race_attn_debug_buckets(desc: RaceAttnDesc, K, V, proj_seeds: Sequence[int],
     if st != RACE_OK:
         raise RaceAttnError(st, "race_attn_debug_buckets")
     return A, Bsum
+
+
+def race_attn_state_bytes(desc: RaceAttnDesc) -> int:
+    return int(lib().race_attn_state_bytes(ctypes.byref(desc)))
+
+
+def race_attn_state_init(desc: RaceAttnDesc, K, V, proj_seeds: Sequence[int], state=None, workspace=None, stream=None):
+    """State (B, H, L, R, d+1) float32 holding the bucket statistics of the desc.N keys/values (zeros for N == 0)."""
+    torch = _torch()
+    shape = (desc.B, desc.H, desc.L, 1 << desc.P, desc.d + 1)
+    device = K.device if K is not None else (state.device if state is not None else "cuda")
+    state = torch.empty(shape, dtype=torch.float32, device=device) if state is None else state
+    _check_tensor(state, desc, "state", shape, torch.float32)
+    if desc.N > 0:
+        _check_tensor(K, desc, "K")
+        _check_tensor(V, desc, "V")
+        workspace, nbytes = _workspace(desc, workspace, K.device)
+        wptr = workspace.data_ptr()
+    else:
+        nbytes, wptr = 0, None
+    st = lib().race_attn_state_init(ctypes.byref(desc), K.data_ptr() if desc.N > 0 else None,
+                                    V.data_ptr() if desc.N > 0 else None, _seeds(proj_seeds), state.data_ptr(),
+                                    wptr, nbytes, _stream(stream))
+    if st != RACE_OK:
+        raise RaceAttnError(st, "race_attn_state_init")
+    return state
+
+
+def race_attn_step_workspace_bytes(desc: RaceAttnDesc) -> int:
+    return int(lib().race_attn_step_workspace_bytes(ctypes.byref(desc)))
+
+
+def race_attn_step(desc: RaceAttnDesc, q, k, v, proj_seeds: Sequence[int], state, o=None, den=None, workspace=None,
+                   stream=None):
+    """One decoding step: q, k, v (B, H, d); state updated in place; returns o (B, H, d) and den (B, H)."""
+    torch = _torch()
+    row = (desc.B, desc.H, desc.d)
+    for t, n in ((q, "q"), (k, "k"), (v, "v")):
+        _check_tensor(t, desc, n, row)
+    _check_tensor(state, desc, "state", (desc.B, desc.H, desc.L, 1 << desc.P, desc.d + 1), torch.float32)
+    o = torch.empty_like(v) if o is None else o
+    den = torch.empty((desc.B, desc.H), dtype=torch.float32, device=v.device) if den is None else den
+    _check_tensor(o, desc, "o", row)
+    _check_tensor(den, desc, "den", (desc.B, desc.H), torch.float32)
+    need = race_attn_step_workspace_bytes(desc)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=v.device)
+    st = lib().race_attn_step(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(), _seeds(proj_seeds),
+                              state.data_ptr(), o.data_ptr(), den.data_ptr(), workspace.data_ptr(),
+                              workspace.numel() * workspace.element_size(), _stream(stream))
+    if st != RACE_OK:
+        raise RaceAttnError(st, "race_attn_step")
+    return o, den
 
 
 def race_attn_calibration_copy(dst, src, stream=None) -> None:

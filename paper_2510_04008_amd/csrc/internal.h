@@ -71,8 +71,14 @@ hipError_t simple_bwd(const Plan &p, const void *Q, const void *K, const void *V
                       const float *den, const void *dO, void *dQ, void *dK, void *dV, float *dbeta, char *ws,
                       hipStream_t st);
 hipError_t simple_hash(const Plan &p, const void *X, uint8_t *codes, float *phi, char *ws, hipStream_t st);
-hipError_t simple_buckets(const Plan &p, const void *K, const void *V, float *A, float *Bsum, char *ws,
-                          hipStream_t st);
+// A[(bh*L*R + row) * a_stride] and Bsum[(bh*L*R + row) * b_stride + column]: separate tensors (1, d) or one
+// interleaved (B, H, L, R, d+1) state (A = state + d, Bsum = state, both strides d+1)
+hipError_t simple_buckets(const Plan &p, const void *K, const void *V, float *A, float *Bsum, int a_stride,
+                          int b_stride, char *ws, hipStream_t st);
+// One decoding step (simple_kernels.hip): W fp32 (H, L*P, d) and partial (BH, L, d+1) in the workspace.
+hipError_t decode_step(const Plan &p, const float *W, const void *q, const void *k, const void *v, float *state,
+                       float *partial, void *o, float *den, hipStream_t st);
+hipError_t zero_floats(float *dst, size_t n, hipStream_t st);
 
 // ---- MFMA family (mfma_kernels.hip, mfma_grad.hip).  Compiled shapes: X(d, P, L)
 #define RACE_MFMA_SHAPES(X) X(128, 6, 8) X(64, 4, 16)
@@ -87,7 +93,7 @@ hipError_t mfma_bwd(const Plan &p, const void *Q, const void *K, const void *V, 
                     hipStream_t st);
 int mfma_dbeta_parts(const Plan &p);           // workgroups per (side, batch*head) of the gradient kernels
 hipError_t mfma_hash(const Plan &p, const void *X, uint8_t *codes, float *phi, char *ws, hipStream_t st);
-hipError_t mfma_buckets(const Plan &p, const void *K, const void *V, float *A, float *Bsum, char *ws,
-                        hipStream_t st);
+hipError_t mfma_buckets(const Plan &p, const void *K, const void *V, float *A, float *Bsum, int a_stride,
+                        int b_stride, char *ws, hipStream_t st);
 
 }  // namespace race

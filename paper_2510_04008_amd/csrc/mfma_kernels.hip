@@ -447,9 +447,9 @@ __global__ void scan_kernel(float *state, int nseg, int elems, int mode)
     }
 }
 
-// Debug tap: totals over all segments, split into A (BH, L, R) and B (BH, L, R, D)
+// Totals over all segments, written as A[(bh*LR + r) * a_stride] and Bsum[(bh*LR + r) * b_stride + c]
 template <class C>
-__global__ void bucket_tap_kernel(const float *state, int nseg, int BH, float *A, float *Bsum)
+__global__ void bucket_tap_kernel(const float *state, int nseg, int BH, float *A, float *Bsum, int a_stride, int b_stride)
 {
     const size_t i = blockIdx.x * static_cast<size_t>(blockDim.x) + threadIdx.x;
     if (i >= static_cast<size_t>(BH) * C::STATE) return;
@@ -457,8 +457,8 @@ __global__ void bucket_tap_kernel(const float *state, int nseg, int BH, float *A
     const int e = static_cast<int>(i - bh * C::STATE);
     float run = 0.f;
     for (int s = 0; s < nseg; ++s) run += state[(bh * nseg + s) * C::STATE + e];
-    if (e < C::LR * C::D) Bsum[bh * C::LR * C::D + e] = run;
-    else A[bh * C::LR + (e - C::LR * C::D)] = run;
+    if (e < C::LR * C::D) Bsum[(bh * C::LR + e / C::D) * b_stride + e % C::D] = run;
+    else A[(bh * C::LR + (e - C::LR * C::D)) * a_stride] = run;
 }
 
 // Debug tap: hard codes and phi from the production step itself.
@@ -651,13 +651,14 @@ hipError_t bwd_t(const Plan &p, const void *Q, const void *K, const void *V, con
 }
 
 template <class C>
-hipError_t buckets_t(const Plan &p, const void *K, const void *V, float *A, float *Bsum, char *ws, hipStream_t st)
+hipError_t buckets_t(const Plan &p, const void *K, const void *V, float *A, float *Bsum, int a_stride, int b_stride,
+                     char *ws, hipStream_t st)
 {
     KArgs a = make_kargs<C>(p, ws);
     RACE_TRY((launch_totals<C, 0>(p, a, K, V, nullptr, nullptr, st)));
     const size_t total = static_cast<size_t>(p.BH) * C::STATE;
     hipLaunchKernelGGL(bucket_tap_kernel<C>, dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0, st, a.state,
-                       p.nseg, p.BH, A, Bsum);
+                       p.nseg, p.BH, A, Bsum, a_stride, b_stride);
     return hipGetLastError();
 }
 
@@ -783,9 +784,10 @@ hipError_t mfma_hash(const Plan &p, const void *X_, uint8_t *codes, float *phi, 
     return hipErrorNotSupported;
 }
 
-hipError_t mfma_buckets(const Plan &p, const void *K, const void *V, float *A, float *Bsum, char *ws, hipStream_t st)
+hipError_t mfma_buckets(const Plan &p, const void *K, const void *V, float *A, float *Bsum, int a_stride, int b_stride,
+                        char *ws, hipStream_t st)
 {
-#define X(DD, PP_, LL) if (p.d == DD && p.P == PP_ && p.L == LL) return buckets_t<Cfg<DD, PP_, LL>>(p, K, V, A, Bsum, ws, st);
+#define X(DD, PP_, LL) if (p.d == DD && p.P == PP_ && p.L == LL) return buckets_t<Cfg<DD, PP_, LL>>(p, K, V, A, Bsum, a_stride, b_stride, ws, st);
     RACE_SHAPES(X)
 #undef X
     return hipErrorNotSupported;

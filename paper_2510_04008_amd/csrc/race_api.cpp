@@ -377,9 +377,90 @@ race_status_t race_attn_debug_buckets(const race_attn_desc_t *desc, const void *
     char *ws = static_cast<char *>(workspace);
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     if ((s = upload_projection(p, proj_seeds, ws, st)) != RACE_OK) return s;
-    hipError_t e = (p.family == kFamilyMfma) ? mfma_buckets(p, K, V, A, Bsum, ws, st)
-                                             : simple_buckets(p, K, V, A, Bsum, ws, st);
+    hipError_t e = (p.family == kFamilyMfma) ? mfma_buckets(p, K, V, A, Bsum, 1, p.d, ws, st)
+                                             : simple_buckets(p, K, V, A, Bsum, 1, p.d, ws, st);
     return e == hipSuccess ? RACE_OK : hip_failed(e, "race_attn_debug_buckets launch");
+}
+
+size_t race_attn_state_bytes(const race_attn_desc_t *desc)
+{
+    Plan p;
+    race_attn_desc_t one;
+    if (!desc) return 0;
+    one = *desc;
+    one.N = 1;                             // the state does not depend on the context length
+    if (one.chunk < 0) one.chunk = 0;
+    if (make_plan(&one, &p) != RACE_OK) return 0;
+    return static_cast<size_t>(p.BH) * p.LR * (p.d + 1) * sizeof(float);
+}
+
+race_status_t race_attn_state_init(const race_attn_desc_t *desc, const void *K, const void *V,
+                                   const uint64_t *proj_seeds, float *state, void *workspace,
+                                   size_t workspace_bytes, race_stream_t stream)
+{
+    Plan p;
+    race_status_t s = make_plan(desc, &p);
+    if (s != RACE_OK) return s;
+    if (!state) return RACE_ERR_INVALID_ARG;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (p.N == 0) {                        // empty context
+        hipError_t e = zero_floats(state, static_cast<size_t>(p.BH) * p.LR * (p.d + 1), st);
+        return e == hipSuccess ? RACE_OK : hip_failed(e, "race_attn_state_init launch");
+    }
+    if (!K || !V || !proj_seeds) return RACE_ERR_INVALID_ARG;
+    if (static_cast<const void *>(state) == K || static_cast<const void *>(state) == V) return RACE_ERR_INVALID_ARG;
+    if ((s = check_workspace(p, workspace, workspace_bytes, p.total)) != RACE_OK) return s;
+    char *ws = static_cast<char *>(workspace);
+    if ((s = upload_projection(p, proj_seeds, ws, st)) != RACE_OK) return s;
+    // interleaved layout: per bucket row d sums, then the mass
+    hipError_t e = (p.family == kFamilyMfma) ? mfma_buckets(p, K, V, state + p.d, state, p.d + 1, p.d + 1, ws, st)
+                                             : simple_buckets(p, K, V, state + p.d, state, p.d + 1, p.d + 1, ws, st);
+    return e == hipSuccess ? RACE_OK : hip_failed(e, "race_attn_state_init launch");
+}
+
+namespace {
+// A decoding step runs on the generic kernels' fp32 image of W whatever family serves the long passes.
+race_status_t make_step_plan(const race_attn_desc_t *desc, Plan *pl)
+{
+    if (!desc) return RACE_ERR_INVALID_ARG;
+    race_attn_desc_t one = *desc;
+    one.N = 1;
+    one.causal = 1;
+    one.chunk = 0;
+    race_status_t s = make_plan(&one, pl);
+    if (s != RACE_OK) return s;
+    pl->family = kFamilySimple;
+    pl->off_W = 0;
+    pl->bytes_W = align256(static_cast<size_t>(pl->H) * pl->LP * pl->d * sizeof(float));
+    pl->off_part = pl->bytes_W;
+    pl->bytes_part = align256(static_cast<size_t>(pl->BH) * pl->L * (pl->d + 1) * sizeof(float));
+    pl->total = pl->off_part + pl->bytes_part;
+    return RACE_OK;
+}
+}  // namespace
+
+size_t race_attn_step_workspace_bytes(const race_attn_desc_t *desc)
+{
+    Plan p;
+    return make_step_plan(desc, &p) == RACE_OK ? p.total : 0;
+}
+
+race_status_t race_attn_step(const race_attn_desc_t *desc, const void *q, const void *k, const void *v,
+                             const uint64_t *proj_seeds, float *state, void *o, float *den, void *workspace,
+                             size_t workspace_bytes, race_stream_t stream)
+{
+    Plan p;
+    race_status_t s = make_step_plan(desc, &p);
+    if (s != RACE_OK) return s;
+    if (!q || !k || !v || !proj_seeds || !state || !o || !den) return RACE_ERR_INVALID_ARG;
+    if (any_equal({state, o, den}, {q, k, v, state, o, den})) return RACE_ERR_INVALID_ARG;
+    if ((s = check_workspace(p, workspace, workspace_bytes, p.total)) != RACE_OK) return s;
+    char *ws = static_cast<char *>(workspace);
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if ((s = upload_projection(p, proj_seeds, ws, st)) != RACE_OK) return s;
+    hipError_t e = decode_step(p, reinterpret_cast<const float *>(ws + p.off_W), q, k, v, state,
+                               reinterpret_cast<float *>(ws + p.off_part), o, den, st);
+    return e == hipSuccess ? RACE_OK : hip_failed(e, "race_attn_step launch");
 }
 
 const char *race_status_string(race_status_t status)

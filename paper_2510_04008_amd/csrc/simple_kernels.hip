@@ -486,8 +486,8 @@ __global__ void simple_hash_tap(Args a, int BH, const T *X, uint8_t *codes, floa
     }
 }
 
-// Debug tap: sum the per-segment totals and split them into A and B.
-__global__ void simple_bucket_tap(Args a, int BH, const float *state, float *A, float *Bsum)
+// Sum of the per-segment totals, written as A[row * a_stride] and Bsum[row * b_stride + c], row = (bh, l, r).
+__global__ void simple_bucket_tap(Args a, int BH, const float *state, float *A, float *Bsum, int a_stride, int b_stride)
 {
     const size_t i = blockIdx.x * static_cast<size_t>(blockDim.x) + threadIdx.x;
     const int d1 = a.d + 1;
@@ -498,8 +498,82 @@ __global__ void simple_bucket_tap(Args a, int BH, const float *state, float *A, 
     float run = 0.f;
     for (int s = 0; s < a.nseg; ++s) run += state[(bl * a.nseg + s) * a.R * d1 + e];
     const int r = static_cast<int>(e / d1), c = static_cast<int>(e - static_cast<size_t>(r) * d1);
-    if (c == a.d) A[bl * a.R + r] = run;
-    else Bsum[(bl * a.R + r) * a.d + c] = run;
+    if (c == a.d) A[(bl * a.R + r) * a_stride] = run;
+    else Bsum[(bl * a.R + r) * b_stride + c] = run;
+}
+
+// ------------------------------------------------------------------ incremental decoding
+// One workgroup per (table, batch*head): hash the new key and query (Algorithm 1, steps 2-4), add the key/value
+// to the table's statistics, read them with the query (Algorithm 2's loop body).  partial: (BH, L, d+1).
+template <typename T>
+__global__ __launch_bounds__(256) void decode_step_kernel(int H, int L, int P, int d, float beta, const float *W,
+                                                          const T *q, const T *k, const T *v, float *state,
+                                                          float *partial)
+{
+    extern __shared__ float lds[];
+    const int R = 1 << P, d1 = d + 1;
+    float *xq = lds, *xk = xq + d, *vv = xk + d, *pp = vv + d1, *phiq = pp + 4 * P, *phik = phiq + R;
+    const int l = blockIdx.x, bh = blockIdx.y, h = bh % H, tid = threadIdx.x;
+    const float *Wl = W + (static_cast<size_t>(h) * L + l) * P * d;
+    for (int c = tid; c < d; c += blockDim.x) {
+        xq[c] = load_elem(q, static_cast<size_t>(bh) * d + c);
+        xk[c] = load_elem(k, static_cast<size_t>(bh) * d + c);
+        vv[c] = load_elem(v, static_cast<size_t>(bh) * d + c);
+    }
+    if (tid == 0) vv[d] = 1.0f;
+    __syncthreads();
+    if (tid < 2 * P) {                        // per-bit masses of the query (t < P) and of the key
+        const int t = tid % P;
+        const float *x = tid < P ? xq : xk;
+        float z = 0.f;
+        for (int c = 0; c < d; ++c) z = fmaf(Wl[t * d + c], x[c], z);
+        const float u = tanhf(z);
+        const float e = expf(-2.0f * beta * fabsf(u));
+        const float big = 1.0f / (1.0f + e), small = e / (1.0f + e);
+        pp[2 * tid] = (u >= 0.f) ? big : small;          // mass on the +1 side
+        pp[2 * tid + 1] = (u >= 0.f) ? small : big;
+    }
+    __syncthreads();
+    for (int r = tid; r < 2 * R; r += blockDim.x) {
+        const int side = r / R, c = r % R;
+        float f = 1.f;
+        for (int t = 0; t < P; ++t) f *= pp[2 * (side * P + t) + (((c >> t) & 1) ? 0 : 1)];
+        (side ? phik : phiq)[c] = f;
+    }
+    __syncthreads();
+    float *S = state + (static_cast<size_t>(bh) * L + l) * R * d1;
+    for (int c = tid; c < d1; c += blockDim.x) {
+        const float y = vv[c];
+        float acc = 0.f;
+        for (int r = 0; r < R; ++r) {
+            const float s = fmaf(phik[r], y, S[r * d1 + c]);
+            S[r * d1 + c] = s;
+            acc = fmaf(phiq[r], s, acc);
+        }
+        partial[(static_cast<size_t>(bh) * L + l) * d1 + c] = acc;
+    }
+}
+
+// Sum over tables in table order, normalise (Algorithm 1, steps 7-8).
+template <typename T>
+__global__ void decode_combine_kernel(int L, int d, const float *partial, T *o, float *den)
+{
+    const int bh = blockIdx.x, d1 = d + 1;
+    const float *src = partial + static_cast<size_t>(bh) * L * d1;
+    float dn = 0.f;
+    for (int l = 0; l < L; ++l) dn += src[l * d1 + d];
+    for (int c = threadIdx.x; c < d; c += blockDim.x) {
+        float num = 0.f;
+        for (int l = 0; l < L; ++l) num += src[l * d1 + c];
+        store_elem(o, static_cast<size_t>(bh) * d + c, num / dn);
+    }
+    if (threadIdx.x == 0) den[bh] = dn / static_cast<float>(L);
+}
+
+__global__ void zero_kernel(float *dst, size_t n)
+{
+    const size_t stride = static_cast<size_t>(gridDim.x) * blockDim.x;
+    for (size_t i = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = 0.f;
 }
 
 // ------------------------------------------------------------------ host side
@@ -646,8 +720,33 @@ hipError_t simple_hash(const Plan &p, const void *X, uint8_t *codes, float *phi,
     return hipGetLastError();
 }
 
-hipError_t simple_buckets(const Plan &p, const void *K, const void *V, float *A, float *Bsum, char *ws,
-                          hipStream_t st)
+hipError_t zero_floats(float *dst, size_t n, hipStream_t st)
+{
+    const size_t want = (n + 255) / 256;
+    hipLaunchKernelGGL(zero_kernel, dim3(static_cast<unsigned>(want < 4096 ? (want ? want : 1) : 4096)), dim3(256), 0, st,
+                       dst, n);
+    return hipGetLastError();
+}
+
+hipError_t decode_step(const Plan &p, const float *W, const void *q, const void *k, const void *v, float *state,
+                       float *partial, void *o, float *den, hipStream_t st)
+{
+    const size_t lds = (static_cast<size_t>(3) * p.d + 1 + 4 * p.P + 2 * p.R) * sizeof(float);
+    const dim3 grid(p.L, p.BH);
+    if (p.dtype == RACE_F32) {
+        hipLaunchKernelGGL((decode_step_kernel<float>), grid, dim3(256), lds, st, p.H, p.L, p.P, p.d, p.beta, W,
+                           (const float *)q, (const float *)k, (const float *)v, state, partial);
+        hipLaunchKernelGGL((decode_combine_kernel<float>), dim3(p.BH), dim3(128), 0, st, p.L, p.d, partial, (float *)o, den);
+    } else {
+        hipLaunchKernelGGL((decode_step_kernel<bf16_t>), grid, dim3(256), lds, st, p.H, p.L, p.P, p.d, p.beta, W,
+                           (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v, state, partial);
+        hipLaunchKernelGGL((decode_combine_kernel<bf16_t>), dim3(p.BH), dim3(128), 0, st, p.L, p.d, partial, (bf16_t *)o, den);
+    }
+    return hipGetLastError();
+}
+
+hipError_t simple_buckets(const Plan &p, const void *K, const void *V, float *A, float *Bsum, int a_stride,
+                          int b_stride, char *ws, hipStream_t st)
 {
     const Args a = make_args(p, ws);
     const size_t lds = smem_floats(p.R, p.d, p.P, a.TT) * sizeof(float);
@@ -663,7 +762,8 @@ hipError_t simple_buckets(const Plan &p, const void *K, const void *V, float *A,
                            (const bf16_t *)V, (const bf16_t *)nullptr, (const float *)nullptr, state);
     }
     const size_t total = static_cast<size_t>(p.BH) * p.L * p.R * (p.d + 1);
-    hipLaunchKernelGGL(simple_bucket_tap, dim3(blocks_for(total, 256)), dim3(256), 0, st, a, p.BH, state, A, Bsum);
+    hipLaunchKernelGGL(simple_bucket_tap, dim3(blocks_for(total, 256)), dim3(256), 0, st, a, p.BH, state, A, Bsum,
+                       a_stride, b_stride);
     return hipGetLastError();
 }
 

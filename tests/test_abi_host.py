@@ -143,3 +143,24 @@ def test_calibration_mfma_rejects_bad_arguments_on_the_host():
     assert lib.race_attn_calibration_mfma(0, 1, fake, None) == ra.RACE_ERR_INVALID_ARG
     assert lib.race_attn_calibration_mfma(1, 0, fake, None) == ra.RACE_ERR_INVALID_ARG
     assert lib.race_attn_calibration_mfma((1 << 20) + 1, 1, fake, None) == ra.RACE_ERR_INVALID_ARG
+
+
+def test_decode_entry_points_check_arguments_on_the_host():
+    lib = ra.lib()
+    d = _desc()
+    assert ra.race_attn_state_bytes(d) == d.B * d.H * d.L * (1 << d.P) * (d.d + 1) * 4
+    assert ra.race_attn_state_bytes(_desc(N=0)) == ra.race_attn_state_bytes(_desc(N=10 ** 6))     # no N in it
+    assert ra.race_attn_state_bytes(_desc(P=0)) == 0 and ra.race_attn_step_workspace_bytes(_desc(L=0)) == 0
+    need = ra.race_attn_step_workspace_bytes(d)
+    assert need > 0 and need % 256 == 0
+    p = [ctypes.c_void_p(256 * (i + 1)) for i in range(8)]
+    seeds = (ctypes.c_uint64 * 2)(1, 2)
+    ok_ws = ctypes.c_void_p(1 << 20)
+    E = ra.RACE_ERR_INVALID_ARG
+    assert lib.race_attn_step(ctypes.byref(d), None, p[1], p[2], seeds, p[3], p[4], p[5], ok_ws, need, None) == E
+    assert lib.race_attn_step(ctypes.byref(d), p[0], p[1], p[2], seeds, None, p[4], p[5], ok_ws, need, None) == E
+    assert lib.race_attn_step(ctypes.byref(d), p[0], p[1], p[2], seeds, p[3], p[2], p[5], ok_ws, need, None) == E
+    assert lib.race_attn_step(ctypes.byref(d), p[0], p[1], p[2], seeds, p[3], p[4], p[5], ok_ws, need - 1, None) == ra.RACE_ERR_WORKSPACE
+    assert lib.race_attn_state_init(ctypes.byref(d), p[0], p[1], seeds, None, ok_ws, 1 << 30, None) == E
+    assert lib.race_attn_state_init(ctypes.byref(d), p[0], p[1], seeds, p[0], ok_ws, 1 << 30, None) == E
+    assert lib.race_attn_state_init(ctypes.byref(d), p[0], p[1], seeds, p[2], ok_ws, 0, None) == ra.RACE_ERR_WORKSPACE
