@@ -44,7 +44,11 @@ C2 = Workload("C2-causal-bf16-64K", 1, 4, 65536, 128, 8, 6, 8.0, True, "bf16", n
 C3 = Workload("C3-noncausal-bf16-16K", 8, 8, 16384, 64, 16, 4, 4.0, False, "bf16")
 C4 = Workload("C4-causal-bf16-4M", 1, 4, 4194304, 128, 8, 6, 8.0, True, "bf16")
 C5 = Workload("C5-causal-bf16-12M", 1, 4, 12582912, 128, 8, 6, 8.0, True, "bf16")
-WORKLOADS = {w.name.split("-")[0]: w for w in (C1, C2, C3, C4, C5)}
+# the paper's own scaling grid (Section 4, single-layer stress test): (P, L) in {(2,2), (3,3), (4,4)}, B=1, H=4, d=128
+G22 = Workload("G22-causal-bf16-1M", 1, 4, 1048576, 128, 2, 2, 8.0, True, "bf16")
+G33 = Workload("G33-causal-bf16-1M", 1, 4, 1048576, 128, 3, 3, 8.0, True, "bf16")
+G44 = Workload("G44-causal-bf16-1M", 1, 4, 1048576, 128, 4, 4, 8.0, True, "bf16")
+WORKLOADS = {w.name.split("-")[0]: w for w in (C1, C2, C3, C4, C5, G22, G33, G44)}
 
 SEED_QKV, SEED_W, SEED_DO = 0, 1, 2
 _SLICE = 1 << 18      # tokens generated at a time (bounds the fp32 temporary)
