@@ -15,6 +15,10 @@ constexpr int kFamilyMfma = 2;     // bf16 MFMA kernels, register-resident bucke
 // Everything the launchers need, derived once from a validated descriptor.
 struct Plan {
     int B, H, BH, d, L, P, R, LP, LR;
+    // MFMA family: the compiled shape that serves the problem (Lc >= L tables, Pc >= P hyperplanes; the padding
+    // tables are empty and the padding hyperplanes put all mass on one side); equal to L, P, LR otherwise
+    int Lc, Pc, LRc;
+    int pad;            // 1: the padded instantiation of the compiled shape serves the problem
     int64_t N;
     float beta;
     int causal;
@@ -81,8 +85,10 @@ hipError_t decode_step(const Plan &p, const float *W, const void *q, const void 
 hipError_t zero_floats(float *dst, size_t n, hipStream_t st);
 
 // ---- MFMA family (mfma_kernels.hip, mfma_grad.hip).  Compiled shapes: X(d, P, L)
-#define RACE_MFMA_SHAPES(X) X(128, 6, 8) X(64, 4, 16)
-bool mfma_supported(int d, int L, int P);
+// X(d, P, L, PAD): PAD = 0 serves exactly that shape, PAD = 1 also everything smaller in L and P
+#define RACE_MFMA_SHAPES(X) X(128, 6, 8, 0) X(64, 4, 16, 0) X(64, 4, 16, 1) X(128, 4, 16, 1)
+// The exact shape if compiled, else the padded instantiation with the fewest bucket rows that covers (d, L, P).
+bool mfma_pick(int d, int L, int P, int *Lc, int *Pc, int *pad);
 size_t mfma_scratch_bytes(const Plan &p);      // backward-pass scratch beyond the two state areas
 size_t mfma_projection_bytes(const Plan &p);
 void mfma_pack_projection(const Plan &p, const float *W, void *image);   // host

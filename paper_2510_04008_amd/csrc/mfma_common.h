@@ -43,9 +43,11 @@ constexpr int kThreads = 64 * kWaves;
 constexpr int kRowGroups = 4;  // stream kernels: wavefront w owns bucket-row group w % 4 and column group w / 4
 constexpr int kTile = 32;      // tokens per tile
 
-template <int D_, int P_, int L_>
+// PAD_: the instantiation also serves problems with fewer tables and hyperplanes than its shape (see Soft).
+template <int D_, int P_, int L_, bool PAD_ = false>
 struct Cfg {
     static constexpr int D = D_, P = P_, L = L_;
+    static constexpr bool PAD = PAD_;
     static constexpr int R = 1 << P, LR = L * R;
     static constexpr int PP = P > 4 ? 8 : 4;            // hyperplanes per table, padded
     static constexpr int TPG = 32 / PP;                 // tables per 32-row projection group
@@ -87,11 +89,22 @@ __device__ __forceinline__ int opaque(int x)
     return x;
 }
 
+// The soft assignment's run-time parameters.  A compiled shape <d, P, L> also serves smaller problems
+// (tables L_real <= L, hyperplanes P_real <= P): tables beyond L_real get zero assignments, and a hyperplane
+// beyond P_real is a bit whose mass sits entirely on its +1 side, so that the 2^P_real real corners are the
+// corners of the compiled hypercube with all padding bits set.
+struct Soft {
+    float beta;
+    int L, P;
+};
+
 // kernel arguments common to the family
 struct KArgs {
     int H, nseg, causal;
     int64_t N, seg_len;
     float beta;
+    int L_real, P_real;    // the problem's tables and hyperplanes (<= the compiled shape's)
+    __host__ __device__ Soft soft() const { return Soft{beta, L_real, P_real}; }
     const bf16raw *Wp;     // (H, LPP, D) bf16, rows in projection-group order
     const bf16raw *WpT;    // (H, D, LPP) bf16
     float *state;          // (BH, nseg, STATE) fp32
@@ -238,13 +251,13 @@ __device__ __forceinline__ void fetch_cotangent(const bf16raw *dO, const bf16raw
 }
 
 template <class C, int ROWS, int STRIDE = C::XS, bool IL = false>
-__device__ __forceinline__ void store_cotangent(const CotChunks<C, ROWS> &r, bf16raw *dst, float *ge)
+__device__ __forceinline__ void store_cotangent(const CotChunks<C, ROWS> &r, bf16raw *dst, float *ge, int L_real)
 {
     const int tid = opaque(static_cast<int>(threadIdx.x));
 #pragma unroll
     for (int k = 0; k < RowChunks<C, ROWS>::N; ++k) {
         const int c = tid + k * kThreads, row = c / C::CPR, ch = c % C::CPR;
-        const float inv = r.den[k] > 0.f ? 1.0f / (r.den[k] * static_cast<float>(C::L)) : 0.f;
+        const float inv = r.den[k] > 0.f ? 1.0f / (r.den[k] * static_cast<float>(L_real)) : 0.f;
         const uint32_t gw[4] = {r.g.v[k].x, r.g.v[k].y, r.g.v[k].z, r.g.v[k].w};
         const uint32_t ow[4] = {r.o.v[k].x, r.o.v[k].y, r.o.v[k].z, r.o.v[k].w};
         uint32_t out[4];
@@ -290,13 +303,21 @@ __device__ __forceinline__ constexpr int zslot(int j, int t)
 }
 
 // Per-bit masses of one table: p[t] = sigmoid(2 beta tanh z_t) (mass on the +1 side), q[t] = 1 - p[t],
-// computed without cancellation; sech2[t] = 1 - tanh^2 z_t; u[t] = tanh z_t.
+// computed without cancellation; sech2[t] = 1 - tanh^2 z_t; u[t] = tanh z_t.  Padding bits (t >= sf.P): all the
+// mass on the +1 side, no dependence on the input.
 template <class C>
-__device__ __forceinline__ void bit_masses(const f32x16 &z, int j, float beta, float *p, float *q, float *sech2,
+__device__ __forceinline__ void bit_masses(const f32x16 &z, int j, const Soft &sf, float *p, float *q, float *sech2,
                                            float *u = nullptr)
 {
+    const float beta = sf.beta;
 #pragma unroll
     for (int t = 0; t < C::P; ++t) {
+        if (C::PAD && t >= sf.P) {
+            p[t] = 1.f; q[t] = 0.f;
+            if (sech2) sech2[t] = 0.f;
+            if (u) u[t] = 0.f;
+            continue;
+        }
         const float zt = z[zslot<C>(j, t)];
         const float e2 = __expf(-2.0f * fabsf(zt));
         const float inv = __builtin_amdgcn_rcpf(1.0f + e2);
@@ -345,7 +366,7 @@ __device__ __forceinline__ void kron_factors(const float *p, const float *q, flo
 // If mass != null (bucket masses in the same pair-interleaved order), returns sum_r phi[r] * mass[r] over
 // what was written (the read-out of the bucket masses A by this token, i.e. its share of the normaliser).
 template <class C, int STRIDE = C::PS>
-__device__ __forceinline__ float write_assignments(const f32x16 &z, int g, int row, int h, float beta, bool valid,
+__device__ __forceinline__ float write_assignments(const f32x16 &z, int g, int row, int h, const Soft &sf, bool valid,
                                                    bf16raw *ph, int j0 = 0, int jstep = 1, int a0 = 0,
                                                    int a1 = 1 << C::PHI, const float *mass = nullptr)
 {
@@ -356,11 +377,20 @@ __device__ __forceinline__ float write_assignments(const f32x16 &z, int g, int r
         const int table = g * C::TPG + h * C::TPL + j;
         if (table >= C::L) break;
         if (j < j0 || (j - j0) % jstep != 0) continue;
-        float p[C::P], q[C::P], lo[1 << C::PLO], hi[1 << C::PHI];
-        bit_masses<C>(z, j, beta, p, q, nullptr);
-        kron_factors<C>(p, q, lo, hi);
         const int tbase = opaque(table * C::R);                   // one base register, constants folded into offsets
         bf16raw *prow = ph + opaque(row * STRIDE);
+        if (C::PAD && table >= sf.L) {                            // a padding table: zero assignments
+#pragma unroll
+            for (int a = 0; a < (1 << C::PHI); a += 2) {
+                if (a < a0 || a >= a1) continue;
+                *reinterpret_cast<u32x4 *>(prow + tbase + a * 8) = u32x4{0u, 0u, 0u, 0u};
+                *reinterpret_cast<u32x4 *>(prow + tbase + a * 8 + 8) = u32x4{0u, 0u, 0u, 0u};
+            }
+            continue;
+        }
+        float p[C::P], q[C::P], lo[1 << C::PLO], hi[1 << C::PHI];
+        bit_masses<C>(z, j, sf, p, q, nullptr);
+        kron_factors<C>(p, q, lo, hi);
 #pragma unroll
         for (int a = 0; a < (1 << C::PHI); a += 2) {
             if (a < a0 || a >= a1) continue;

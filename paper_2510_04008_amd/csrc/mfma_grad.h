@@ -187,12 +187,12 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
         store_rows<C, kTile>(pre_r, xr);
         if (intra) store_rows<C, kTile>(pre_w, xw);
         if (SIDE == 0) {
-            store_cotangent<C, kTile, C::XS, true>(pre_c, yr, sr);
+            store_cotangent<C, kTile, C::XS, true>(pre_c, yr, sr, a.L_real);
             if (intra) store_rows<C, kTile, C::YS, true>(pre_v, yw);
             if (tid < kTile) sw[tid] = 1.f;
         } else {
             store_rows<C, kTile, C::XS, true>(pre_v, yr);
-            if (intra) store_cotangent<C, kTile, C::YS, true>(pre_c, yw, sw);
+            if (intra) store_cotangent<C, kTile, C::YS, true>(pre_c, yw, sw, a.L_real);
             if (tid < kTile) sr[tid] = 1.f;
         }
         GRAD_PHASE(0)
@@ -212,7 +212,7 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
             const int pg = w % G::NGW, pj = (w / G::NGW) % C::TPL, as = w / (G::NGW * C::TPL);
             constexpr int kShare = (1 << C::PHI) / G::AS;
             const f32x16 zw = project<C>(wp, xw, th * G::NGW + pg, ln, h);
-            write_assignments<C, C::PST>(zw, th * G::NGW + pg, ln, h, a.beta, ln < nvalid, phw, pj, C::TPL, as * kShare,
+            write_assignments<C, C::PST>(zw, th * G::NGW + pg, ln, h, a.soft(), ln < nvalid, phw, pj, C::TPL, as * kShare,
                                  (as + 1) * kShare);
         }
         if (w >= G::RD0 && w < G::RD0 + G::NR) {
@@ -226,7 +226,8 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
 #pragma unroll
                 for (int t = 0; t < C::PP; ++t) p[t] = q[t] = s2[t] = u[t] = 0.f;
                 float *dst = pm + ((pg * C::TPG + h * C::TPL + j) * kTile + ln) * S::PMS;
-                bit_masses<C>(zr, j, a.beta, p, q, s2, u);
+                // (a padding table has zero statistics and zero cotangents: any finite masses will do)
+                if (!C::PAD || (th * G::NGW + pg) * C::TPG + h * C::TPL + j < a.L_real) bit_masses<C>(zr, j, a.soft(), p, q, s2, u);
 #pragma unroll
                 for (int t = 0; t < C::PP; t += 4) {
                     *reinterpret_cast<float4 *>(dst + t) = float4{p[t], p[t + 1], p[t + 2], p[t + 3]};

@@ -119,7 +119,7 @@ void totals_kernel(KArgs a, const bf16raw *X, const bf16raw *Y, const bf16raw *O
         const int64_t t0 = t_begin + static_cast<int64_t>(it) * TT;
         const int nvalid = step_nv(t0);
         store_rows<C, TT>(pre_x, xs);
-        if (QG) store_cotangent<C, TT, C::YS>(pre_c, ys, ge_lds);
+        if (QG) store_cotangent<C, TT, C::YS>(pre_c, ys, ge_lds, a.L_real);
         else store_rows<C, TT, C::YS>(pre_y, ys);
         if (it + 1 < nsteps) fetch(it + 1);
         __syncthreads();
@@ -127,7 +127,7 @@ void totals_kernel(KArgs a, const bf16raw *X, const bf16raw *Y, const bf16raw *O
             // wavefront = (token half, projection group, share of the group's tables)
             const int half = w / 4, g = w % C::NG, jq = (w % 4) / C::NG;
             const f32x16 z = project<C>(wp, xs + half * 32 * C::XS, g, ln, h);
-            write_assignments<C, C::PST>(z, g, half * 32 + ln, h, a.beta, half * 32 + ln < nvalid, ph, jq, C::JSTEP);
+            write_assignments<C, C::PST>(z, g, half * 32 + ln, h, a.soft(), half * 32 + ln < nvalid, ph, jq, C::JSTEP);
         }
         __syncthreads();
 #pragma unroll
@@ -269,7 +269,7 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
         store_rows<C, kTile>(pre_r, xr);
         if (intra) {
             store_rows<C, kTile>(pre_w, xw);
-            if (MODE == kGradV) store_cotangent<C, kTile, C::YS>(pre_c, ytile, nullptr);
+            if (MODE == kGradV) store_cotangent<C, kTile, C::YS>(pre_c, ytile, nullptr, a.L_real);
             else store_rows<C, kTile, C::YS>(pre_y, ytile);
         }
         RACE_PHASE(0)
@@ -281,12 +281,12 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
             const int side = w / 4, g = w % C::NG, jq = (w % 4) / C::NG;
             if (side == 0) {
                 const f32x16 z = project<C>(wp, xr, g, ln, h);
-                const float dnl = write_assignments<C>(z, g, ln, h, a.beta, true, phr, jq, C::JSTEP, 0, 1 << C::PHI,
+                const float dnl = write_assignments<C>(z, g, ln, h, a.soft(), true, phr, jq, C::JSTEP, 0, 1 << C::PHI,
                                                        MODE == kForward ? mass : nullptr);
                 if (MODE == kForward) dnp[w * 64 + lane] = dnl;       // this lane's tables' share of the normaliser
             } else if (intra) {
                 const f32x16 z = project<C>(wp, xw, g, ln, h);
-                write_assignments<C>(z, g, ln, h, a.beta, ln < nvalid, phw, jq, C::JSTEP);
+                write_assignments<C>(z, g, ln, h, a.soft(), ln < nvalid, phw, jq, C::JSTEP);
             }
         }
         RACE_PHASE(2)
@@ -406,7 +406,7 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
                 for (int c = 0; c < NP; ++c)
                     *reinterpret_cast<u32x2 *>(dst + 64 * c) =
                         u32x2{pack2(acc[c][0] * scale, acc[c][1] * scale), pack2(acc[c][2] * scale, acc[c][3] * scale)};
-                if (MODE == kForward && (tid & 15) == 0) den_out[t0 + tok] = e * (1.0f / C::L);
+                if (MODE == kForward && (tid & 15) == 0) den_out[t0 + tok] = e / static_cast<float>(a.L_real);
             }
         }
         RACE_PHASE(9)
@@ -447,18 +447,27 @@ __global__ void scan_kernel(float *state, int nseg, int elems, int mode)
     }
 }
 
-// Totals over all segments, written as A[(bh*LR + r) * a_stride] and Bsum[(bh*LR + r) * b_stride + c]
+// Totals over all segments of the problem's own buckets, written as A[row * a_stride] and
+// Bsum[row * b_stride + c] with row = (bh * L_real + l) * R_real + r.  Real corner r of a real table sits at
+// the compiled corner with all padding bits set.
 template <class C>
-__global__ void bucket_tap_kernel(const float *state, int nseg, int BH, float *A, float *Bsum, int a_stride, int b_stride)
+__global__ void bucket_tap_kernel(const float *state, int nseg, int BH, int L_real, int P_real, float *A, float *Bsum,
+                                  int a_stride, int b_stride)
 {
+    const int R_real = 1 << P_real, pad = (C::R - 1) & ~(R_real - 1);
+    const size_t per = static_cast<size_t>(L_real) * R_real * (C::D + 1);
     const size_t i = blockIdx.x * static_cast<size_t>(blockDim.x) + threadIdx.x;
-    if (i >= static_cast<size_t>(BH) * C::STATE) return;
-    const size_t bh = i / C::STATE;
-    const int e = static_cast<int>(i - bh * C::STATE);
+    if (i >= static_cast<size_t>(BH) * per) return;
+    const size_t bh = i / per;
+    const int e = static_cast<int>(i - bh * per);
+    const int row = e / (C::D + 1), c = e % (C::D + 1), l = row / R_real, r = row % R_real;
+    const int src = l * C::R + (r | pad);
+    const int off = c < C::D ? src * C::D + c : C::LR * C::D + src;
     float run = 0.f;
-    for (int s = 0; s < nseg; ++s) run += state[(bh * nseg + s) * C::STATE + e];
-    if (e < C::LR * C::D) Bsum[(bh * C::LR + e / C::D) * b_stride + e % C::D] = run;
-    else A[(bh * C::LR + (e - C::LR * C::D)) * a_stride] = run;
+    for (int s = 0; s < nseg; ++s) run += state[(bh * nseg + s) * C::STATE + off];
+    const size_t dst = (bh * L_real + l) * R_real + r;
+    if (c < C::D) Bsum[dst * b_stride + c] = run;
+    else A[dst * a_stride] = run;
 }
 
 // Debug tap: hard codes and phi from the production step itself.
@@ -487,24 +496,27 @@ __global__ __launch_bounds__(kThreads) void hash_tap_kernel(KArgs a, const bf16r
     if (w < C::NG) {
         const int g = w;
         const f32x16 z = project<C>(wp, x, g, ln, h);
-        write_assignments<C>(z, g, ln, h, a.beta, true, ph);
+        write_assignments<C>(z, g, ln, h, a.soft(), true, ph);
         if (ln < nvalid) {
 #pragma unroll
             for (int j = 0; j < C::TPL; ++j) {
                 const int table = g * C::TPG + h * C::TPL + j;
-                if (table >= C::L) break;
+                if (table >= C::L || table >= a.L_real) break;
                 unsigned code = 0;
 #pragma unroll
-                for (int t = 0; t < C::P; ++t) code |= (z[zslot<C>(j, t)] >= 0.f ? 1u : 0u) << t;
-                codes[(static_cast<size_t>(bh) * a.N + t0 + ln) * C::L + table] = static_cast<uint8_t>(code);
+                for (int t = 0; t < C::P; ++t) code |= (t < a.P_real && z[zslot<C>(j, t)] >= 0.f ? 1u : 0u) << t;
+                codes[(static_cast<size_t>(bh) * a.N + t0 + ln) * a.L_real + table] = static_cast<uint8_t>(code);
             }
         }
     }
     __syncthreads();
     if (phi) {
-        for (int i = tid; i < nvalid * C::LR; i += kThreads) {
-            const int row = i / C::LR, r = i % C::LR;
-            phi[(static_cast<size_t>(bh) * a.N + t0 + row) * C::LR + r] = __uint_as_float(static_cast<uint32_t>(ph[row * C::PS + il(r)]) << 16);
+        // the problem's own corners: real corner r of a real table is the compiled corner with all padding bits set
+        const int R_real = 1 << a.P_real, LR_real = a.L_real * R_real, pad = (C::R - 1) & ~(R_real - 1);
+        for (int i = tid; i < nvalid * LR_real; i += kThreads) {
+            const int row = i / LR_real, lr = i % LR_real, src = (lr / R_real) * C::R + ((lr % R_real) | pad);
+            phi[(static_cast<size_t>(bh) * a.N + t0 + row) * LR_real + lr] =
+                __uint_as_float(static_cast<uint32_t>(ph[row * C::PS + il(src)]) << 16);
         }
     }
 }
@@ -553,6 +565,7 @@ KArgs make_kargs(const Plan &p, char *ws)
 {
     KArgs a;
     a.H = p.H; a.nseg = p.nseg; a.causal = p.causal; a.N = p.N; a.seg_len = p.seg_len; a.beta = p.beta;
+    a.L_real = p.L; a.P_real = p.P;
     a.Wp = reinterpret_cast<const bf16raw *>(ws + p.off_W);
     a.WpT = a.Wp + static_cast<size_t>(p.H) * C::LPP * C::D;
     a.state = reinterpret_cast<float *>(ws + p.off_stateA);
@@ -656,9 +669,9 @@ hipError_t buckets_t(const Plan &p, const void *K, const void *V, float *A, floa
 {
     KArgs a = make_kargs<C>(p, ws);
     RACE_TRY((launch_totals<C, 0>(p, a, K, V, nullptr, nullptr, st)));
-    const size_t total = static_cast<size_t>(p.BH) * C::STATE;
+    const size_t total = static_cast<size_t>(p.BH) * p.LR * (C::D + 1);
     hipLaunchKernelGGL(bucket_tap_kernel<C>, dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0, st, a.state,
-                       p.nseg, p.BH, A, Bsum, a_stride, b_stride);
+                       p.nseg, p.BH, p.L, p.P, A, Bsum, a_stride, b_stride);
     return hipGetLastError();
 }
 
@@ -699,7 +712,7 @@ void pack_t(const Plan &p, const float *W, void *image)
             const int table = g * C::TPG + tl;
             for (int c = 0; c < C::D; ++c) {
                 float v = 0.f;
-                if (table < C::L && t < C::P) v = W[(static_cast<size_t>(hd) * p.LP + table * C::P + t) * C::D + c];
+                if (table < p.L && t < p.P) v = W[(static_cast<size_t>(hd) * p.LP + table * p.P + t) * C::D + c];
                 const uint16_t bits = host_bf16(v);
                 wp[(static_cast<size_t>(hd) * C::LPP + row) * C::D + c] = bits;
                 wpt[(static_cast<size_t>(hd) * C::D + c) * C::LPP + row] = bits;
@@ -719,18 +732,30 @@ hipError_t calibration_mfma(int workgroups, int iters, float *sink, hipStream_t 
     return hipGetLastError();
 }
 
-bool mfma_supported(int d, int L, int P)
+bool mfma_pick(int d, int L, int P, int *Lc, int *Pc, int *pad)
 {
-#define X(DD, PP_, LL) if (d == DD && P == PP_ && L == LL) return true;
+    int best = 0;
+#define X(DD, PP_, LL, PD)                                                                              \
+    if (PD == 0 && d == DD && P == PP_ && L == LL) {                                                    \
+        *Lc = LL; *Pc = PP_; *pad = 0;                                                                  \
+        return true;                                                                                    \
+    }
     RACE_SHAPES(X)
 #undef X
-    return false;
+#define X(DD, PP_, LL, PD)                                                                              \
+    if (PD == 1 && d == DD && P <= PP_ && L <= LL && (best == 0 || LL * (1 << PP_) < best)) {           \
+        best = LL * (1 << PP_);                                                                         \
+        *Lc = LL; *Pc = PP_; *pad = 1;                                                                  \
+    }
+    RACE_SHAPES(X)
+#undef X
+    return best != 0;
 }
 
 size_t mfma_scratch_bytes(const Plan &p)
 {
-#define X(DD, PP_, LL) if (p.d == DD && p.P == PP_ && p.L == LL) \
-        return GradCfg<Cfg<DD, PP_, LL>>::TSPLIT == 1 ? 0 : static_cast<size_t>(p.BH) * static_cast<size_t>(p.N) * Cfg<DD, PP_, LL>::LPP * 2;
+#define X(DD, PP_, LL, PD) if (p.d == DD && p.Pc == PP_ && p.Lc == LL && p.pad == PD) \
+        return GradCfg<Cfg<DD, PP_, LL, PD != 0>>::TSPLIT == 1 ? 0 : static_cast<size_t>(p.BH) * static_cast<size_t>(p.N) * Cfg<DD, PP_, LL, PD != 0>::LPP * 2;
     RACE_SHAPES(X)
 #undef X
     return 0;
@@ -738,7 +763,7 @@ size_t mfma_scratch_bytes(const Plan &p)
 
 size_t mfma_projection_bytes(const Plan &p)
 {
-#define X(DD, PP_, LL) if (p.d == DD && p.P == PP_ && p.L == LL) return static_cast<size_t>(p.H) * Cfg<DD, PP_, LL>::LPP * DD * 2 * 2;
+#define X(DD, PP_, LL, PD) if (p.d == DD && p.Pc == PP_ && p.Lc == LL && p.pad == PD) return static_cast<size_t>(p.H) * Cfg<DD, PP_, LL, PD != 0>::LPP * DD * 2 * 2;
     RACE_SHAPES(X)
 #undef X
     return 0;
@@ -746,14 +771,14 @@ size_t mfma_projection_bytes(const Plan &p)
 
 void mfma_pack_projection(const Plan &p, const float *W, void *image)
 {
-#define X(DD, PP_, LL) if (p.d == DD && p.P == PP_ && p.L == LL) return pack_t<Cfg<DD, PP_, LL>>(p, W, image);
+#define X(DD, PP_, LL, PD) if (p.d == DD && p.Pc == PP_ && p.Lc == LL && p.pad == PD) return pack_t<Cfg<DD, PP_, LL, PD != 0>>(p, W, image);
     RACE_SHAPES(X)
 #undef X
 }
 
 hipError_t mfma_fwd(const Plan &p, const void *Q, const void *K, const void *V, void *O, float *den, char *ws, hipStream_t st)
 {
-#define X(DD, PP_, LL) if (p.d == DD && p.P == PP_ && p.L == LL) return fwd_t<Cfg<DD, PP_, LL>>(p, Q, K, V, O, den, ws, st);
+#define X(DD, PP_, LL, PD) if (p.d == DD && p.Pc == PP_ && p.Lc == LL && p.pad == PD) return fwd_t<Cfg<DD, PP_, LL, PD != 0>>(p, Q, K, V, O, den, ws, st);
     RACE_SHAPES(X)
 #undef X
     return hipErrorNotSupported;
@@ -761,7 +786,7 @@ hipError_t mfma_fwd(const Plan &p, const void *Q, const void *K, const void *V, 
 
 int mfma_dbeta_parts(const Plan &p)
 {
-#define X(DD, PP_, LL) if (p.d == DD && p.P == PP_ && p.L == LL) return p.nseg * GradCfg<Cfg<DD, PP_, LL>>::TSPLIT;
+#define X(DD, PP_, LL, PD) if (p.d == DD && p.Pc == PP_ && p.Lc == LL && p.pad == PD) return p.nseg * GradCfg<Cfg<DD, PP_, LL, PD != 0>>::TSPLIT;
     RACE_SHAPES(X)
 #undef X
     return 0;
@@ -770,7 +795,7 @@ int mfma_dbeta_parts(const Plan &p)
 hipError_t mfma_bwd(const Plan &p, const void *Q, const void *K, const void *V, const void *O, const float *den,
                     const void *dO, void *dQ, void *dK, void *dV, float *dbeta, char *ws, hipStream_t st)
 {
-#define X(DD, PP_, LL) if (p.d == DD && p.P == PP_ && p.L == LL) return bwd_t<Cfg<DD, PP_, LL>>(p, Q, K, V, O, den, dO, dQ, dK, dV, dbeta, ws, st);
+#define X(DD, PP_, LL, PD) if (p.d == DD && p.Pc == PP_ && p.Lc == LL && p.pad == PD) return bwd_t<Cfg<DD, PP_, LL, PD != 0>>(p, Q, K, V, O, den, dO, dQ, dK, dV, dbeta, ws, st);
     RACE_SHAPES(X)
 #undef X
     return hipErrorNotSupported;
@@ -778,7 +803,7 @@ hipError_t mfma_bwd(const Plan &p, const void *Q, const void *K, const void *V, 
 
 hipError_t mfma_hash(const Plan &p, const void *X_, uint8_t *codes, float *phi, char *ws, hipStream_t st)
 {
-#define X(DD, PP_, LL) if (p.d == DD && p.P == PP_ && p.L == LL) return hash_t<Cfg<DD, PP_, LL>>(p, X_, codes, phi, ws, st);
+#define X(DD, PP_, LL, PD) if (p.d == DD && p.Pc == PP_ && p.Lc == LL && p.pad == PD) return hash_t<Cfg<DD, PP_, LL, PD != 0>>(p, X_, codes, phi, ws, st);
     RACE_SHAPES(X)
 #undef X
     return hipErrorNotSupported;
@@ -787,7 +812,7 @@ hipError_t mfma_hash(const Plan &p, const void *X_, uint8_t *codes, float *phi, 
 hipError_t mfma_buckets(const Plan &p, const void *K, const void *V, float *A, float *Bsum, int a_stride, int b_stride,
                         char *ws, hipStream_t st)
 {
-#define X(DD, PP_, LL) if (p.d == DD && p.P == PP_ && p.L == LL) return buckets_t<Cfg<DD, PP_, LL>>(p, K, V, A, Bsum, a_stride, b_stride, ws, st);
+#define X(DD, PP_, LL, PD) if (p.d == DD && p.Pc == PP_ && p.Lc == LL && p.pad == PD) return buckets_t<Cfg<DD, PP_, LL, PD != 0>>(p, K, V, A, Bsum, a_stride, b_stride, ws, st);
     RACE_SHAPES(X)
 #undef X
     return hipErrorNotSupported;

@@ -186,8 +186,11 @@ race_status_t make_plan(const race_attn_desc_t *desc, Plan *pl)
 
     const char *force = std::getenv("RACE_ATTN_FORCE_GENERIC");
     const bool forced = force && force[0] == '1';
-    if (p.dtype == RACE_BF16 && !forced && mfma_supported(p.d, p.L, p.P)) p.family = kFamilyMfma;
-    else if (simple_supported(p.R, p.d, p.P)) p.family = kFamilySimple;
+    p.Lc = p.L; p.Pc = p.P; p.LRc = p.LR; p.pad = 0;
+    if (p.dtype == RACE_BF16 && !forced && mfma_pick(p.d, p.L, p.P, &p.Lc, &p.Pc, &p.pad)) {
+        p.family = kFamilyMfma;
+        p.LRc = p.Lc * (1 << p.Pc);
+    } else if (simple_supported(p.R, p.d, p.P)) p.family = kFamilySimple;
     else return RACE_ERR_UNSUPPORTED;
 
     const int64_t n = p.N > 0 ? p.N : 1;
@@ -216,7 +219,7 @@ race_status_t make_plan(const race_attn_desc_t *desc, Plan *pl)
         if ((n + len - 1) / len > 65535) return RACE_ERR_UNSUPPORTED;
         p.nseg = static_cast<int>((n + len - 1) / len);
         p.bytes_W = align256(mfma_projection_bytes(p));
-        p.bytes_state = align256(static_cast<size_t>(p.BH) * p.nseg * p.LR * (p.d + 1) * sizeof(float));
+        p.bytes_state = align256(static_cast<size_t>(p.BH) * p.nseg * p.LRc * (p.d + 1) * sizeof(float));
         p.bytes_part = align256(mfma_scratch_bytes(p));
         p.dbeta_parts = mfma_dbeta_parts(p);
     }
