@@ -66,6 +66,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="C5")
     ap.add_argument("--tokens", type=int, default=0, help="override N of the workload")
+    ap.add_argument("--chunk", type=int, default=-1, help="override the scan segment length in tokens (0 = let the library choose)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=196608)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-attainable", action="store_true", help="skip the copy / MFMA-loop calibration launches")
@@ -85,6 +86,8 @@ def main() -> int:
     w = synth.WORKLOADS[args.workload]
     if args.tokens:
         w = w.scaled(args.tokens)
+    if args.chunk >= 0:
+        w = synth.Workload(w.name, w.B, w.H, w.N, w.d, w.L, w.P, w.sharpening, w.causal, w.dtype, w.normalize_qk, args.chunk)
     dev = "cuda:0"
     torch.cuda.set_device(0)
     desc = ra.make_desc(w.B, w.H, w.N, w.d, w.L, w.P, w.sharpening, w.causal,
