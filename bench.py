@@ -4,8 +4,9 @@ roofline fraction and the fp64 oracle timed on the host cores as a baseline.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C5|C4|C2|C3] [--tokens N]
 
-A step is one race_attn_fwd plus one race_attn_bwd over one batch of synthetic, seeded inputs that
-are resident in HBM before the timed region starts.  Prints ONE JSON line on stdout.
+A step is one race_attn_fwd plus one backward pass (race_attn_bwd_saved on the forward's workspace, or
+race_attn_bwd with --bwd-recompute) over one batch of synthetic, seeded inputs that are resident in HBM
+before the timed region starts.  Prints ONE JSON line on stdout.
 """
 from __future__ import annotations
 
@@ -69,6 +70,8 @@ def main() -> int:
     ap.add_argument("--chunk", type=int, default=-1, help="override the scan segment length in tokens (0 = let the library choose)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=196608)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--bwd-recompute", action="store_true",
+                    help="time race_attn_bwd (derives the key/value statistics again) instead of race_attn_bwd_saved")
     ap.add_argument("--no-attainable", action="store_true", help="skip the copy / MFMA-loop calibration launches")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="before the warm-up, run one plain copy kernel of this many MiB (scale for byte counters)")
@@ -107,9 +110,15 @@ def main() -> int:
     sys.stderr.write("inputs resident after %.1f s; workspace %.1f MiB; kernel family %d\n"
                      % (time.perf_counter() - t_gen, ws.numel() / 2 ** 20, family))
 
+    # The backward pass of a training step follows the forward pass of the same inputs, whose workspace still
+    # holds the key/value statistics at segment starts: race_attn_bwd_saved reads them (bit-identical results);
+    # --bwd-recompute times race_attn_bwd, which derives them again from K and V.
     def step():
         ra.race_attn_fwd(desc, Q, K, V, seeds, O=O, den=den, workspace=ws)
-        ra.race_attn_bwd(desc, Q, K, V, O, den, dO, seeds, dQ=dQ, dK=dK, dV=dV, workspace=ws)
+        if args.bwd_recompute:
+            ra.race_attn_bwd(desc, Q, K, V, O, den, dO, seeds, dQ=dQ, dK=dK, dV=dV, workspace=ws)
+        else:
+            ra.race_attn_bwd_saved(desc, Q, K, V, O, den, dO, seeds, ws, dQ=dQ, dK=dK, dV=dV)
 
     if args.calibration_copy_mib:
         src = torch.randint(0, 256, (args.calibration_copy_mib << 20,), dtype=torch.uint8, device=dev)
@@ -204,7 +213,8 @@ def main() -> int:
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "N": w.N, "d": w.d, "L": w.L, "P": w.P,
-                   "sharpening": w.sharpening, "causal": w.causal, "kernel_family": family},
+                   "sharpening": w.sharpening, "causal": w.causal, "kernel_family": family,
+                   "backward": "race_attn_bwd" if args.bwd_recompute else "race_attn_bwd_saved"},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "step_roofline": {"algorithmic_tflop": step_flops / 1e12, "algorithmic_gb": step_bytes / 1e9,

@@ -105,6 +105,20 @@ race_status_t race_attn_bwd_beta(const race_attn_desc_t *desc, const void *Q, co
                                  const uint64_t *proj_seeds, void *dQ, void *dK, void *dV, float *dbeta,
                                  void *workspace, size_t workspace_bytes, race_stream_t stream);
 
+/* The backward pass for a caller that kept the forward's workspace.  race_attn_fwd leaves in the workspace what
+ * the backward pass would otherwise derive again from K and V: the packed W and the key/value bucket statistics
+ * (A, B of Algorithm 1, step 5; in the causal case Algorithm 2's running statistics at the start of every scan
+ * segment).  This entry point reads them instead of recomputing them: one pass over K and V fewer.
+ * Contract: `workspace` is the buffer that the last race_attn_fwd with the same desc, K, V and proj_seeds wrote,
+ * nothing has written to it since, and this call is stream-ordered after that forward.  A workspace that does not
+ * hold that forward's data gives wrong gradients, never an out-of-bounds access.  Arguments, outputs, dbeta
+ * (may be NULL) and error behaviour are those of race_attn_bwd_beta, whose results it reproduces bit for bit.
+ * Kernel families that keep no such statistics recompute them (the call is then race_attn_bwd_beta). */
+race_status_t race_attn_bwd_saved(const race_attn_desc_t *desc, const void *Q, const void *K, const void *V,
+                                  const void *O, const float *den, const void *dO,
+                                  const uint64_t *proj_seeds, void *dQ, void *dK, void *dV, float *dbeta,
+                                  void *workspace, size_t workspace_bytes, race_stream_t stream);
+
 /* Host-only: expands the seeds into W_host (HOST, float, (H, L*P, d)), the values the kernels
  * multiply with (Algorithm 1, step 2).  Generator: element e = row*d + col of head h is Gaussian
  * number (e mod 4) of block e/4 of Philox-4x32-10 with key = (low, high) 32 bits of the head's

@@ -54,6 +54,8 @@ def lib() -> ctypes.CDLL:
         L.race_attn_bwd.restype = ctypes.c_int
         L.race_attn_bwd_beta.argtypes = [dp, vp, vp, vp, vp, fp, vp, u64p, vp, vp, vp, fp, vp, ctypes.c_size_t, vp]
         L.race_attn_bwd_beta.restype = ctypes.c_int
+        L.race_attn_bwd_saved.argtypes = L.race_attn_bwd_beta.argtypes
+        L.race_attn_bwd_saved.restype = ctypes.c_int
         L.race_attn_expand_projection.argtypes = [dp, u64p, ctypes.POINTER(ctypes.c_float)]
         L.race_attn_expand_projection.restype = ctypes.c_int
         L.race_attn_debug_hash.argtypes = [dp, vp, u64p, u8p, fp, vp, ctypes.c_size_t, vp]
@@ -203,6 +205,34 @@ def race_attn_bwd_beta(desc: RaceAttnDesc, Q, K, V, O, den, dO, proj_seeds: Sequ
     if st != RACE_OK:
         raise RaceAttnError(st, "race_attn_bwd_beta")
     return dQ, dK, dV, dbeta
+
+
+def race_attn_bwd_saved(desc: RaceAttnDesc, Q, K, V, O, den, dO, proj_seeds: Sequence[int], workspace, dQ=None, dK=None,
+                        dV=None, dbeta=None, want_dbeta: bool = False, stream=None):
+    """The backward pass on the workspace that race_attn_fwd of the same inputs left behind (required argument).
+    Returns dQ, dK, dV and, if want_dbeta or dbeta is given, dbeta (B, H)."""
+    torch = _torch()
+    for t, n in ((Q, "Q"), (K, "K"), (V, "V"), (O, "O"), (dO, "dO")):
+        _check_tensor(t, desc, n)
+    _check_tensor(den, desc, "den", (desc.B, desc.H, desc.N), torch.float32)
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(K) if dK is None else dK
+    dV = torch.empty_like(V) if dV is None else dV
+    for t, n in ((dQ, "dQ"), (dK, "dK"), (dV, "dV")):
+        _check_tensor(t, desc, n)
+    if dbeta is None and want_dbeta:
+        dbeta = torch.empty((desc.B, desc.H), dtype=torch.float32, device=V.device)
+    if dbeta is not None:
+        _check_tensor(dbeta, desc, "dbeta", (desc.B, desc.H), torch.float32)
+    if workspace is None:
+        raise ValueError("race_attn_bwd_saved needs the workspace the forward pass wrote")
+    st = lib().race_attn_bwd_saved(ctypes.byref(desc), Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(),
+                                   den.data_ptr(), dO.data_ptr(), _seeds(proj_seeds), dQ.data_ptr(), dK.data_ptr(),
+                                   dV.data_ptr(), dbeta.data_ptr() if dbeta is not None else None,
+                                   workspace.data_ptr(), workspace.numel(), _stream(stream))
+    if st != RACE_OK:
+        raise RaceAttnError(st, "race_attn_bwd_saved")
+    return (dQ, dK, dV, dbeta) if dbeta is not None else (dQ, dK, dV)
 
 
 def race_attn_debug_hash(desc: RaceAttnDesc, X, proj_seeds: Sequence[int], want_phi: bool = False,

@@ -41,6 +41,9 @@ struct Plan {
     size_t bytes_dbeta;
     int dbeta_parts;    // partial sums per (side, batch*head): one per workgroup of the gradient kernels
     size_t total;
+    // backward only: the workspace still holds the forward's projection image and segment-start key/value
+    // statistics (set by race_attn_bwd_saved for the families that can use them)
+    int fwd_state_kept;
 };
 
 // Validates desc and fills plan.  Returns RACE_OK, RACE_ERR_INVALID_ARG or RACE_ERR_UNSUPPORTED.

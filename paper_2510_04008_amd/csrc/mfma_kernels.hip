@@ -651,9 +651,12 @@ hipError_t bwd_t(const Plan &p, const void *Q, const void *K, const void *V, con
     KArgs a = make_kargs<C>(p, ws);
     KArgs b = a;
     b.state = reinterpret_cast<float *>(ws + p.off_stateB);
-    // statistics of (phi_K, [V | 1]) at segment starts; of (phi_Q, read-out cotangents) at segment ends
-    RACE_TRY((launch_totals<C, 0>(p, a, K, V, nullptr, nullptr, st)));
-    RACE_TRY(launch_scan(p, a.state, C::STATE, p.causal ? 0 : 2, st));
+    // statistics of (phi_K, [V | 1]) at segment starts (the forward leaves exactly these behind: its scan is in
+    // place and its streaming pass only reads them); of (phi_Q, read-out cotangents) at segment ends
+    if (!p.fwd_state_kept) {
+        RACE_TRY((launch_totals<C, 0>(p, a, K, V, nullptr, nullptr, st)));
+        RACE_TRY(launch_scan(p, a.state, C::STATE, p.causal ? 0 : 2, st));
+    }
     RACE_TRY((launch_totals<C, 1>(p, b, Q, dO, O, den, st)));
     RACE_TRY(launch_scan(p, b.state, C::STATE, p.causal ? 1 : 2, st));
     RACE_TRY((launch_stream<C, kGradV>(p, b, K, Q, dO, O, den, dV, nullptr, st)));

@@ -318,10 +318,32 @@ race_status_t race_attn_bwd(const race_attn_desc_t *desc, const void *Q, const v
                               stream);
 }
 
+namespace {
+race_status_t backward(const race_attn_desc_t *desc, const void *Q, const void *K, const void *V, const void *O,
+                       const float *den, const void *dO, const uint64_t *proj_seeds, void *dQ, void *dK, void *dV,
+                       float *dbeta, void *workspace, size_t workspace_bytes, race_stream_t stream, bool saved);
+}
+
 race_status_t race_attn_bwd_beta(const race_attn_desc_t *desc, const void *Q, const void *K, const void *V,
                                  const void *O, const float *den, const void *dO, const uint64_t *proj_seeds,
                                  void *dQ, void *dK, void *dV, float *dbeta, void *workspace,
                                  size_t workspace_bytes, race_stream_t stream)
+{
+    return backward(desc, Q, K, V, O, den, dO, proj_seeds, dQ, dK, dV, dbeta, workspace, workspace_bytes, stream, false);
+}
+
+race_status_t race_attn_bwd_saved(const race_attn_desc_t *desc, const void *Q, const void *K, const void *V,
+                                  const void *O, const float *den, const void *dO, const uint64_t *proj_seeds,
+                                  void *dQ, void *dK, void *dV, float *dbeta, void *workspace,
+                                  size_t workspace_bytes, race_stream_t stream)
+{
+    return backward(desc, Q, K, V, O, den, dO, proj_seeds, dQ, dK, dV, dbeta, workspace, workspace_bytes, stream, true);
+}
+
+namespace {
+race_status_t backward(const race_attn_desc_t *desc, const void *Q, const void *K, const void *V, const void *O,
+                       const float *den, const void *dO, const uint64_t *proj_seeds, void *dQ, void *dK, void *dV,
+                       float *dbeta, void *workspace, size_t workspace_bytes, race_stream_t stream, bool saved)
 {
     Plan p;
     race_status_t s = make_plan(desc, &p);
@@ -333,11 +355,15 @@ race_status_t race_attn_bwd_beta(const race_attn_desc_t *desc, const void *Q, co
     if ((s = check_workspace(p, workspace, workspace_bytes, p.total)) != RACE_OK) return s;
     char *ws = static_cast<char *>(workspace);
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    if ((s = upload_projection(p, proj_seeds, ws, st)) != RACE_OK) return s;
+    // the MFMA family's forward leaves its projection image and segment-start statistics where the backward
+    // pass looks for them; the generic family's forward reuses that area for other things and starts over
+    p.fwd_state_kept = (saved && p.family == kFamilyMfma) ? 1 : 0;
+    if (!p.fwd_state_kept && (s = upload_projection(p, proj_seeds, ws, st)) != RACE_OK) return s;
     hipError_t e = (p.family == kFamilyMfma) ? mfma_bwd(p, Q, K, V, O, den, dO, dQ, dK, dV, dbeta, ws, st)
                                              : simple_bwd(p, Q, K, V, O, den, dO, dQ, dK, dV, dbeta, ws, st);
     return e == hipSuccess ? RACE_OK : hip_failed(e, "race_attn_bwd launch");
 }
+}  // namespace
 
 race_status_t race_attn_expand_projection(const race_attn_desc_t *desc, const uint64_t *proj_seeds, float *W_host)
 {

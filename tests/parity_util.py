@@ -35,12 +35,19 @@ def rel_err(gpu: torch.Tensor, ref: np.ndarray, floor: float = 0.0) -> float:
     return float(np.abs(g - ref).max() / (scale if scale > 0 else 1.0))
 
 
-def run_gpu(w: synth.Workload, tensors=None, seeds=None):
+def run_gpu(w: synth.Workload, tensors=None, seeds=None, saved=False):
+    """One forward and one backward pass through the C ABI.  saved: the backward pass reads the workspace the
+    forward pass left behind (race_attn_bwd_saved), the pair of calls the benchmark times."""
     Q, K, V, dO = tensors if tensors is not None else synth.make_inputs(w, "cuda")
     seeds = seeds if seeds is not None else synth.projection_seeds(w)
     d = desc_of(w)
-    O, den = ra.race_attn_fwd(d, Q, K, V, seeds)
-    dQ, dK, dV = ra.race_attn_bwd(d, Q, K, V, O, den, dO, seeds)
+    if saved:
+        ws = torch.empty(ra.race_attn_workspace_bytes(d), dtype=torch.uint8, device="cuda")
+        O, den = ra.race_attn_fwd(d, Q, K, V, seeds, workspace=ws)
+        dQ, dK, dV = ra.race_attn_bwd_saved(d, Q, K, V, O, den, dO, seeds, ws)
+    else:
+        O, den = ra.race_attn_fwd(d, Q, K, V, seeds)
+        dQ, dK, dV = ra.race_attn_bwd(d, Q, K, V, O, den, dO, seeds)
     torch.cuda.synchronize()
     return dict(Q=Q, K=K, V=V, dO=dO, O=O, den=den, dQ=dQ, dK=dK, dV=dV, seeds=seeds)
 

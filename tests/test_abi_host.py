@@ -90,6 +90,11 @@ def test_null_pointers_workspace_and_aliasing_are_checked_before_any_launch():
     assert lib.race_attn_bwd_beta(ctypes.byref(d), p[0], p[1], p[2], p[3], p[4], p[5], seeds, p[6], p[7], p[8], p[0], ok_ws, need, None) == ra.RACE_ERR_INVALID_ARG
     assert lib.race_attn_bwd_beta(ctypes.byref(d), p[0], p[1], p[2], p[3], p[4], p[5], seeds, p[6], p[7], p[8], p[9], ok_ws, 0, None) == ra.RACE_ERR_WORKSPACE
     assert lib.race_attn_bwd_beta(ctypes.byref(d), p[0], p[1], p[2], p[3], p[4], p[5], seeds, p[6], p[7], p[8], None, ok_ws, 0, None) == ra.RACE_ERR_WORKSPACE
+    # the variant that reads the forward's workspace checks its arguments the same way
+    assert lib.race_attn_bwd_saved(ctypes.byref(d), p[0], p[1], p[2], p[3], p[4], p[5], seeds, p[6], p[7], None, None, ok_ws, need, None) == ra.RACE_ERR_INVALID_ARG
+    assert lib.race_attn_bwd_saved(ctypes.byref(d), p[0], p[1], p[2], p[3], p[4], p[5], seeds, p[6], p[7], p[8], p[7], ok_ws, need, None) == ra.RACE_ERR_INVALID_ARG
+    assert lib.race_attn_bwd_saved(ctypes.byref(d), p[0], p[1], p[2], p[3], p[4], p[5], seeds, p[6], p[7], p[8], None, None, need, None) == ra.RACE_ERR_WORKSPACE
+    assert lib.race_attn_bwd_saved(ctypes.byref(d), p[0], p[1], p[2], p[3], p[4], p[5], seeds, p[6], p[7], p[8], None, ok_ws, need - 1, None) == ra.RACE_ERR_WORKSPACE
     assert lib.race_attn_debug_hash(ctypes.byref(d), p[0], seeds, None, None, ok_ws, need, None) == ra.RACE_ERR_INVALID_ARG
     assert lib.race_attn_debug_buckets(ctypes.byref(d), p[0], p[1], seeds, p[2], None, ok_ws, need, None) == ra.RACE_ERR_INVALID_ARG
 
@@ -103,6 +108,7 @@ def test_empty_sequence_is_a_no_op():
     assert lib.race_attn_fwd(ctypes.byref(d), p[0], p[1], p[2], seeds, p[3], p[4], None, 0, None) == ra.RACE_OK
     assert lib.race_attn_bwd(ctypes.byref(d), p[0], p[1], p[2], p[3], p[4], p[5], seeds, p[6], p[7], p[8], None, 0, None) == ra.RACE_OK
     assert lib.race_attn_bwd_beta(ctypes.byref(d), p[0], p[1], p[2], p[3], p[4], p[5], seeds, p[6], p[7], p[8], p[9], None, 0, None) == ra.RACE_OK
+    assert lib.race_attn_bwd_saved(ctypes.byref(d), p[0], p[1], p[2], p[3], p[4], p[5], seeds, p[6], p[7], p[8], p[9], None, 0, None) == ra.RACE_OK
 
 
 def test_workspace_grows_with_the_problem_and_families_are_reported():

@@ -135,7 +135,7 @@ def _long_context(w, n0):
     """Full-size run in the benchmark's launch configuration; prefix parity and size-free properties."""
     assert _is_mfma(w)
     Q, K, V, dO = synth.make_inputs(w, "cuda", on_device_rng=True)
-    g = run_gpu(w, (Q, K, V, dO))
+    g = run_gpu(w, (Q, K, V, dO), saved=True)
     W = oracle_w(w, g["seeds"])
     host = [to_f64(t[:, :, :n0]) for t in (Q, K, V, dO)]
     O, den = oracle_stream.forward(host[0], host[1], host[2], W, w.sharpening, w.L, w.P, True)
@@ -189,3 +189,33 @@ def test_beta_cotangent_encoder_shape():
     from parity_util import check_dbeta
     check_dbeta(Workload("m-beta-c3", 2, 2, 900, 64, 16, 4, 4.0, True, "bf16", chunk=128))
     check_dbeta(Workload("m-beta-c3n", 2, 2, 900, 64, 16, 4, 4.0, False, "bf16"))
+
+
+@pytest.mark.parametrize("w", [
+    Workload("saved-causal", 1, 2, 4100, 128, 8, 6, 8.0, True, "bf16", normalize_qk=True, chunk=1024),
+    Workload("saved-noncausal", 1, 2, 1000, 128, 8, 6, 8.0, False, "bf16", normalize_qk=True, chunk=256),
+    Workload("saved-encoder", 2, 2, 900, 64, 16, 4, 4.0, True, "bf16", chunk=128),
+    Workload("saved-padded", 1, 2, 1000, 128, 3, 3, 8.0, True, "bf16", normalize_qk=True, chunk=256),
+    Workload("saved-generic", 1, 1, 300, 64, 4, 4, 8.0, True, "fp32", chunk=64),
+], ids=lambda w: w.name)
+def test_backward_on_the_forward_workspace_is_bit_identical(w):
+    """race_attn_bwd_saved reads the statistics race_attn_fwd left in the workspace instead of deriving them
+    again; its outputs must equal race_attn_bwd_beta's (oracle-checked above) bit for bit.  The generic family
+    keeps nothing and recomputes."""
+    Q, K, V, dO = synth.make_inputs(w, "cuda")
+    seeds = synth.projection_seeds(w)
+    d = desc_of(w)
+    ws = torch.empty(ra.race_attn_workspace_bytes(d), dtype=torch.uint8, device="cuda")
+    O, den = ra.race_attn_fwd(d, Q, K, V, seeds, workspace=ws)
+    got = ra.race_attn_bwd_saved(d, Q, K, V, O, den, dO, seeds, ws, want_dbeta=True)
+    torch.cuda.synchronize()
+    ws2 = torch.zeros_like(ws)
+    ref = ra.race_attn_bwd_beta(d, Q, K, V, O, den, dO, seeds, workspace=ws2)
+    torch.cuda.synchronize()
+    for name, a, b in zip(("dQ", "dK", "dV", "dbeta"), got, ref):
+        assert torch.equal(a, b), name
+    # twice in a row on the same workspace (the backward pass does not disturb what it reads)
+    again = ra.race_attn_bwd_saved(d, Q, K, V, O, den, dO, seeds, ws)
+    torch.cuda.synchronize()
+    for name, a, b in zip(("dQ", "dK", "dV"), again, ref):
+        assert torch.equal(a, b), name
