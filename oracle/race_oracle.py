@@ -194,6 +194,35 @@ def forward_streaming(Q, K, V, W, beta, L, P):
     return num / den[:, None], den
 
 
+def forward_hard(Q, K, V, W, L, P, causal):
+    """Hard RACE (Section 3.3: the hash h(x) = sign(W x) before it is softened; the limit beta -> infinity of
+    Algorithms 1/2).  Every table keeps per-bucket counters A (keys seen) and B (their summed values); key j
+    goes to bucket hard_codes(K_j) of every table, query i reads the counters of its own buckets:
+    Num_i = (1/L) sum_l B_l[code_l(Q_i)], Den_i = (1/L) sum_l A_l[code_l(Q_i)], O_i = Num_i / Den_i.
+    Causal: key i is added before query i reads (Algorithm 2).  A query whose buckets are all empty has
+    Den_i = 0; O_i is defined as 0 then (the paper does not say; the soft assignment never gets there)."""
+    cq, ck = hard_codes(Q, W, L, P), hard_codes(K, W, L, P)
+    N, d = V.shape
+    R = 1 << P
+    A = np.zeros((L, R))
+    B = np.zeros((L, R, d))
+    num = np.zeros((N, d))
+    den = np.zeros(N)
+    tables = np.arange(L)
+    if not causal:
+        for j in range(N):
+            A[tables, ck[j]] += 1.0
+            B[tables, ck[j]] += V[j]
+    for i in range(N):
+        if causal:
+            A[tables, ck[i]] += 1.0
+            B[tables, ck[i]] += V[i]
+        num[i] = B[tables, cq[i]].sum(axis=0) / L
+        den[i] = A[tables, cq[i]].sum() / L
+    O = np.where(den[:, None] > 0, num / np.where(den > 0, den, 1.0)[:, None], 0.0)
+    return O, den
+
+
 def bucket_statistics(K, V, W, beta, L, P):
     """Final (all-N) per-table statistics A (L, R) and B (L, R, d) of Algorithm 1, step 5."""
     pk = soft_hash(K, W, beta, L, P)

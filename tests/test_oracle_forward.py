@@ -267,3 +267,40 @@ def test_decode_steps_reproduce_the_causal_forward_and_the_state_is_the_bucket_s
     for t in range(n0, N):
         o, _ = ro.decode_step(st, Q[t], K[t], V[t], W, beta, L, P)
         assert np.allclose(o, O[t], rtol=1e-12, atol=1e-14)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_hard_race_is_collision_count_attention_and_the_limit_of_the_soft_one(causal):
+    # Section 3.3: with h(x) = sign(W x), key j gets weight (number of tables where it shares the query's bucket);
+    # brute force over pairs, then the soft layer at a large temperature away from the hyperplanes.
+    rng = np.random.default_rng(9)
+    N, d, L, P = 70, 8, 5, 3
+    W = ro.expand_projection(13, L, P, d)
+    def far(n):
+        out = []
+        while len(out) < n:
+            x = rng.standard_normal(d) * 2
+            if np.abs(W @ x).min() > 0.5:
+                out.append(x)
+        return np.array(out)
+    Q, K = far(N), far(N)
+    V = rng.standard_normal((N, d))
+    O, den = ro.forward_hard(Q, K, V, W, L, P, causal)
+    cq, ck = ro.hard_codes(Q, W, L, P), ro.hard_codes(K, W, L, P)
+    empty = 0
+    for i in range(N):
+        js = np.arange(i + 1) if causal else np.arange(N)
+        c = (cq[i][None, :] == ck[js]).sum(axis=1).astype(float)       # collisions per key
+        assert den[i] == c.sum() / L
+        if c.sum() == 0:
+            assert not O[i].any()
+            empty += 1
+        else:
+            assert np.allclose(O[i], (c[:, None] * V[js]).sum(axis=0) / c.sum(), atol=1e-12)
+    assert empty < N // 2
+    Os, dens = ro.forward_quadratic(Q, K, V, W, 60.0, L, P, causal)
+    keep = den > 0
+    assert np.allclose(dens[keep], den[keep], atol=1e-8) and np.allclose(Os[keep], O[keep], atol=1e-7)
+    # causal self-attention (Q = K): token i always meets itself in all L tables
+    O2, den2 = ro.forward_hard(K, K, V, W, L, P, True)
+    assert den2.min() >= 1.0 and np.allclose(O2[0], V[0])
