@@ -23,6 +23,11 @@
  *     significant bit and belongs to row l*P+0 of W).
  *   - sharpening is the temperature beta of Algorithms 1/2.  Q and K are used as given:
  *     no normalisation and no 1/sqrt(d) scaling happens inside the layer.
+ *     beta = +infinity selects the hard hash h(x) = sign(W x) that Section 3.3 starts from
+ *     (bit t of the bucket is [<w_t, x> >= 0]; counters instead of soft masses), for inference:
+ *     the forward pass, the taps and incremental decoding accept it, the backward passes return
+ *     RACE_ERR_UNSUPPORTED (the hard hash is piecewise constant).  A query all of whose buckets
+ *     are empty has den = 0 and gets O = 0 (non-causal only; the soft layer never has den = 0).
  *   - The caller owns every buffer, including the workspace (device memory, 256-byte
  *     aligned, at least race_attn_workspace_bytes() bytes; contents are scratch).  The
  *     library allocates no device memory, never synchronises the stream and launches all
@@ -62,7 +67,7 @@ typedef struct {
     int64_t N;        /* tokens per sequence (>= 0)                                            */
     int32_t d;        /* head dimension: multiple of 8, 8 <= d <= 256                          */
     int32_t L, P;     /* tables (>= 1), hyperplanes per table (1..8); R = 1 << P               */
-    float sharpening; /* beta > 0, finite                                                      */
+    float sharpening; /* beta > 0; +infinity = hard hash (forward only)                        */
     int32_t causal;   /* 0: Algorithm 1 (all keys); 1: Algorithm 2 (keys j <= i)               */
     int32_t dtype;    /* race_dtype_t of Q, K, V, O, dO, dQ, dK, dV                            */
     int64_t chunk;    /* tokens per scan segment: the sequence is cut into segments whose

@@ -322,7 +322,8 @@ __device__ __forceinline__ void bit_masses(const f32x16 &z, int j, const Soft &s
         const float e2 = __expf(-2.0f * fabsf(zt));
         const float inv = __builtin_amdgcn_rcpf(1.0f + e2);
         const float ua = (1.0f - e2) * inv;                    // |tanh z|
-        const float e = __expf(-2.0f * beta * ua);
+        // beta = +infinity is the hard hash: e = 0, and at z = 0 (-inf * 0 = NaN; fmaxf returns its other argument) the bit is set
+        const float e = __expf(fmaxf(-2.0f * beta * ua, -1e30f));
         const float big = __builtin_amdgcn_rcpf(1.0f + e), small = e * big;
         const bool pos = zt >= 0.f;
         p[t] = pos ? big : small;

@@ -400,7 +400,7 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
                 if (MODE == kForward) e += src[C::D] + (dnp[gg * 64 + tok] + dnp[gg * 64 + 32 + tok]);
             }
             if (tok < nvalid) {
-                const float scale = (MODE == kForward) ? 1.0f / e : 1.0f;
+                const float scale = (MODE == kForward) ? (e > 0.f ? 1.0f / e : 0.f) : 1.0f;   // e = 0: hard hash, empty buckets
                 bf16raw *dst = Out + (t0 + tok) * C::D + c0;
 #pragma unroll
                 for (int c = 0; c < NP; ++c)

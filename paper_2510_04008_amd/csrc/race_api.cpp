@@ -170,7 +170,7 @@ race_status_t make_plan(const race_attn_desc_t *desc, Plan *pl)
     if (!desc) return RACE_ERR_INVALID_ARG;
     if (desc->B < 1 || desc->H < 1 || desc->N < 0 || desc->d < 1 || desc->L < 1 || desc->P < 1)
         return RACE_ERR_INVALID_ARG;
-    if (!(desc->sharpening > 0.0f) || !std::isfinite(desc->sharpening)) return RACE_ERR_INVALID_ARG;
+    if (!(desc->sharpening > 0.0f)) return RACE_ERR_INVALID_ARG;         // NaN fails too; +infinity = hard hash
     if (desc->causal != 0 && desc->causal != 1) return RACE_ERR_INVALID_ARG;
     if (desc->dtype != RACE_F32 && desc->dtype != RACE_BF16) return RACE_ERR_INVALID_ARG;
     if (desc->chunk < 0) return RACE_ERR_INVALID_ARG;
@@ -350,6 +350,7 @@ race_status_t backward(const race_attn_desc_t *desc, const void *Q, const void *
     if (s != RACE_OK) return s;
     if (p.N == 0) return RACE_OK;      // nothing to do, pointers may be null
     if (!Q || !K || !V || !O || !den || !dO || !proj_seeds || !dQ || !dK || !dV) return RACE_ERR_INVALID_ARG;
+    if (std::isinf(p.beta)) return RACE_ERR_UNSUPPORTED;      // the hard hash is piecewise constant: inference only
     if (any_equal({dQ, dK, dV}, {Q, K, V, O, den, dO, dQ, dK, dV})) return RACE_ERR_INVALID_ARG;
     if (dbeta && any_equal({dbeta}, {Q, K, V, O, den, dO, dQ, dK, dV, dbeta})) return RACE_ERR_INVALID_ARG;
     if ((s = check_workspace(p, workspace, workspace_bytes, p.total)) != RACE_OK) return s;

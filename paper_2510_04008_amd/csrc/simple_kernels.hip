@@ -116,6 +116,13 @@ __device__ void load_cotangent_rows(const T *dO, const T *O, const float *den, s
 
 // Projection + soft assignment of nt rows (Algorithm 1, steps 2-4).  phi is built from its
 // factorised form phi_r = prod_t sigmoid(2 beta v_{r,t} u_t), u = tanh(W x), which equals the
+// e = exp(-2 beta |u|), the ratio of the two masses of a bit.  beta = +infinity is the hard hash of Section 3.3:
+// e = 0 for u != 0, and for u = 0 (where -inf * 0 is NaN; fmaxf returns its other argument) the bit counts as set, like z >= 0.
+__device__ __forceinline__ float mass_ratio(float beta, float u)
+{
+    return expf(fmaxf(-2.0f * beta * fabsf(u), -1e30f));
+}
+
 // softmax over corners exactly (the softmax denominator is prod_t 2 cosh(beta u_t)).
 __device__ void hash_rows(const Args &a, const float *Wl, const float *xs, int nt, HashView hv)
 {
@@ -129,7 +136,7 @@ __device__ void hash_rows(const Args &a, const float *Wl, const float *xs, int n
         z += __shfl_xor(z, 2, 64);
         if (sub == 0) {
             const float u = tanhf(z);
-            const float e = expf(-2.0f * a.beta * fabsf(u));      // in (0, 1]
+            const float e = mass_ratio(a.beta, u);                  // in [0, 1]
             const float big = 1.0f / (1.0f + e), small = e / (1.0f + e);
             const float e2 = expf(-2.0f * fabsf(z));               // 1 - tanh^2 z = 4 e2 / (1 + e2)^2
             hv.u[pair] = u;
@@ -306,7 +313,7 @@ __global__ void simple_fwd_combine(Args a, int BH, const float *part, T *O, floa
         dn += p[a.d];
     }
     const float invL = 1.0f / static_cast<float>(a.L);
-    store_elem(O, i, (num * invL) / (dn * invL));
+    store_elem(O, i, dn > 0.f ? (num * invL) / (dn * invL) : 0.f);      // dn = 0: only the hard hash, empty buckets
     if (c == 0) den[row] = dn * invL;
 }
 
@@ -471,7 +478,7 @@ __global__ void simple_hash_tap(Args a, int BH, const T *X, uint8_t *codes, floa
         for (int c = 0; c < a.d; ++c) z = fmaf(Wl[t * a.d + c], load_elem(X, row * a.d + c), z);
         code |= (z >= 0.f ? 1u : 0u) << t;
         const float u = tanhf(z);
-        const float e = expf(-2.0f * a.beta * fabsf(u));
+        const float e = mass_ratio(a.beta, u);
         const float big = 1.0f / (1.0f + e), small = e / (1.0f + e);
         p[t] = (u >= 0.f) ? big : small;
         q[t] = (u >= 0.f) ? small : big;
@@ -528,7 +535,7 @@ __global__ __launch_bounds__(256) void decode_step_kernel(int H, int L, int P, i
         float z = 0.f;
         for (int c = 0; c < d; ++c) z = fmaf(Wl[t * d + c], x[c], z);
         const float u = tanhf(z);
-        const float e = expf(-2.0f * beta * fabsf(u));
+        const float e = mass_ratio(beta, u);
         const float big = 1.0f / (1.0f + e), small = e / (1.0f + e);
         pp[2 * tid] = (u >= 0.f) ? big : small;          // mass on the +1 side
         pp[2 * tid + 1] = (u >= 0.f) ? small : big;
@@ -565,7 +572,7 @@ __global__ void decode_combine_kernel(int L, int d, const float *partial, T *o, 
     for (int c = threadIdx.x; c < d; c += blockDim.x) {
         float num = 0.f;
         for (int l = 0; l < L; ++l) num += src[l * d1 + c];
-        store_elem(o, static_cast<size_t>(bh) * d + c, num / dn);
+        store_elem(o, static_cast<size_t>(bh) * d + c, dn > 0.f ? num / dn : 0.f);
     }
     if (threadIdx.x == 0) den[bh] = dn / static_cast<float>(L);
 }

@@ -39,7 +39,7 @@ def _desc(**kw):
 
 @pytest.mark.parametrize("bad", [dict(B=0), dict(H=0), dict(N=-1), dict(d=0), dict(L=0), dict(P=0),
                                  dict(sharpening=0.0), dict(sharpening=-1.0), dict(sharpening=float("nan")),
-                                 dict(sharpening=float("inf")), dict(dtype=7), dict(chunk=-5)])
+                                 dict(sharpening=float("-inf")), dict(dtype=7), dict(chunk=-5)])
 def test_invalid_descriptors_are_rejected(bad):
     d = _desc(**bad)
     if "causal" not in bad:
@@ -49,6 +49,19 @@ def test_invalid_descriptors_are_rejected(bad):
     seeds = (ctypes.c_uint64 * 2)(1, 2)
     st = lib.race_attn_fwd(ctypes.byref(d), fake, fake, fake, seeds, fake, fake, fake, 1 << 40, None)
     assert st == ra.RACE_ERR_INVALID_ARG
+
+
+def test_infinite_temperature_is_the_hard_hash_forward_only():
+    d = _desc(sharpening=float("inf"))
+    need = ra.race_attn_workspace_bytes(d)
+    assert need > 0
+    lib = ra.lib()
+    p = [ctypes.c_void_p(256 * (i + 1)) for i in range(10)]
+    seeds = (ctypes.c_uint64 * 2)(1, 2)
+    ok_ws = ctypes.c_void_p(1 << 20)
+    for entry in (lib.race_attn_bwd_beta, lib.race_attn_bwd_saved):
+        assert entry(ctypes.byref(d), p[0], p[1], p[2], p[3], p[4], p[5], seeds, p[6], p[7], p[8], None, ok_ws, need, None) == ra.RACE_ERR_UNSUPPORTED
+    assert lib.race_attn_bwd(ctypes.byref(d), p[0], p[1], p[2], p[3], p[4], p[5], seeds, p[6], p[7], p[8], ok_ws, need, None) == ra.RACE_ERR_UNSUPPORTED
 
 
 def test_causal_flag_must_be_0_or_1():
