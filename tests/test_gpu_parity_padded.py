@@ -14,7 +14,9 @@ from parity_util import TOL, check_case, check_dbeta, desc_of, oracle_w, to_f64
 
 pytestmark = pytest.mark.gpu
 
-GRID = [(2, 2, 128), (3, 3, 128), (4, 4, 128), (3, 5, 64), (1, 1, 128), (4, 16, 128)]
+GRID = [(2, 2, 128), (3, 3, 128), (4, 4, 128), (3, 5, 64), (1, 1, 128), (4, 16, 128),
+        # beyond four hyperplanes: the padded instantiations of the L = 8, P = 6 shape
+        (5, 5, 128), (6, 4, 128), (5, 8, 128), (6, 8, 64), (5, 3, 64)]
 
 
 @pytest.mark.parametrize("P,L,d", GRID)
