@@ -68,6 +68,11 @@ struct TotalsLds {
     static_assert(total <= 160 * 1024, "LDS budget");
 };
 
+// which column group carries the extra column of row tile mt (alternating halves the vector work per wavefront;
+// with a single row tile per wavefront, column group 0 has it)
+template <class C>
+__device__ __forceinline__ bool mass_owner(int mt, int cg) { return C::MT > 1 ? (mt & 1) == cg : cg == 0; }
+
 template <class C, int QG>
 __global__ __launch_bounds__(kThreads)
 void totals_kernel(KArgs a, const bf16raw *X, const bf16raw *Y, const bf16raw *Oin, const float *den_in)
@@ -136,14 +141,14 @@ void totals_kernel(KArgs a, const bf16raw *X, const bf16raw *Y, const bf16raw *O
 #pragma unroll
             for (int nt = 0; nt < C::NTW; ++nt) by[nt] = lds_tr_plain(ys, C::YS, 16 * s, c_own + 32 * nt, ln, h);
             float4 g0 = {1.f, 1.f, 1.f, 1.f}, g1 = g0;
-            if (QG && cg == 0) {
+            if (QG) {
                 g0 = *reinterpret_cast<const float4 *>(ge_lds + 16 * s + 8 * h);
                 g1 = *reinterpret_cast<const float4 *>(ge_lds + 16 * s + 8 * h + 4);
             }
 #pragma unroll
             for (int mt = 0; mt < C::MT; ++mt) {
                 const u32x4 ap = lds_tr_plain<true>(ph, C::PST, 16 * s, r_own + 32 * mt, ln, h);
-                if (cg == 0)      // the extra column (bucket mass, or its cotangent) is carried by column group 0
+                if (mass_owner<C>(mt, cg))      // the extra column (bucket mass, or its cotangent): shared out over the column groups
                     macc[mt] += bf_lo(ap.x) * g0.x + bf_hi(ap.x) * g0.y + bf_lo(ap.y) * g0.z + bf_hi(ap.y) * g0.w +
                                 bf_lo(ap.z) * g1.x + bf_hi(ap.z) * g1.y + bf_lo(ap.w) * g1.z + bf_hi(ap.w) * g1.w;
 #pragma unroll
@@ -161,7 +166,7 @@ void totals_kernel(KArgs a, const bf16raw *X, const bf16raw *Y, const bf16raw *O
                 st[state_b<C>(r_own + 32 * mt + acc_row(v, h), c_own + 32 * nt + ln)] = Sacc[mt][nt][v];
         }
         const float tot = macc[mt] + __shfl_xor(macc[mt], 32, 64);
-        if (cg == 0 && h == 0) st[state_a<C>(r_own + 32 * mt + ln)] = tot;
+        if (mass_owner<C>(mt, cg) && h == 0) st[state_a<C>(r_own + 32 * mt + ln)] = tot;
     }
 }
 
