@@ -194,14 +194,17 @@ struct RowChunks {
     u32x4 v[N];
 };
 
+// Every lane loads, unconditionally: rows past the end of the tile (nvalid >= 1 rows are real) re-read the last real
+// row and are zeroed when they are stored.  (A load under a condition, into registers cleared first, makes the
+// compiler wait for every load in flight before the clearing moves: the loads of a tile would complete one by one.)
 template <class C, int ROWS>
 __device__ __forceinline__ void fetch_rows(const bf16raw *X, int64_t t0, int nvalid, RowChunks<C, ROWS> &r)
 {
 #pragma unroll
     for (int k = 0; k < RowChunks<C, ROWS>::N; ++k) {
         const int c = threadIdx.x + k * kThreads, row = c / C::CPR, ch = c % C::CPR;
-        r.v[k] = u32x4{0, 0, 0, 0};
-        if (row < nvalid) r.v[k] = *reinterpret_cast<const u32x4 *>(X + (t0 + row) * C::D + ch * 8);
+        const int rr = row < nvalid ? row : nvalid - 1;
+        r.v[k] = *reinterpret_cast<const u32x4 *>(X + (t0 + rr) * C::D + ch * 8);
     }
 }
 
@@ -219,14 +222,17 @@ __device__ __forceinline__ void store_chunk(bf16raw *dst, int row, int ch, u32x4
     }
 }
 
+// nvalid: rows of the tile that exist; the others are stored as zeros.
 template <class C, int ROWS, int STRIDE = C::XS, bool IL = false>
-__device__ __forceinline__ void store_rows(const RowChunks<C, ROWS> &r, bf16raw *dst)
+__device__ __forceinline__ void store_rows(const RowChunks<C, ROWS> &r, bf16raw *dst, int nvalid)
 {
     const int tid = opaque(static_cast<int>(threadIdx.x));       // keeps the tile addresses out of long-lived registers
 #pragma unroll
     for (int k = 0; k < RowChunks<C, ROWS>::N; ++k) {
         const int c = tid + k * kThreads, row = c / C::CPR, ch = c % C::CPR;
-        if (row < ROWS) store_chunk<STRIDE, IL>(dst, row, ch, r.v[k]);
+        const bool real = row < nvalid;
+        const u32x4 v = {real ? r.v[k].x : 0u, real ? r.v[k].y : 0u, real ? r.v[k].z : 0u, real ? r.v[k].w : 0u};
+        if (row < ROWS) store_chunk<STRIDE, IL>(dst, row, ch, v);
     }
 }
 
@@ -246,18 +252,19 @@ __device__ __forceinline__ void fetch_cotangent(const bf16raw *dO, const bf16raw
 #pragma unroll
     for (int k = 0; k < RowChunks<C, ROWS>::N; ++k) {
         const int row = (threadIdx.x + k * kThreads) / C::CPR;
-        r.den[k] = (row < nvalid) ? den[t0 + row] : 0.f;
+        r.den[k] = den[t0 + (row < nvalid ? row : nvalid - 1)];
     }
 }
 
 template <class C, int ROWS, int STRIDE = C::XS, bool IL = false>
-__device__ __forceinline__ void store_cotangent(const CotChunks<C, ROWS> &r, bf16raw *dst, float *ge, int L_real)
+__device__ __forceinline__ void store_cotangent(const CotChunks<C, ROWS> &r, bf16raw *dst, float *ge, int L_real, int nvalid)
 {
     const int tid = opaque(static_cast<int>(threadIdx.x));
 #pragma unroll
     for (int k = 0; k < RowChunks<C, ROWS>::N; ++k) {
         const int c = tid + k * kThreads, row = c / C::CPR, ch = c % C::CPR;
-        const float inv = r.den[k] > 0.f ? 1.0f / (r.den[k] * static_cast<float>(L_real)) : 0.f;
+        // rows past the end of the tile hold a copy of the last real row: they get zero cotangents
+        const float inv = (row < nvalid && r.den[k] > 0.f) ? 1.0f / (r.den[k] * static_cast<float>(L_real)) : 0.f;
         const uint32_t gw[4] = {r.g.v[k].x, r.g.v[k].y, r.g.v[k].z, r.g.v[k].w};
         const uint32_t ow[4] = {r.o.v[k].x, r.o.v[k].y, r.o.v[k].z, r.o.v[k].w};
         uint32_t out[4];

@@ -184,15 +184,15 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
         const int nvalid = tile_nv(t0);
 
         // ---- registers -> LDS
-        store_rows<C, kTile>(pre_r, xr);
-        if (intra) store_rows<C, kTile>(pre_w, xw);
+        store_rows<C, kTile>(pre_r, xr, nvalid);
+        if (intra) store_rows<C, kTile>(pre_w, xw, nvalid);
         if (SIDE == 0) {
-            store_cotangent<C, kTile, C::XS, true>(pre_c, yr, sr, a.L_real);
-            if (intra) store_rows<C, kTile, C::YS, true>(pre_v, yw);
+            store_cotangent<C, kTile, C::XS, true>(pre_c, yr, sr, a.L_real, nvalid);
+            if (intra) store_rows<C, kTile, C::YS, true>(pre_v, yw, nvalid);
             if (tid < kTile) sw[tid] = 1.f;
         } else {
-            store_rows<C, kTile, C::XS, true>(pre_v, yr);
-            if (intra) store_cotangent<C, kTile, C::YS, true>(pre_c, yw, sw, a.L_real);
+            store_rows<C, kTile, C::XS, true>(pre_v, yr, nvalid);
+            if (intra) store_cotangent<C, kTile, C::YS, true>(pre_c, yw, sw, a.L_real, nvalid);
             if (tid < kTile) sr[tid] = 1.f;
         }
         GRAD_PHASE(0)

@@ -123,9 +123,9 @@ void totals_kernel(KArgs a, const bf16raw *X, const bf16raw *Y, const bf16raw *O
     for (int it = 0; it < nsteps; ++it) {
         const int64_t t0 = t_begin + static_cast<int64_t>(it) * TT;
         const int nvalid = step_nv(t0);
-        store_rows<C, TT>(pre_x, xs);
-        if (QG) store_cotangent<C, TT, C::YS>(pre_c, ys, ge_lds, a.L_real);
-        else store_rows<C, TT, C::YS>(pre_y, ys);
+        store_rows<C, TT>(pre_x, xs, nvalid);
+        if (QG) store_cotangent<C, TT, C::YS>(pre_c, ys, ge_lds, a.L_real, nvalid);
+        else store_rows<C, TT, C::YS>(pre_y, ys, nvalid);
         if (it + 1 < nsteps) fetch(it + 1);
         __syncthreads();
         {
@@ -271,11 +271,11 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
         const int nvalid = tile_nv(t0);
 
         // ---- registers -> LDS, then start the next tile's loads
-        store_rows<C, kTile>(pre_r, xr);
+        store_rows<C, kTile>(pre_r, xr, nvalid);
         if (intra) {
-            store_rows<C, kTile>(pre_w, xw);
-            if (MODE == kGradV) store_cotangent<C, kTile, C::YS>(pre_c, ytile, nullptr, a.L_real);
-            else store_rows<C, kTile, C::YS>(pre_y, ytile);
+            store_rows<C, kTile>(pre_w, xw, nvalid);
+            if (MODE == kGradV) store_cotangent<C, kTile, C::YS>(pre_c, ytile, nullptr, a.L_real, nvalid);
+            else store_rows<C, kTile, C::YS>(pre_y, ytile, nvalid);
         }
         RACE_PHASE(0)
         __syncthreads();
@@ -495,7 +495,7 @@ __global__ __launch_bounds__(kThreads) void hash_tap_kernel(KArgs a, const bf16r
     {
         RowChunks<C, kTile> rows;
         fetch_rows<C, kTile>(X + static_cast<size_t>(bh) * a.N * C::D, t0, nvalid, rows);
-        store_rows<C, kTile>(rows, x);
+        store_rows<C, kTile>(rows, x, nvalid);
     }
     __syncthreads();
     if (w < C::NG) {
