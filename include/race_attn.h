@@ -169,7 +169,9 @@ size_t race_attn_step_workspace_bytes(const race_attn_desc_t *desc);
 /* One new token per (batch, head): q, k, v are DEVICE (B, H, d) rows of desc->dtype.  The state is updated in
  * place with (k, v) first, then q reads it (the loop body of Algorithm 2): o (DEVICE (B, H, d), desc->dtype) and
  * den (DEVICE float (B, H), with the 1/L of Algorithm 1 step 7).  desc->N, desc->causal and desc->chunk are
- * ignored.  Arithmetic is fp32 on the values as given.  Cost O(L R d) per token and head. */
+ * ignored.  Arithmetic is fp32 on the values as given.  Cost O(L R d) per token and head; one kernel launch.
+ * The call expands proj_seeds into the workspace (a copy from pinned host memory) and leaves W there: a later step
+ * with the same desc on a workspace nobody has written to since may pass proj_seeds = NULL and skips the copy. */
 race_status_t race_attn_step(const race_attn_desc_t *desc, const void *q, const void *k, const void *v,
                              const uint64_t *proj_seeds, float *state, void *o, float *den,
                              void *workspace, size_t workspace_bytes, race_stream_t stream);

@@ -298,7 +298,8 @@ def race_attn_step_workspace_bytes(desc: RaceAttnDesc) -> int:
 
 def race_attn_step(desc: RaceAttnDesc, q, k, v, proj_seeds: Sequence[int], state, o=None, den=None, workspace=None,
                    stream=None):
-    """One decoding step: q, k, v (B, H, d); state updated in place; returns o (B, H, d) and den (B, H)."""
+    """One decoding step: q, k, v (B, H, d); state updated in place; returns o (B, H, d) and den (B, H).
+    proj_seeds = None: the workspace (then a required argument) still holds W from an earlier step."""
     torch = _torch()
     row = (desc.B, desc.H, desc.d)
     for t, n in ((q, "q"), (k, "k"), (v, "v")):
@@ -310,8 +311,11 @@ def race_attn_step(desc: RaceAttnDesc, q, k, v, proj_seeds: Sequence[int], state
     _check_tensor(den, desc, "den", (desc.B, desc.H), torch.float32)
     need = race_attn_step_workspace_bytes(desc)
     if workspace is None:
+        if proj_seeds is None:
+            raise ValueError("race_attn_step without seeds needs the workspace of an earlier step")
         workspace = torch.empty(need, dtype=torch.uint8, device=v.device)
-    st = lib().race_attn_step(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(), _seeds(proj_seeds),
+    st = lib().race_attn_step(ctypes.byref(desc), q.data_ptr(), k.data_ptr(), v.data_ptr(),
+                              _seeds(proj_seeds) if proj_seeds is not None else None,
                               state.data_ptr(), o.data_ptr(), den.data_ptr(), workspace.data_ptr(),
                               workspace.numel() * workspace.element_size(), _stream(stream))
     if st != RACE_OK:

@@ -84,7 +84,7 @@ hipError_t simple_buckets(const Plan &p, const void *K, const void *V, float *A,
                           int b_stride, char *ws, hipStream_t st);
 // One decoding step (simple_kernels.hip): W fp32 (H, L*P, d) and partial (BH, L, d+1) in the workspace.
 hipError_t decode_step(const Plan &p, const float *W, const void *q, const void *k, const void *v, float *state,
-                       float *partial, void *o, float *den, hipStream_t st);
+                       void *o, float *den, hipStream_t st);
 hipError_t zero_floats(float *dst, size_t n, hipStream_t st);
 
 // ---- MFMA family (mfma_kernels.hip, mfma_grad.hip).  Compiled shapes: X(d, P, L)

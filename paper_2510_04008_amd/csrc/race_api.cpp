@@ -463,7 +463,7 @@ race_status_t make_step_plan(const race_attn_desc_t *desc, Plan *pl)
     pl->off_W = 0;
     pl->bytes_W = align256(static_cast<size_t>(pl->H) * pl->LP * pl->d * sizeof(float));
     pl->off_part = pl->bytes_W;
-    pl->bytes_part = align256(static_cast<size_t>(pl->BH) * pl->L * (pl->d + 1) * sizeof(float));
+    pl->bytes_part = 0;
     pl->total = pl->off_part + pl->bytes_part;
     return RACE_OK;
 }
@@ -482,14 +482,14 @@ race_status_t race_attn_step(const race_attn_desc_t *desc, const void *q, const 
     Plan p;
     race_status_t s = make_step_plan(desc, &p);
     if (s != RACE_OK) return s;
-    if (!q || !k || !v || !proj_seeds || !state || !o || !den) return RACE_ERR_INVALID_ARG;
+    if (!q || !k || !v || !state || !o || !den) return RACE_ERR_INVALID_ARG;
     if (any_equal({state, o, den}, {q, k, v, state, o, den})) return RACE_ERR_INVALID_ARG;
     if ((s = check_workspace(p, workspace, workspace_bytes, p.total)) != RACE_OK) return s;
     char *ws = static_cast<char *>(workspace);
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    if ((s = upload_projection(p, proj_seeds, ws, st)) != RACE_OK) return s;
-    hipError_t e = decode_step(p, reinterpret_cast<const float *>(ws + p.off_W), q, k, v, state,
-                               reinterpret_cast<float *>(ws + p.off_part), o, den, st);
+    // no seeds: the workspace still holds the W that an earlier step put there
+    if (proj_seeds && (s = upload_projection(p, proj_seeds, ws, st)) != RACE_OK) return s;
+    hipError_t e = decode_step(p, reinterpret_cast<const float *>(ws + p.off_W), q, k, v, state, o, den, st);
     return e == hipSuccess ? RACE_OK : hip_failed(e, "race_attn_step launch");
 }
 

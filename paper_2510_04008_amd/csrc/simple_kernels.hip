@@ -510,71 +510,102 @@ __global__ void simple_bucket_tap(Args a, int BH, const float *state, float *A, 
 }
 
 // ------------------------------------------------------------------ incremental decoding
-// One workgroup per (table, batch*head): hash the new key and query (Algorithm 1, steps 2-4), add the key/value
-// to the table's statistics, read them with the query (Algorithm 2's loop body).  partial: (BH, L, d+1).
+// One decoding step, one workgroup of 1024 threads per (batch, head).  Threads form TF = 1024 / TL slots of
+// TL = 64 ceil(d / 64) threads; a slot takes the tables slot, slot + TF, ... one after the other, thread c of a slot
+// owning column c: it hashes the new key and query against the table's hyperplanes with its slot-mates (Algorithm 1,
+// steps 2-4), adds the key/value to the table's statistics and reads them with the query, column by column
+// (Algorithm 2's loop body; coalesced rows of d+1 floats).  The sums over tables and the normalisation follow in the
+// same kernel (Algorithm 1, steps 7-8): numerators over the slots in slot order, the normaliser over the wavefronts.
+constexpr int kDecodeThreads = 1024;
+
 template <typename T>
-__global__ __launch_bounds__(256) void decode_step_kernel(int H, int L, int P, int d, float beta, const float *W,
-                                                          const T *q, const T *k, const T *v, float *state,
-                                                          float *partial)
+__global__ __launch_bounds__(kDecodeThreads) void decode_step_kernel(int H, int L, int P, int d, float beta, const float *W,
+                                                                     const T *q, const T *k, const T *v, float *state,
+                                                                     T *o, float *den)
 {
     extern __shared__ float lds[];
     const int R = 1 << P, d1 = d + 1;
-    float *xq = lds, *xk = xq + d, *vv = xk + d, *pp = vv + d1, *phiq = pp + 4 * P, *phik = phiq + R;
-    const int l = blockIdx.x, bh = blockIdx.y, h = bh % H, tid = threadIdx.x;
-    const float *Wl = W + (static_cast<size_t>(h) * L + l) * P * d;
-    for (int c = tid; c < d; c += blockDim.x) {
-        xq[c] = load_elem(q, static_cast<size_t>(bh) * d + c);
-        xk[c] = load_elem(k, static_cast<size_t>(bh) * d + c);
-        vv[c] = load_elem(v, static_cast<size_t>(bh) * d + c);
-    }
-    if (tid == 0) vv[d] = 1.0f;
-    __syncthreads();
-    if (tid < 2 * P) {                        // per-bit masses of the query (t < P) and of the key
-        const int t = tid % P;
-        const float *x = tid < P ? xq : xk;
-        float z = 0.f;
-        for (int c = 0; c < d; ++c) z = fmaf(Wl[t * d + c], x[c], z);
-        const float u = tanhf(z);
-        const float e = mass_ratio(beta, u);
-        const float big = 1.0f / (1.0f + e), small = e / (1.0f + e);
-        pp[2 * tid] = (u >= 0.f) ? big : small;          // mass on the +1 side
-        pp[2 * tid + 1] = (u >= 0.f) ? small : big;
-    }
-    __syncthreads();
-    for (int r = tid; r < 2 * R; r += blockDim.x) {
-        const int side = r / R, c = r % R;
-        float f = 1.f;
-        for (int t = 0; t < P; ++t) f *= pp[2 * (side * P + t) + (((c >> t) & 1) ? 0 : 1)];
-        (side ? phik : phiq)[c] = f;
-    }
-    __syncthreads();
-    float *S = state + (static_cast<size_t>(bh) * L + l) * R * d1;
-    for (int c = tid; c < d1; c += blockDim.x) {
-        const float y = vv[c];
-        float acc = 0.f;
-        for (int r = 0; r < R; ++r) {
-            const float s = fmaf(phik[r], y, S[r * d1 + c]);
-            S[r * d1 + c] = s;
-            acc = fmaf(phiq[r], s, acc);
+    const int TL = (d + 63) & ~63, TF = kDecodeThreads / TL, NWV = TL / 64;
+    const int tid = threadIdx.x, slot = tid / TL, c = tid % TL, lane = tid & 63, wv = c >> 6;
+    const int bh = blockIdx.x, h = bh % H;
+    float *zred = lds;                              // [TF][2P][NWV] partial projections
+    float *pq = zred + TF * 2 * P * NWV;            // [TF][2P][2]   per-bit masses (+1 side, -1 side)
+    float *phi = pq + TF * 2 * P * 2;               // [TF][2][R]    assignments of the query (0) and the key (1)
+    float *numred = phi + TF * 2 * R;               // [TF][d]       numerators per slot
+    float *dred = numred + TF * d;                  // [16]          normaliser per wavefront
+    const bool active = slot < TF, colok = active && c < d;
+    const float xq = colok ? load_elem(q, static_cast<size_t>(bh) * d + c) : 0.f;
+    const float xk = colok ? load_elem(k, static_cast<size_t>(bh) * d + c) : 0.f;
+    const float vv = colok ? load_elem(v, static_cast<size_t>(bh) * d + c) : 0.f;
+    float num = 0.f, dn = 0.f;
+    for (int l0 = 0; l0 < L; l0 += TF) {
+        const int l = l0 + slot;
+        const bool on = active && l < L;
+        const float *Wl = W + (static_cast<size_t>(h) * L + (on ? l : 0)) * P * d;
+        for (int t = 0; t < P; ++t) {
+            const float w = (on && c < d) ? Wl[t * d + c] : 0.f;
+            float a = w * xq, b = w * xk;
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) {
+                a += __shfl_xor(a, m, 64);
+                b += __shfl_xor(b, m, 64);
+            }
+            if (active && lane == 0) {
+                zred[(slot * 2 * P + t) * NWV + wv] = a;
+                zred[(slot * 2 * P + P + t) * NWV + wv] = b;
+            }
         }
-        partial[(static_cast<size_t>(bh) * L + l) * d1 + c] = acc;
+        __syncthreads();
+        if (on && c < 2 * P) {                      // per-bit masses of the query (c < P) and of the key
+            float z = 0.f;
+            for (int i = 0; i < NWV; ++i) z += zred[(slot * 2 * P + c) * NWV + i];
+            const float u = tanhf(z);
+            const float e = mass_ratio(beta, u);
+            const float big = 1.0f / (1.0f + e), small = e / (1.0f + e);
+            pq[(slot * 2 * P + c) * 2] = (u >= 0.f) ? big : small;          // mass on the +1 side
+            pq[(slot * 2 * P + c) * 2 + 1] = (u >= 0.f) ? small : big;
+        }
+        __syncthreads();
+        if (on) {
+            for (int r = c; r < 2 * R; r += TL) {
+                const int side = r / R, cr = r % R;
+                float f = 1.f;
+                for (int t = 0; t < P; ++t) f *= pq[(slot * 2 * P + side * P + t) * 2 + (((cr >> t) & 1) ? 0 : 1)];
+                phi[(slot * 2 + side) * R + cr] = f;
+            }
+        }
+        __syncthreads();
+        if (on) {
+            const float *pqv = phi + (slot * 2) * R, *pk = pqv + R;
+            float *S = state + (static_cast<size_t>(bh) * L + l) * R * d1;
+            if (c < d) {
+#pragma unroll 8
+                for (int r = 0; r < R; ++r) {
+                    const float sv = fmaf(pk[r], vv, S[r * d1 + c]);
+                    S[r * d1 + c] = sv;
+                    num = fmaf(pqv[r], sv, num);
+                }
+            }
+            for (int r = c; r < R; r += TL) {       // the mass column
+                const float sv = S[r * d1 + d] + pk[r];
+                S[r * d1 + d] = sv;
+                dn = fmaf(pqv[r], sv, dn);
+            }
+        }
+        __syncthreads();
     }
-}
-
-// Sum over tables in table order, normalise (Algorithm 1, steps 7-8).
-template <typename T>
-__global__ void decode_combine_kernel(int L, int d, const float *partial, T *o, float *den)
-{
-    const int bh = blockIdx.x, d1 = d + 1;
-    const float *src = partial + static_cast<size_t>(bh) * L * d1;
-    float dn = 0.f;
-    for (int l = 0; l < L; ++l) dn += src[l * d1 + d];
-    for (int c = threadIdx.x; c < d; c += blockDim.x) {
-        float num = 0.f;
-        for (int l = 0; l < L; ++l) num += src[l * d1 + c];
-        store_elem(o, static_cast<size_t>(bh) * d + c, dn > 0.f ? num / dn : 0.f);
+    if (colok) numred[slot * d + c] = num;
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) dn += __shfl_xor(dn, m, 64);
+    if (lane == 0) dred[tid >> 6] = dn;
+    __syncthreads();
+    if (tid < d) {
+        float tot = 0.f, dnt = 0.f;
+        for (int sl = 0; sl < TF; ++sl) tot += numred[sl * d + tid];
+        for (int i = 0; i < kDecodeThreads / 64; ++i) dnt += dred[i];
+        store_elem(o, static_cast<size_t>(bh) * d + tid, dnt > 0.f ? tot / dnt : 0.f);
+        if (tid == 0) den[bh] = dnt / static_cast<float>(L);
     }
-    if (threadIdx.x == 0) den[bh] = dn / static_cast<float>(L);
 }
 
 __global__ void zero_kernel(float *dst, size_t n)
@@ -736,19 +767,16 @@ hipError_t zero_floats(float *dst, size_t n, hipStream_t st)
 }
 
 hipError_t decode_step(const Plan &p, const float *W, const void *q, const void *k, const void *v, float *state,
-                       float *partial, void *o, float *den, hipStream_t st)
+                       void *o, float *den, hipStream_t st)
 {
-    const size_t lds = (static_cast<size_t>(3) * p.d + 1 + 4 * p.P + 2 * p.R) * sizeof(float);
-    const dim3 grid(p.L, p.BH);
-    if (p.dtype == RACE_F32) {
-        hipLaunchKernelGGL((decode_step_kernel<float>), grid, dim3(256), lds, st, p.H, p.L, p.P, p.d, p.beta, W,
-                           (const float *)q, (const float *)k, (const float *)v, state, partial);
-        hipLaunchKernelGGL((decode_combine_kernel<float>), dim3(p.BH), dim3(128), 0, st, p.L, p.d, partial, (float *)o, den);
-    } else {
-        hipLaunchKernelGGL((decode_step_kernel<bf16_t>), grid, dim3(256), lds, st, p.H, p.L, p.P, p.d, p.beta, W,
-                           (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v, state, partial);
-        hipLaunchKernelGGL((decode_combine_kernel<bf16_t>), dim3(p.BH), dim3(128), 0, st, p.L, p.d, partial, (bf16_t *)o, den);
-    }
+    const int TL = (p.d + 63) & ~63, TF = kDecodeThreads / TL;
+    const size_t lds = (static_cast<size_t>(TF) * 2 * p.P * (TL / 64) + TF * 4 * p.P + TF * 2 * p.R + TF * p.d + 16) * sizeof(float);
+    if (p.dtype == RACE_F32)
+        hipLaunchKernelGGL((decode_step_kernel<float>), dim3(p.BH), dim3(kDecodeThreads), lds, st, p.H, p.L, p.P, p.d, p.beta, W,
+                           (const float *)q, (const float *)k, (const float *)v, state, (float *)o, den);
+    else
+        hipLaunchKernelGGL((decode_step_kernel<bf16_t>), dim3(p.BH), dim3(kDecodeThreads), lds, st, p.H, p.L, p.P, p.d, p.beta, W,
+                           (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v, state, (bf16_t *)o, den);
     return hipGetLastError();
 }
 

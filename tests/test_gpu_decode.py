@@ -65,3 +65,31 @@ def test_decode_after_prefill_mfma_family_bf16():
 
 def test_decode_from_empty_state_bf16_headline_shape():
     _decode_against_oracle(Workload("dec-bf16", 1, 4, 0, 128, 8, 6, 8.0, True, "bf16"), 0, 16)
+
+
+@pytest.mark.parametrize("d,L,P", [(192, 3, 5), (256, 5, 2), (72, 17, 3), (64, 20, 8)])
+def test_decode_odd_shapes_fp32(d, L, P):
+    # column slots of 64..256 threads, more tables than slots, a slot count that does not divide the workgroup
+    _decode_against_oracle(Workload("dec-odd-d%d-L%d-P%d" % (d, L, P), 1, 2, 0, d, L, P, 4.0, True, "f32"), 0, 6)
+
+
+def test_later_steps_may_reuse_the_projection_in_the_workspace():
+    w = Workload("dec-reuse", 2, 2, 10, 128, 8, 6, 8.0, True, "bf16", normalize_qk=True)
+    Q, K, V, _ = synth.make_inputs(w, "cuda")
+    seeds = synth.projection_seeds(w)
+    d = desc_of(w)
+    d0 = ra.make_desc(w.B, w.H, 0, w.d, w.L, w.P, w.sharpening, True, d.dtype, 0)
+    ws = torch.empty(ra.race_attn_step_workspace_bytes(d), dtype=torch.uint8, device="cuda")
+    runs = []
+    for reuse in (False, True):
+        state = ra.race_attn_state_init(d0, None, None, seeds)
+        outs = []
+        for t in range(w.N):
+            s = None if (reuse and t > 0) else seeds
+            o, den = ra.race_attn_step(d, Q[:, :, t].contiguous(), K[:, :, t].contiguous(), V[:, :, t].contiguous(), s,
+                                       state, workspace=ws)
+            outs += [o.clone(), den.clone()]
+        torch.cuda.synchronize()
+        runs.append(outs + [state])
+    for a, b in zip(*runs):
+        assert torch.equal(a, b)
