@@ -90,7 +90,7 @@ hipError_t zero_floats(float *dst, size_t n, hipStream_t st);
 // ---- MFMA family (mfma_kernels.hip, mfma_grad.hip).  Compiled shapes: X(d, P, L)
 // X(d, P, L, PAD): PAD = 0 serves exactly that shape, PAD = 1 also everything smaller in L and P
 #ifndef RACE_MFMA_SHAPES
-#define RACE_MFMA_SHAPES(X) X(128, 6, 8, 0) X(64, 4, 16, 0) X(64, 4, 16, 1) X(128, 4, 16, 1) X(128, 6, 8, 1) X(64, 6, 8, 1)
+#define RACE_MFMA_SHAPES(X) X(128, 6, 8, 0) X(64, 4, 16, 0) X(64, 4, 16, 1) X(128, 4, 16, 1) X(128, 6, 8, 1) X(64, 6, 8, 1) X(128, 4, 4, 1) X(128, 4, 8, 1)
 #endif
 // The exact shape if compiled, else the padded instantiation with the fewest bucket rows that covers (d, L, P).
 bool mfma_pick(int d, int L, int P, int *Lc, int *Pc, int *pad);

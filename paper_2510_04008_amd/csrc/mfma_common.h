@@ -40,7 +40,7 @@ typedef uint16_t bf16raw;
 
 constexpr int kWaves = 8;
 constexpr int kThreads = 64 * kWaves;
-constexpr int kRowGroups = 4;  // stream kernels: wavefront w owns bucket-row group w % 4 and column group w / 4
+constexpr int kRowGroups = 4;  // most row groups a workgroup's statistics are split into (stream kernels)
 constexpr int kTile = 32;      // tokens per tile
 
 // PAD_: the instantiation also serves problems with fewer tables and hyperplanes than its shape (see Soft).
@@ -54,10 +54,15 @@ struct Cfg {
     static constexpr int TPL = TPG / 2;                 // tables per lane (per half-wave)
     static constexpr int NG = (L + TPG - 1) / TPG;      // projection groups
     static constexpr int LPP = NG * 32;                 // padded projection rows
-    static constexpr int LRW = LR / kRowGroups;         // bucket rows of one row group (stream kernels)
+    // stream kernels: wavefront w owns bucket-row group w % RG and column group w / RG (four row groups x two
+    // column groups, or two x four when there are only 64 bucket rows)
+    static constexpr int RG = LR / 32 >= kRowGroups ? kRowGroups : LR / 32;
+    static constexpr int CG = kWaves / RG;
+    static constexpr int LRW = LR / RG;                 // bucket rows of one row group
     static constexpr int MT = LRW / 32;                 // 32-row tiles of bucket rows per row group
     static constexpr int NT = D / 32;                   // 32-column tiles of the head dimension
-    static constexpr int NTW = NT / 2;                  // column tiles per wavefront (stream kernels)
+    static constexpr int NTW = NT / CG;                 // column tiles per wavefront
+    static constexpr int DW = D / CG;                   // columns per wavefront
     static constexpr int LRG = LR / kWaves;             // bucket rows per wavefront (grad kernel)
     static constexpr int MTG = LRG / 32;                // 32-row tiles per wavefront (grad kernel)
     static constexpr int JSTEP = 4 / NG;                // wavefronts that share one projection group
@@ -71,7 +76,7 @@ struct Cfg {
                                                         // 16-byte row writes and transposing reads both 2-way at most)
     static constexpr int ZS = LPP + 8;                  // [token][padded projection] tiles
     static constexpr int STATE = LR * (D + 1);          // floats per saved state: B [LR][D] then A [LR]
-    static_assert(LR % (32 * kRowGroups) == 0, "bucket rows must split into 32-row tiles per row group");
+    static_assert(RG >= 1 && LR % (32 * RG) == 0 && NT % CG == 0 && NTW >= 1, "bucket rows and columns over the wavefronts");
     static_assert(D % 64 == 0 && P >= 4, "shape (assignments are written for pairs of high-bit indices)");
     static_assert(4 % NG == 0 && NG <= 4, "projection groups must divide four wavefronts");
 };

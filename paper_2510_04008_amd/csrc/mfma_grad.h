@@ -37,13 +37,14 @@ namespace mfma {
 
 // Row tiles per wavefront: all of LR / 256 if that is at most two (128 registers of statistics per lane is what
 // fits next to the working set); beyond that the bucket rows are split over TSPLIT workgroups by tables.
-template <class C> constexpr int grad_row_tiles() { return C::LR / (32 * kWaves) <= 2 ? C::LR / (32 * kWaves) : 2; }
+template <class C> constexpr int grad_row_tiles() { return C::LR / (32 * kWaves) >= 2 ? 2 : 1; }
 
 template <class C>
 struct GradCfg {
     static constexpr int MTG = grad_row_tiles<C>();                     // 32-row tiles of bucket rows per wavefront
     static constexpr int RW = 32 * MTG;                                 // bucket rows per wavefront
-    static constexpr int TSPLIT = C::LR / (RW * kWaves);                // workgroups per (segment, head)
+    static constexpr int NRW = C::LR / RW >= kWaves ? kWaves : C::LR / RW;   // wavefronts that own bucket rows (the first NRW)
+    static constexpr int TSPLIT = C::LR / (RW * NRW);                   // workgroups per (segment, head)
     static constexpr int NGW = C::NG / TSPLIT;                          // projection groups per workgroup
     static constexpr int ROWS = C::LR / TSPLIT;                         // bucket rows per workgroup
     static constexpr int TABLES = NGW * C::TPG;                         // tables per workgroup
@@ -54,9 +55,10 @@ struct GradCfg {
     static constexpr int TW = C::R >= 32 ? 1 : 32 / C::R;               // tables per tile
     static constexpr int KM = (C::R >= 32 ? 32 : C::R) / 8;             // groups of 8 corners per table and tile
     static constexpr int MB = KM == 4 ? 2 : (KM == 2 ? 1 : 0);          // corner bits 3.. that vary inside a tile
-    static_assert(MTG >= 1 && TSPLIT >= 1 && TSPLIT * RW * kWaves == C::LR, "bucket rows over wavefronts");
+    static_assert(MTG >= 1 && NRW >= 1 && TSPLIT >= 1 && TSPLIT * RW * NRW == C::LR, "bucket rows over wavefronts");
+    static_assert(NRW == kWaves || TSPLIT == 1, "a workgroup with spare wavefronts holds all the rows");
     static_assert(C::NG % TSPLIT == 0 && kWaves % NGW == 0, "table split");
-    static_assert(NGW * C::TPG * C::R == ROWS, "a workgroup's rows are the tables of its projection groups");
+    static_assert(NGW * C::TPG * C::R >= ROWS, "a workgroup's rows are the tables of its projection groups");
     static_assert(C::P >= 3 && C::P <= 7, "corner bits 0..2 are register/lane bits; a partial record is P+1 <= 8 floats");
     // production roles.  Writer hashing: one wavefront per (projection group, table of the lane, share of the
     // high-bit indices); reader masses: one per (projection group, table of the lane) if there is room, else one
@@ -84,7 +86,8 @@ struct GradLds {
     static constexpr int PMS = 4 * C::PP + 4;                           // floats per (table, token): p, q, sech^2, tanh, each padded
                                                                         // to PP; + 4 keeps 16-byte reads of 16 tokens on distinct banks
     static constexpr int pm = (sw + kTile * 4 + 15) & ~15;              // [TABLES][32][PMS] fp32: per-bit masses of the reader
-    static constexpr int part = pm + G::TABLES * kTile * PMS * 4;       // [kWaves][32][8] fp32: partial (m, E_t) of table shares
+    static constexpr int PMT = G::TABLES < C::L ? G::TABLES : C::L;     // tables of the workgroup that exist
+    static constexpr int part = pm + PMT * kTile * PMS * 4;             // [kWaves][32][8] fp32: partial (m, G_t) of table shares
     static constexpr int yr = part + (G::WPT > 1 ? kWaves * kTile * 8 * 4 : 0);   // [32][XS] reader-Y rows, pair-interleaved columns
     static constexpr int ttop = yr + kTile * C::XS * 2;                 // [2][64] x 16 B: masked in-tile term as MFMA operands
     static constexpr int xr = (ttop + 2 * 64 * 16 + 255) & ~255;        // [32][XS]
@@ -129,6 +132,9 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
     const int tl0 = (w * G::RW) / C::R;              // first table, counted inside the workgroup
     const int ro = (w * G::RW) % C::R;               // first corner of the share (0 unless a table spans several wavefronts)
     const bool intra = a.causal;
+    // shapes with fewer than 8 x 32 bucket rows: only the first NRW wavefronts carry statistics; the others take
+    // part in the production, the loads and dX
+    const bool has_rows = G::NRW == kWaves || w < G::NRW;
 
     const size_t base = static_cast<size_t>(bh) * a.N * C::D;
     Q += base; K += base; V += base; O += base; dO += base;
@@ -145,6 +151,10 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
             *reinterpret_cast<u32x4 *>(wp + row * C::XS + ch * 8) = *reinterpret_cast<const u32x4 *>(src + row * C::D + ch * 8);
         }
     }
+    if (G::TABLES * C::R != G::ROWS) {
+        // projection slots of tables that do not exist are never written below: they must be zeros for dX = dz . W
+        for (int i = tid; i < kTile * S::DZS; i += kThreads) dz[i] = 0;
+    }
     // statistics at the start of the segment, transposed tiles ST[row tile][column tile]: columns x 32 bucket rows
     f32x16 ST[G::MTG][C::NT];
     float macc[G::MTG];       // extra column (A or dA): per-half partial sum, lane n <-> row r_own + 32 mr + n
@@ -153,9 +163,10 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
 #pragma unroll
         for (int mtc = 0; mtc < C::NT; ++mtc) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) ST[mr][mtc][v] = st[(r_own + 32 * mr + ln) * C::D + 32 * mtc + acc_row(v, h)];
+            for (int v = 0; v < 16; ++v)
+                ST[mr][mtc][v] = has_rows ? st[(r_own + 32 * mr + ln) * C::D + 32 * mtc + acc_row(v, h)] : 0.f;
         }
-        macc[mr] = (h == 0) ? st[C::LR * C::D + r_own + 32 * mr + ln] : 0.f;
+        macc[mr] = (has_rows && h == 0) ? st[C::LR * C::D + r_own + 32 * mr + ln] : 0.f;
     }
 
     const int64_t t_begin = seg * a.seg_len;
@@ -283,6 +294,7 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
         }
 #pragma unroll
         for (int mr = 0; mr < G::MTG; ++mr) {
+            if (!has_rows) break;
             f32x16 dP;
             {
                 // extra column first: sr_a * (A or dA)[r] with the masses before this tile
@@ -361,14 +373,14 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
 #pragma unroll
             for (int t = 0; t <= C::P; ++t) rec[i][t] += __shfl_xor(rec[i][t], 32, 64);
         }
-        if (G::WPT > 1 && ro != 0) {
+        if (G::WPT > 1 && has_rows && ro != 0) {
             // a later share of a table: hand the partial sums to the wavefront that owns the table's first share
             float *dst = part + ((w * kTile + ln) * 8 + 4 * h);
             *reinterpret_cast<float4 *>(dst) = float4{rec[0][4 * h], rec[0][4 * h + 1], rec[0][4 * h + 2], rec[0][4 * h + 3]};
         }
         GRAD_PHASE(5)
         // ---- statistics += Yw^T . phi_writer
-        if (intra) {
+        if (intra && has_rows) {
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
                 const float4 g0 = *reinterpret_cast<const float4 *>(sw + 16 * s + 8 * h);
@@ -393,7 +405,7 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
 
         // ---- finish per (token, table): du_t = +-2 beta (small_t (m - G_t) - big_t G_t),  dz_t = du_t (1 - tanh^2 z_t);
         //      lane half h' takes the padded projection slots 4h' .. 4h'+3
-        if (ro == 0) {
+        if (has_rows && ro == 0) {
 #pragma unroll
             for (int ti = 0; ti < G::TWW; ++ti) {
                 if (4 * h >= C::PP) break;

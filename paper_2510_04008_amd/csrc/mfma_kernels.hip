@@ -68,10 +68,9 @@ struct TotalsLds {
     static_assert(total <= 160 * 1024, "LDS budget");
 };
 
-// which column group carries the extra column of row tile mt (alternating halves the vector work per wavefront;
-// with a single row tile per wavefront, column group 0 has it)
+// which column group carries the extra column of row tile mt (taking turns spreads the vector work over the wavefronts)
 template <class C>
-__device__ __forceinline__ bool mass_owner(int mt, int cg) { return C::MT > 1 ? (mt & 1) == cg : cg == 0; }
+__device__ __forceinline__ bool mass_owner(int mt, int cg) { return mt % C::CG == cg; }
 
 template <class C, int QG>
 __global__ __launch_bounds__(kThreads)
@@ -88,8 +87,8 @@ void totals_kernel(KArgs a, const bf16raw *X, const bf16raw *Y, const bf16raw *O
 
     const int seg = blockIdx.x, bh = blockIdx.y, head = bh % a.H;
     const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, ln = lane & 31, h = lane >> 5;
-    const int rg = w % kRowGroups, cg = w / kRowGroups;
-    const int r_own = rg * C::LRW, c_own = cg * (C::D / 2);
+    const int rg = w % C::RG, cg = w / C::RG;
+    const int r_own = rg * C::LRW, c_own = cg * C::DW;
     const size_t base = static_cast<size_t>(bh) * a.N * C::D;
     X += base; Y += base;
     if (QG) { Oin += base; den_in += static_cast<size_t>(bh) * a.N; }
@@ -191,8 +190,8 @@ struct StreamLds {
     static constexpr int endA = phw + kTile * C::PS * 2;
     // phase B (reduction over the four bucket-row groups) reuses the same bytes
     static constexpr int RS = C::D + 4;                                 // fp32 row stride: D numerators, 1 normaliser part
-    static constexpr int red = area;                                    // [4][32][RS] fp32
-    static constexpr int endB = red + kRowGroups * kTile * RS * 4;
+    static constexpr int red = area;                                    // [RG][32][RS] fp32
+    static constexpr int endB = red + C::RG * kTile * RS * 4;
     static constexpr int total = endA > endB ? endA : endB;
     static_assert(total <= 160 * 1024, "LDS budget");
 };
@@ -217,8 +216,8 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
     constexpr bool kReverse = (MODE == kGradV);
     const int seg = blockIdx.x, bh = blockIdx.y, head = bh % a.H;
     const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, ln = lane & 31, h = lane >> 5;
-    const int rg = w % kRowGroups, cg = w / kRowGroups;
-    const int r_own = rg * C::LRW, c_own = cg * (C::D / 2);
+    const int rg = w % C::RG, cg = w / C::RG;
+    const int r_own = rg * C::LRW, c_own = cg * C::DW;
     const bool intra = a.causal;                      // the tile's own keys take part
 
     const size_t base = static_cast<size_t>(bh) * a.N * C::D;
@@ -240,8 +239,8 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
                 Sacc[mt][nt][v] = st[state_b<C>(r_own + 32 * mt + acc_row(v, h), c_own + 32 * nt + ln)];
         }
         // the bucket masses of tile mt are carried by column group mt % 2 (balances the vector work)
-        macc[mt] = (MODE == kForward && (mt & 1) == cg && h == 0) ? st[state_a<C>(r_own + 32 * mt + ln)] : 0.f;
-        if (MODE == kForward && (mt & 1) == cg && h == 0) mass[r_own + 32 * mt + il(ln)] = macc[mt];
+        macc[mt] = (MODE == kForward && mass_owner<C>(mt, cg) && h == 0) ? st[state_a<C>(r_own + 32 * mt + ln)] : 0.f;
+        if (MODE == kForward && mass_owner<C>(mt, cg) && h == 0) mass[r_own + 32 * mt + il(ln)] = macc[mt];
     }
 
     const int64_t t_begin = seg * a.seg_len;
@@ -348,7 +347,7 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
 #pragma unroll
                 for (int mt = 0; mt < C::MT; ++mt) {
                     const u32x4 ap = lds_tr_plain<true>(phw, C::PS, 16 * s, r_own + 32 * mt, ln, h);
-                    if (MODE == kForward && (mt & 1) == cg) macc[mt] += sum8(ap);
+                    if (MODE == kForward && mass_owner<C>(mt, cg)) macc[mt] += sum8(ap);
 #pragma unroll
                     for (int nt = 0; nt < C::NTW; ++nt) Sacc[mt][nt] = mma(ap, by[nt], Sacc[mt][nt]);
                     RACE_SCHED_FENCE();
@@ -361,7 +360,7 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
         __syncthreads();        // every wavefront is done with the tiles of this step
         RACE_PHASE(6)
 
-        // ---- reduction over the four bucket-row groups: partial read-outs through LDS, 16 bytes per store
+        // ---- reduction over the bucket-row groups: partial read-outs through LDS, 16 bytes per store
         //      (a lane holds four consecutive columns of its token in registers 4k .. 4k+3)
         const int rbase = opaque((rg * kTile + ln) * S::RS + c_own + 4 * h);
 #pragma unroll
@@ -377,7 +376,7 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
             // masses after this tile, for the next tile's read-out
 #pragma unroll
             for (int mt = 0; mt < C::MT; ++mt) {
-                if ((mt & 1) != cg) continue;
+                if (!mass_owner<C>(mt, cg)) continue;
                 const float tot = macc[mt] + __shfl_xor(macc[mt], 32, 64);
                 if (h == 0) mass[r_own + 32 * mt + il(ln)] = tot;
             }
@@ -395,14 +394,19 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
             for (int c = 0; c < NP; ++c) acc[c][0] = acc[c][1] = acc[c][2] = acc[c][3] = 0.f;
             float e = 0.f;
 #pragma unroll
-            for (int gg = 0; gg < kRowGroups; ++gg) {
+            for (int gg = 0; gg < 4; ++gg) {              // row groups (at most four) and the four reader wavefronts
                 const float *src = red + (gg * kTile + tok) * S::RS;
+                if (gg < C::RG) {
 #pragma unroll
-                for (int c = 0; c < NP; ++c) {
-                    const float4 p4 = *reinterpret_cast<const float4 *>(src + c0 + 64 * c);
-                    acc[c][0] += p4.x; acc[c][1] += p4.y; acc[c][2] += p4.z; acc[c][3] += p4.w;
+                    for (int c = 0; c < NP; ++c) {
+                        const float4 p4 = *reinterpret_cast<const float4 *>(src + c0 + 64 * c);
+                        acc[c][0] += p4.x; acc[c][1] += p4.y; acc[c][2] += p4.z; acc[c][3] += p4.w;
+                    }
                 }
-                if (MODE == kForward) e += src[C::D] + (dnp[gg * 64 + tok] + dnp[gg * 64 + 32 + tok]);
+                if (MODE == kForward) {
+                    const float dpart = dnp[gg * 64 + tok] + dnp[gg * 64 + 32 + tok];
+                    e += gg < C::RG ? src[C::D] + dpart : dpart;
+                }
             }
             if (tok < nvalid) {
                 const float scale = (MODE == kForward) ? (e > 0.f ? 1.0f / e : 0.f) : 1.0f;   // e = 0: hard hash, empty buckets

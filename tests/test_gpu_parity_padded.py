@@ -16,7 +16,9 @@ pytestmark = pytest.mark.gpu
 
 GRID = [(2, 2, 128), (3, 3, 128), (4, 4, 128), (3, 5, 64), (1, 1, 128), (4, 16, 128),
         # beyond four hyperplanes: the padded instantiations of the L = 8, P = 6 shape
-        (5, 5, 128), (6, 4, 128), (5, 8, 128), (6, 8, 64), (5, 3, 64)]
+        (5, 5, 128), (6, 4, 128), (5, 8, 128), (6, 8, 64), (5, 3, 64),
+        # the 64- and 128-row shapes (two and four wavefronts carry the statistics in the gradient kernels)
+        (4, 3, 128), (4, 8, 128), (3, 7, 128), (4, 5, 128)]
 
 
 @pytest.mark.parametrize("P,L,d", GRID)
