@@ -73,7 +73,7 @@ template <class C>
 __device__ __forceinline__ bool mass_owner(int mt, int cg) { return mt % C::CG == cg; }
 
 template <class C, int QG>
-__global__ __launch_bounds__(kThreads)
+__global__ __launch_bounds__(kThreads, C::STREAM_WAVES_PER_SIMD)
 void totals_kernel(KArgs a, const bf16raw *X, const bf16raw *Y, const bf16raw *Oin, const float *den_in)
 {
     using S = TotalsLds<C>;
@@ -197,7 +197,7 @@ struct StreamLds {
 };
 
 template <class C, int MODE>
-__global__ __launch_bounds__(kThreads)
+__global__ __launch_bounds__(kThreads, C::STREAM_WAVES_PER_SIMD)
 void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw *Y, const bf16raw *Oin,
                    const float *den_in, bf16raw *Out, float *den_out)
 {
