@@ -66,7 +66,9 @@ struct GradCfg {
     // roles double up on the last wavefronts.
     static constexpr int AS = (C::PHI >= 2 && NGW * C::TPL * 2 + NGW + 1 <= kWaves) ? 2 : 1;     // shares hold pairs of indices
     static constexpr int NW = NGW * C::TPL * AS;                        // writer wavefronts
-    static constexpr int RJ = (NW + NGW * C::TPL + 1 <= kWaves) ? C::TPL : 1;
+    // (where every wavefront carries statistics, a wavefront is kept free for the in-tile term; where some do not,
+    // it doubles up on a reader: measured faster each way)
+    static constexpr int RJ = (NW + NGW * C::TPL + (NRW < kWaves ? 0 : 1) <= kWaves) ? C::TPL : 1;
     static constexpr bool DISJ = NW + NGW * RJ + 1 <= kWaves;
     static constexpr int RD0 = DISJ ? NW : kWaves - NGW * RJ;           // first reader wavefront
     static constexpr int NR = NGW * RJ;                                 // reader wavefronts
