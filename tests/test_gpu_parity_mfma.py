@@ -177,6 +177,12 @@ def test_config5_causal_12m_tokens_sampled():
     _long_context(synth.C5, 16384)
 
 
+@pytest.mark.parametrize("w", [synth.G22, synth.G44], ids=lambda w: w.name)
+def test_paper_grid_1m_tokens_sampled(w):
+    # the paper's own scaling grid at N = 2^20, on the padded 64-row shape, in the benchmark's launch configuration
+    _long_context(w, 16384)
+
+
 def test_beta_cotangent_headline_shape():
     from parity_util import check_dbeta
     check_dbeta(Workload("m-beta-1", 1, 2, 1000, 128, 8, 6, 8.0, True, "bf16", normalize_qk=True, chunk=256))
