@@ -78,7 +78,8 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         sys.stderr.write("bench.py: this build runs on one GPU; --gpus %d is not supported "
-                         "(the path has no collectives; see the sharding note in DESIGN.md)\n" % args.gpus)
+                         "(the path has no collectives: a sequence would shard by batch and heads, or along N with the bucket "
+                         "statistics exchanged once per segment scan)\n" % args.gpus)
         return 2
 
     import numpy as np
