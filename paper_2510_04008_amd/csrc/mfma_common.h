@@ -63,9 +63,11 @@ struct Cfg {
     static constexpr int NT = D / 32;                   // 32-column tiles of the head dimension
     static constexpr int NTW = NT / CG;                 // column tiles per wavefront
     static constexpr int DW = D / CG;                   // columns per wavefront
-    // wavefronts per SIMD the stream and totals kernels are compiled for: shapes whose statistics need at most 32
-    // registers per lane leave room for a second workgroup on the CU (its phases interleave with the first one's)
-    static constexpr int STREAM_WAVES_PER_SIMD = LR * D <= 16384 ? 4 : 2;
+    // wavefronts per SIMD the stream and totals kernels are compiled for: shapes with at most two accumulator
+    // tiles of statistics and one column tile per wavefront fit 128 registers and leave room for a second workgroup
+    // on the CU, whose phases interleave with the first one's (measured: with two column tiles the kernels spill
+    // at 128 registers and lose more than the second workgroup gains)
+    static constexpr int STREAM_WAVES_PER_SIMD = (MT * NTW <= 2 && NTW == 1) ? 4 : 2;
     static constexpr int LRG = LR / kWaves;             // bucket rows per wavefront (grad kernel)
     static constexpr int MTG = LRG / 32;                // 32-row tiles per wavefront (grad kernel)
     static constexpr int JSTEP = 4 / NG;                // wavefronts that share one projection group
