@@ -274,7 +274,7 @@ __device__ __forceinline__ void store_cotangent(const CotChunks<C, ROWS> &r, bf1
     for (int k = 0; k < RowChunks<C, ROWS>::N; ++k) {
         const int c = tid + k * kThreads, row = c / C::CPR, ch = c % C::CPR;
         // rows past the end of the tile hold a copy of the last real row: they get zero cotangents
-        const float inv = (row < nvalid && r.den[k] > 0.f) ? 1.0f / (r.den[k] * static_cast<float>(L_real)) : 0.f;
+        const float inv = (row < nvalid && r.den[k] > 0.f) ? __builtin_amdgcn_rcpf(r.den[k] * static_cast<float>(L_real)) : 0.f;
         const uint32_t gw[4] = {r.g.v[k].x, r.g.v[k].y, r.g.v[k].z, r.g.v[k].w};
         const uint32_t ow[4] = {r.o.v[k].x, r.o.v[k].y, r.o.v[k].z, r.o.v[k].w};
         uint32_t out[4];

@@ -264,6 +264,7 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
     };
     if (ntiles > 0) fetch(0);
 
+    const float inv_tables = 1.0f / static_cast<float>(a.L_real);
     RACE_PHASE_DECL
     for (int it = 0; it < ntiles; ++it) {
         const int64_t t0 = tile_t0(it);
@@ -409,13 +410,13 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
                 }
             }
             if (tok < nvalid) {
-                const float scale = (MODE == kForward) ? (e > 0.f ? 1.0f / e : 0.f) : 1.0f;   // e = 0: hard hash, empty buckets
+                const float scale = (MODE == kForward) ? (e > 0.f ? __builtin_amdgcn_rcpf(e) : 0.f) : 1.0f;   // e = 0: hard hash, empty buckets
                 bf16raw *dst = Out + (t0 + tok) * C::D + c0;
 #pragma unroll
                 for (int c = 0; c < NP; ++c)
                     *reinterpret_cast<u32x2 *>(dst + 64 * c) =
                         u32x2{pack2(acc[c][0] * scale, acc[c][1] * scale), pack2(acc[c][2] * scale, acc[c][3] * scale)};
-                if (MODE == kForward && (tid & 15) == 0) den_out[t0 + tok] = e / static_cast<float>(a.L_real);
+                if (MODE == kForward && (tid & 15) == 0) den_out[t0 + tok] = e * inv_tables;
             }
         }
         RACE_PHASE(9)
