@@ -14,7 +14,9 @@ differences; nothing here is "parity unpinned".
 
 Readings of the paper taken here (each is listed with its reason in the design notes):
   * beta is the single temperature of Algorithm 1/2 ("sharpening" of the interface).
-  * No normalisation of Q, K and no 1/sqrt(d) scaling inside the layer (Algorithm 1, step 4).
+  * No normalisation of Q, K and no 1/sqrt(d) scaling inside the layer (Algorithm 1, step 4); the
+    unit-norm setting of the analysis (Appendix, setup of the proof of Theorem 1) is an option of the
+    interface, stated here as unit_rows() in front of the layer and unit_rows_vjp() behind its backward pass.
   * Corner r of the hypercube has v_{r,t} = +1 iff bit t of r is set; t = 0 is the
     least significant bit and belongs to row l*P+0 of W.
   * The causal variant is inclusive (j <= i): Algorithm 2 adds key/value t to the
@@ -379,6 +381,32 @@ def finite_difference(Q, K, V, W, beta, L, P, causal, dO, which: str, index, h: 
     plus[which][index] += h
     minus[which][index] -= h
     return (loss(plus["Q"], plus["K"], plus["V"]) - loss(minus["Q"], minus["K"], minus["V"])) / (2 * h)
+
+
+# ----------------------------------------------------------------------------------
+# Optional unit-norm queries and keys (Appendix, setup of the proof of Theorem 1: |Q_i| = |K_j| = 1)
+# ----------------------------------------------------------------------------------
+# The interface can divide every row of Q and K by its Euclidean norm before Algorithm 1/2 sees it.
+# Rows shorter than UNIT_EPS are divided by UNIT_EPS instead (a zero row stays zero).
+
+UNIT_EPS = 1e-12
+
+
+def unit_rows(X: np.ndarray) -> np.ndarray:
+    """x / max(|x|, UNIT_EPS) for every row of X (..., d)."""
+    n = np.maximum(np.sqrt((X * X).sum(axis=-1, keepdims=True)), UNIT_EPS)
+    return X / n
+
+
+def unit_rows_vjp(X: np.ndarray, dXhat: np.ndarray) -> np.ndarray:
+    """Cotangent of X given the cotangent of unit_rows(X): the Jacobian of x -> x / |x| is
+    (I - xhat xhat^T) / |x|, the projection onto the tangent space of the sphere, scaled; a row
+    below UNIT_EPS was only divided by a constant."""
+    norm = np.sqrt((X * X).sum(axis=-1, keepdims=True))
+    n = np.maximum(norm, UNIT_EPS)
+    xhat = X / n
+    radial = (xhat * dXhat).sum(axis=-1, keepdims=True)
+    return np.where(norm >= UNIT_EPS, (dXhat - xhat * radial) / n, dXhat / n)
 
 
 # ----------------------------------------------------------------------------------
