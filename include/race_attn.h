@@ -22,7 +22,10 @@
  *   - Corner r of the hypercube has v_{r,t} = +1 iff bit t of r is set (t = 0 is the least
  *     significant bit and belongs to row l*P+0 of W).
  *   - sharpening is the temperature beta of Algorithms 1/2.  Q and K are used as given:
- *     no normalisation and no 1/sqrt(d) scaling happens inside the layer.
+ *     no 1/sqrt(d) scaling happens inside the layer, and no normalisation unless desc->unit_qk
+ *     asks for it.  With unit_qk = 1 every entry point that hashes rows of Q or K (passes, taps,
+ *     state_init, step) uses x / max(|x|, 1e-12) in place of the row x, in fp32 from the stored
+ *     elements; the backward passes carry the chain rule through that map, (I - xhat xhat^T) / |x|.
  *     beta = +infinity selects the hard hash h(x) = sign(W x) that Section 3.3 starts from
  *     (bit t of the bucket is [<w_t, x> >= 0]; counters instead of soft masses), for inference:
  *     the forward pass, the taps and incremental decoding accept it, the backward passes return
@@ -72,6 +75,10 @@ typedef struct {
     int32_t dtype;    /* race_dtype_t of Q, K, V, O, dO, dQ, dK, dV                            */
     int64_t chunk;    /* tokens per scan segment: the sequence is cut into segments whose
                          bucket statistics are combined by a prefix scan; 0 = choose           */
+    int32_t unit_qk;  /* 0: Q and K enter the projection as given (Algorithm 1, step 4);
+                         1: every row of Q and K is first divided by its Euclidean norm, the
+                         setting |Q_i| = |K_j| = 1 of Theorem 1's proof (Appendix, "Setup and
+                         assumptions"); dQ and dK are then the cotangents of the rows as given  */
 } race_attn_desc_t;
 
 /* Bytes of device workspace that race_attn_fwd / race_attn_bwd / race_attn_debug_buckets need

@@ -20,7 +20,8 @@ class RaceAttnDesc(ctypes.Structure):
     """race_attn_desc_t"""
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("N", ctypes.c_int64), ("d", ctypes.c_int32),
                 ("L", ctypes.c_int32), ("P", ctypes.c_int32), ("sharpening", ctypes.c_float),
-                ("causal", ctypes.c_int32), ("dtype", ctypes.c_int32), ("chunk", ctypes.c_int64)]
+                ("causal", ctypes.c_int32), ("dtype", ctypes.c_int32), ("chunk", ctypes.c_int64),
+                ("unit_qk", ctypes.c_int32)]
 
 
 class RaceAttnError(RuntimeError):
@@ -88,8 +89,9 @@ def lib() -> ctypes.CDLL:
 
 
 def make_desc(B: int, H: int, N: int, d: int, L: int, P: int, sharpening: float, causal: bool,
-              dtype: int, chunk: int = 0) -> RaceAttnDesc:
-    return RaceAttnDesc(B, H, N, d, L, P, float(sharpening), int(bool(causal)), int(dtype), int(chunk))
+              dtype: int, chunk: int = 0, unit_qk: bool = False) -> RaceAttnDesc:
+    return RaceAttnDesc(B, H, N, d, L, P, float(sharpening), int(bool(causal)), int(dtype), int(chunk),
+                        int(bool(unit_qk)))
 
 
 def _seeds(seeds: Sequence[int]):

@@ -22,6 +22,7 @@ struct Plan {
     int64_t N;
     float beta;
     int causal;
+    int unit_qk;        // rows of Q and K are divided by their norms before the projection
     int dtype;
     int family;
     // The sequence is cut into nseg segments of seg_len tokens (the last may be short).  One

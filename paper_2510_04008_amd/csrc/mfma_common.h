@@ -246,6 +246,31 @@ __device__ __forceinline__ void store_rows(const RowChunks<C, ROWS> &r, bf16raw 
     }
 }
 
+// Unit-norm option (the setting |Q_i| = |K_j| = 1 of Theorem 1's proof): scale[row] = 1 / max(|x_row|, 1e-12) for the
+// rows held in r, from the fp32 sum of squares of the stored elements.  (Rows past the end of a tile hold a copy of
+// the last real row.)
+template <class C, int ROWS>
+__device__ __forceinline__ void store_row_scales(const RowChunks<C, ROWS> &r, float *scale)
+{
+    const int tid = opaque(static_cast<int>(threadIdx.x));
+#pragma unroll
+    for (int k = 0; k < RowChunks<C, ROWS>::N; ++k) {
+        const int c = tid + k * kThreads, row = c / C::CPR, ch = c % C::CPR;
+        const uint32_t xw[4] = {r.v[k].x, r.v[k].y, r.v[k].z, r.v[k].w};
+        float ss = 0.f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float x0 = bf_lo(xw[e]), x1 = bf_hi(xw[e]);
+            ss = fmaf(x0, x0, ss);
+            ss = fmaf(x1, x1, ss);
+        }
+        // the CPR threads of one row are consecutive lanes
+#pragma unroll
+        for (int m = C::CPR / 2; m >= 1; m >>= 1) ss += __shfl_xor(ss, m, 64);
+        if (ch == 0 && row < ROWS) scale[row] = __builtin_amdgcn_rsqf(fmaxf(ss, 1e-24f));
+    }
+}
+
 // Read-out cotangent rows: gn = dO / e (e = L * Den) as bf16 rows, ge[row] = -(dO . O) / e as fp32.
 template <class C, int ROWS>
 struct CotChunks {
@@ -300,8 +325,10 @@ __device__ __forceinline__ void store_cotangent(const CotChunks<C, ROWS> &r, bf1
 // z^T (32 projection rows of group g) x (32 tokens) = Wg . X^T, contraction over d (Algorithm 1, step 4:
 // the argument of tanh).  Lane (n, h) ends up with the projections of token n for the TPL tables
 // {g*TPG + h*TPL + j}: the host stores W's rows in that order (see pack_projection()).
+// scale != null: the projections of token n are multiplied by scale[n] (W (x / |x|) = (W x) / |x|).
 template <class C>
-__device__ __forceinline__ f32x16 project(const bf16raw *wp, const bf16raw *x, int g, int ln, int h)
+__device__ __forceinline__ f32x16 project(const bf16raw *wp, const bf16raw *x, int g, int ln, int h,
+                                          const float *scale = nullptr)
 {
     // two accumulators halve the chain of dependent MFMAs
     f32x16 z0 = {0}, z1 = {0};
@@ -310,7 +337,9 @@ __device__ __forceinline__ f32x16 project(const bf16raw *wp, const bf16raw *x, i
         z0 = mma(lds128(wp + (g * 32 + ln) * C::XS + 16 * s + 8 * h), lds128(x + ln * C::XS + 16 * s + 8 * h), z0);
         z1 = mma(lds128(wp + (g * 32 + ln) * C::XS + 16 * s + 16 + 8 * h), lds128(x + ln * C::XS + 16 * s + 16 + 8 * h), z1);
     }
-    return z0 + z1;
+    f32x16 z = z0 + z1;
+    if (scale) z = z * scale[ln];
+    return z;
 }
 // projection t of the lane's j-th table inside the accumulator
 template <class C>

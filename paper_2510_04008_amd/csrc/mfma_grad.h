@@ -77,7 +77,8 @@ struct GradCfg {
     static_assert(NW <= kWaves && RD0 + NR <= kWaves, "production roles must fit the wavefronts");
 };
 
-template <class C>
+// UNIT: the unit-norm option's extras (row scales, parts of z . dz, and z next to the per-bit masses).
+template <class C, bool UNIT>
 struct GradLds {
     using G = GradCfg<C>;
     static constexpr int wp = 0;                                        // [LPP][XS] bf16
@@ -85,9 +86,12 @@ struct GradLds {
     static constexpr int dz = wp + C::LPP * C::XS * 2;                  // [32][DZS] bf16
     static constexpr int sr = dz + kTile * DZS * 2;                     // [32] fp32 extra column of reader-Y
     static constexpr int sw = sr + kTile * 4;                           // [32] fp32 extra column of writer-Y
-    static constexpr int PMS = 4 * C::PP + 4;                           // floats per (table, token): p, q, sech^2, tanh, each padded
-                                                                        // to PP; + 4 keeps 16-byte reads of 16 tokens on distinct banks
-    static constexpr int pm = (sw + kTile * 4 + 15) & ~15;              // [TABLES][32][PMS] fp32: per-bit masses of the reader
+    static constexpr int nrm = sw + kTile * 4;                          // [2][32] fp32: 1 / |x| of the reader and writer rows (unit-norm option)
+    static constexpr int rad = nrm + (UNIT ? 2 * kTile * 4 : 0);        // [kWaves][32] fp32: per-wavefront parts of z . dz per token (same option)
+    static constexpr int PMS = UNIT ? 5 * C::PP + (C::PP == 8 ? 4 : 8)  // floats per (table, token): p, q, sech^2, tanh (, z), each padded
+                                    : 4 * C::PP + 4;                    // to PP; the tail makes PMS / 4 odd, which keeps 16-byte reads of
+                                                                        // 16 tokens on distinct banks
+    static constexpr int pm = (rad + (UNIT ? kWaves * kTile * 4 : 0) + 15) & ~15;              // [TABLES][32][PMS] fp32: per-bit masses of the reader
     static constexpr int PMT = G::TABLES < C::L ? G::TABLES : C::L;     // tables of the workgroup that exist
     static constexpr int part = pm + PMT * kTile * PMS * 4;             // [kWaves][32][8] fp32: partial (m, G_t) of table shares
     static constexpr int yr = part + (G::WPT > 1 ? kWaves * kTile * 8 * 4 : 0);   // [32][XS] reader-Y rows, pair-interleaved columns
@@ -102,18 +106,20 @@ struct GradLds {
     static_assert(total <= 160 * 1024, "LDS budget");
 };
 
-template <class C, int SIDE>
+template <class C, int SIDE, bool UNIT>
 __global__ __launch_bounds__(kThreads)
 void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, const bf16raw *O,
                  const float *den, const bf16raw *dO, bf16raw *dZ, bf16raw *dX)
 {
-    using S = GradLds<C>;
+    using S = GradLds<C, UNIT>;
     using G = GradCfg<C>;
     extern __shared__ __attribute__((aligned(256))) unsigned char lds[];
     bf16raw *wp = reinterpret_cast<bf16raw *>(lds + S::wp);
     bf16raw *dz = reinterpret_cast<bf16raw *>(lds + S::dz);
     float *sr = reinterpret_cast<float *>(lds + S::sr);
     float *sw = reinterpret_cast<float *>(lds + S::sw);
+    float *nrm = reinterpret_cast<float *>(lds + S::nrm);
+    float *rad = reinterpret_cast<float *>(lds + S::rad);
     float *pm = reinterpret_cast<float *>(lds + S::pm);
     bf16raw *yr = reinterpret_cast<bf16raw *>(lds + S::yr);
     bf16raw *xr = reinterpret_cast<bf16raw *>(lds + S::xr);
@@ -199,6 +205,10 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
         // ---- registers -> LDS
         store_rows<C, kTile>(pre_r, xr, nvalid);
         if (intra) store_rows<C, kTile>(pre_w, xw, nvalid);
+        if (UNIT) {
+            store_row_scales<C, kTile>(pre_r, nrm);
+            if (intra) store_row_scales<C, kTile>(pre_w, nrm + kTile);
+        }
         if (SIDE == 0) {
             store_cotangent<C, kTile, C::XS, true>(pre_c, yr, sr, a.L_real, nvalid);
             if (intra) store_rows<C, kTile, C::YS, true>(pre_v, yw, nvalid);
@@ -224,20 +234,23 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
         if (intra && w < G::NW) {
             const int pg = w % G::NGW, pj = (w / G::NGW) % C::TPL, as = w / (G::NGW * C::TPL);
             constexpr int kShare = (1 << C::PHI) / G::AS;
-            const f32x16 zw = project<C>(wp, xw, th * G::NGW + pg, ln, h);
+            const f32x16 zw = project<C>(wp, xw, th * G::NGW + pg, ln, h, UNIT ? nrm + kTile : nullptr);
             write_assignments<C, C::PST>(zw, th * G::NGW + pg, ln, h, a.soft(), ln < nvalid, phw, pj, C::TPL, as * kShare,
                                  (as + 1) * kShare);
         }
         if (w >= G::RD0 && w < G::RD0 + G::NR) {
             const int pg = (w - G::RD0) % G::NGW, rj = (w - G::RD0) / G::NGW;
-            const f32x16 zr = project<C>(wp, xr, th * G::NGW + pg, ln, h);
+            const f32x16 zr = project<C>(wp, xr, th * G::NGW + pg, ln, h, UNIT ? nrm : nullptr);
 #pragma unroll
             for (int j = 0; j < C::TPL; ++j) {
                 if ((th * G::NGW + pg) * C::TPG + h * C::TPL + j >= C::L) break;
                 if (j % G::RJ != rj) continue;
-                float p[C::PP], q[C::PP], s2[C::PP], u[C::PP];
+                float p[C::PP], q[C::PP], s2[C::PP], u[C::PP], zz[C::PP];
 #pragma unroll
-                for (int t = 0; t < C::PP; ++t) p[t] = q[t] = s2[t] = u[t] = 0.f;
+                for (int t = 0; t < C::PP; ++t) {
+                    p[t] = q[t] = s2[t] = u[t] = 0.f;
+                    zz[t] = t < C::P ? zr[zslot<C>(j, t)] : 0.f;
+                }
                 float *dst = pm + ((pg * C::TPG + h * C::TPL + j) * kTile + ln) * S::PMS;
                 // (a padding table has zero statistics and zero cotangents: any finite masses will do)
                 if (!C::PAD || (th * G::NGW + pg) * C::TPG + h * C::TPL + j < a.L_real) bit_masses<C>(zr, j, a.soft(), p, q, s2, u);
@@ -247,6 +260,7 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
                     *reinterpret_cast<float4 *>(dst + C::PP + t) = float4{q[t], q[t + 1], q[t + 2], q[t + 3]};
                     *reinterpret_cast<float4 *>(dst + 2 * C::PP + t) = float4{s2[t], s2[t + 1], s2[t + 2], s2[t + 3]};
                     *reinterpret_cast<float4 *>(dst + 3 * C::PP + t) = float4{u[t], u[t + 1], u[t + 2], u[t + 3]};
+                    if (UNIT) *reinterpret_cast<float4 *>(dst + 4 * C::PP + t) = float4{zz[t], zz[t + 1], zz[t + 2], zz[t + 3]};
                 }
             }
         }
@@ -407,7 +421,12 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
 
         // ---- finish per (token, table): du_t = +-2 beta (small_t (m - G_t) - big_t G_t),  dz_t = du_t (1 - tanh^2 z_t);
         //      lane half h' takes the padded projection slots 4h' .. 4h'+3
+        // unit-norm option: dz is the cotangent of W xhat, so the reader's row gets dx = (g - xhat (xhat . g)) / |x| with
+        // g = W^T dz and xhat . g = z . dz; dz is scaled by 1 / |x| here and this lane's share of z . dz is summed from the
+        // bf16 values the matrix product below will see (which keeps dx orthogonal to x to fp32 accuracy)
+        float radial = 0.f;
         if (has_rows && ro == 0) {
+            const float rs = UNIT ? nrm[ln] : 1.f;
 #pragma unroll
             for (int ti = 0; ti < G::TWW; ++ti) {
                 if (4 * h >= C::PP) break;
@@ -437,14 +456,26 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
                     const float small = minor1 ? pp[e] : qq[e], big = minor1 ? qq[e] : pp[e];
                     const float half = small * (rec[ti][0] - Gt) - big * Gt;
                     const float du = minor1 ? -2.f * half : 2.f * half;         // cotangent of u_t up to the factor beta
-                    dzv[e] = a.beta * du * s2[e];                               // padded slots: p = q = s2 = 0
+                    dzv[e] = a.beta * du * s2[e] * rs;                          // padded slots: p = q = s2 = 0
                     dbeta_acc = fmaf(du, uu[e], dbeta_acc);                     // ... and tanh = 0
                 }
                 // slot 4c.. of the lane-half hh's j-th table is projection row 8 (slots-per-table/4 * j + c) + 4 hh of its group
                 const int gl = tl / C::TPG, tg = tl % C::TPG, hh = tg / C::TPL, j = tg % C::TPL;
                 const int col = gl * 32 + 8 * ((C::PP / 4) * j + h) + 4 * hh;
-                *reinterpret_cast<u32x2 *>(dz + ln * S::DZS + col) = u32x2{pack2(dzv[0], dzv[1]), pack2(dzv[2], dzv[3])};
+                const u32x2 dzw = {pack2(dzv[0], dzv[1]), pack2(dzv[2], dzv[3])};
+                *reinterpret_cast<u32x2 *>(dz + ln * S::DZS + col) = dzw;
+                if (UNIT) {
+                    const float4 z4 = *reinterpret_cast<const float4 *>(src + 4 * C::PP);
+                    radial = fmaf(z4.x, bf_lo(dzw.x), radial);
+                    radial = fmaf(z4.y, bf_hi(dzw.x), radial);
+                    radial = fmaf(z4.z, bf_lo(dzw.y), radial);
+                    radial = fmaf(z4.w, bf_hi(dzw.y), radial);
+                }
             }
+        }
+        if (UNIT) {
+            radial += __shfl_xor(radial, 32, 64);
+            if (h == 0) rad[w * kTile + ln] = radial;
         }
         GRAD_PHASE(9)
         __syncthreads();
@@ -463,6 +494,20 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
 #pragma unroll
                 for (int s = 0; s < C::LPP / 16; ++s)
                     acc = mma(lds_tr_plain(wp, C::XS, 16 * s, 32 * nt, lno, ho), lds128(dz + lno * S::DZS + 16 * s + 8 * ho), acc);
+                if (UNIT) {
+                    float cp = 0.f;                              // (z . dz) / |x|^2 of token lno, parts in wavefront order
+#pragma unroll
+                    for (int i = 0; i < kWaves; ++i) cp += rad[i * kTile + lno];
+                    cp *= nrm[lno];
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const u32x2 xv = *reinterpret_cast<const u32x2 *>(xr + lno * C::XS + 32 * nt + 8 * k + 4 * ho);
+                        acc[4 * k] = fmaf(-cp, bf_lo(xv.x), acc[4 * k]);
+                        acc[4 * k + 1] = fmaf(-cp, bf_hi(xv.x), acc[4 * k + 1]);
+                        acc[4 * k + 2] = fmaf(-cp, bf_lo(xv.y), acc[4 * k + 2]);
+                        acc[4 * k + 3] = fmaf(-cp, bf_hi(xv.y), acc[4 * k + 3]);
+                    }
+                }
                 bf16raw *sg = stg + nt * kTile * S::SS;
 #pragma unroll
                 for (int k = 0; k < 4; ++k)
@@ -486,7 +531,9 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
         }
         GRAD_PHASE(12)
         // no barrier here: the next step's loads-to-LDS touch none of dz, pm, part or the staging tiles, and its
-        // production (which rewrites pm) comes after the next barrier
+        // production (which rewrites pm) comes after the next barrier -- except with the unit-norm option, where the
+        // dX wavefronts have just read the reader's rows and scales, which the next step's first stores overwrite
+        if (UNIT) __syncthreads();
     }
     // ---- cotangent of beta: lanes -> wavefront (shuffles) -> workgroup (LDS, wavefront order) -> one workspace slot
     {

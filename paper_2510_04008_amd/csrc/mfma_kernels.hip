@@ -64,7 +64,8 @@ struct TotalsLds {
     static constexpr int y = x + TT * C::XS * 2;                        // [64][YS] accumulated rows
     static constexpr int ph = y + TT * C::YS * 2;                       // [64][PST] assignments
     static constexpr int ge = ph + TT * C::PST * 2;                     // [64] fp32
-    static constexpr int total = ge + TT * 4;
+    static constexpr int nx = ge + TT * 4;                              // [64] fp32: 1 / |x| of the hashed rows (unit-norm option)
+    static constexpr int total = nx + TT * 4;
     static_assert(total <= 160 * 1024, "LDS budget");
 };
 
@@ -72,7 +73,7 @@ struct TotalsLds {
 template <class C>
 __device__ __forceinline__ bool mass_owner(int mt, int cg) { return mt % C::CG == cg; }
 
-template <class C, int QG>
+template <class C, int QG, bool UNIT>
 __global__ __launch_bounds__(kThreads, C::STREAM_WAVES_PER_SIMD)
 void totals_kernel(KArgs a, const bf16raw *X, const bf16raw *Y, const bf16raw *Oin, const float *den_in)
 {
@@ -84,6 +85,7 @@ void totals_kernel(KArgs a, const bf16raw *X, const bf16raw *Y, const bf16raw *O
     bf16raw *ys = reinterpret_cast<bf16raw *>(lds + S::y);
     bf16raw *ph = reinterpret_cast<bf16raw *>(lds + S::ph);
     float *ge_lds = reinterpret_cast<float *>(lds + S::ge);
+    float *nx = reinterpret_cast<float *>(lds + S::nx);
 
     const int seg = blockIdx.x, bh = blockIdx.y, head = bh % a.H;
     const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, ln = lane & 31, h = lane >> 5;
@@ -123,6 +125,7 @@ void totals_kernel(KArgs a, const bf16raw *X, const bf16raw *Y, const bf16raw *O
         const int64_t t0 = t_begin + static_cast<int64_t>(it) * TT;
         const int nvalid = step_nv(t0);
         store_rows<C, TT>(pre_x, xs, nvalid);
+        if (UNIT) store_row_scales<C, TT>(pre_x, nx);
         if (QG) store_cotangent<C, TT, C::YS>(pre_c, ys, ge_lds, a.L_real, nvalid);
         else store_rows<C, TT, C::YS>(pre_y, ys, nvalid);
         if (it + 1 < nsteps) fetch(it + 1);
@@ -130,7 +133,7 @@ void totals_kernel(KArgs a, const bf16raw *X, const bf16raw *Y, const bf16raw *O
         {
             // wavefront = (token half, projection group, share of the group's tables)
             const int half = w / 4, g = w % C::NG, jq = (w % 4) / C::NG;
-            const f32x16 z = project<C>(wp, xs + half * 32 * C::XS, g, ln, h);
+            const f32x16 z = project<C>(wp, xs + half * 32 * C::XS, g, ln, h, UNIT ? nx + half * 32 : nullptr);
             write_assignments<C, C::PST>(z, g, half * 32 + ln, h, a.soft(), half * 32 + ln < nvalid, ph, jq, C::JSTEP);
         }
         __syncthreads();
@@ -181,7 +184,8 @@ struct StreamLds {
     static constexpr int y = wp + C::LPP * C::XS * 2;                   // [32][YS] bf16: accumulated rows
     static constexpr int mass = y + kTile * C::YS * 2;                  // [LR] fp32: bucket masses A before this tile, pair-interleaved
     static constexpr int dnp = mass + C::LR * 4;                        // [4][2][32] fp32: mass read-outs per reader wavefront and lane half
-    static constexpr int area = (dnp + 4 * 2 * kTile * 4 + 255) & ~255; // start of the aliased area
+    static constexpr int nrm = dnp + 4 * 2 * kTile * 4;                 // [2][32] fp32: 1 / |x| of the reader and writer rows (unit-norm option)
+    static constexpr int area = (nrm + 2 * kTile * 4 + 255) & ~255;     // start of the aliased area
     // phase A (production, contraction)
     static constexpr int xr = area;                                     // [32][XS] reader rows
     static constexpr int xw = xr + kTile * C::XS * 2;                   // [32][XS] writer rows
@@ -196,7 +200,7 @@ struct StreamLds {
     static_assert(total <= 160 * 1024, "LDS budget");
 };
 
-template <class C, int MODE>
+template <class C, int MODE, bool UNIT>
 __global__ __launch_bounds__(kThreads, C::STREAM_WAVES_PER_SIMD)
 void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw *Y, const bf16raw *Oin,
                    const float *den_in, bf16raw *Out, float *den_out)
@@ -207,6 +211,7 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
     bf16raw *ytile = reinterpret_cast<bf16raw *>(lds + S::y);
     float *mass = reinterpret_cast<float *>(lds + S::mass);
     float *dnp = reinterpret_cast<float *>(lds + S::dnp);
+    float *nrm = reinterpret_cast<float *>(lds + S::nrm);
     bf16raw *xr = reinterpret_cast<bf16raw *>(lds + S::xr);
     bf16raw *xw = reinterpret_cast<bf16raw *>(lds + S::xw);
     bf16raw *phr = reinterpret_cast<bf16raw *>(lds + S::phr);
@@ -272,6 +277,10 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
 
         // ---- registers -> LDS, then start the next tile's loads
         store_rows<C, kTile>(pre_r, xr, nvalid);
+        if (UNIT) {
+            store_row_scales<C, kTile>(pre_r, nrm);
+            if (intra) store_row_scales<C, kTile>(pre_w, nrm + kTile);
+        }
         if (intra) {
             store_rows<C, kTile>(pre_w, xw, nvalid);
             if (MODE == kGradV) store_cotangent<C, kTile, C::YS>(pre_c, ytile, nullptr, a.L_real, nvalid);
@@ -285,12 +294,12 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
         {
             const int side = w / 4, g = w % C::NG, jq = (w % 4) / C::NG;
             if (side == 0) {
-                const f32x16 z = project<C>(wp, xr, g, ln, h);
+                const f32x16 z = project<C>(wp, xr, g, ln, h, UNIT ? nrm : nullptr);
                 const float dnl = write_assignments<C>(z, g, ln, h, a.soft(), true, phr, jq, C::JSTEP, 0, 1 << C::PHI,
                                                        MODE == kForward ? mass : nullptr);
                 if (MODE == kForward) dnp[w * 64 + lane] = dnl;       // this lane's tables' share of the normaliser
             } else if (intra) {
-                const f32x16 z = project<C>(wp, xw, g, ln, h);
+                const f32x16 z = project<C>(wp, xw, g, ln, h, UNIT ? nrm + kTile : nullptr);
                 write_assignments<C>(z, g, ln, h, a.soft(), ln < nvalid, phw, jq, C::JSTEP);
             }
         }
@@ -481,13 +490,14 @@ __global__ void bucket_tap_kernel(const float *state, int nseg, int BH, int L_re
 }
 
 // Debug tap: hard codes and phi from the production step itself.
-template <class C>
+template <class C, bool UNIT>
 __global__ __launch_bounds__(kThreads) void hash_tap_kernel(KArgs a, const bf16raw *X, uint8_t *codes, float *phi)
 {
     extern __shared__ __attribute__((aligned(256))) unsigned char lds[];
     bf16raw *wp = reinterpret_cast<bf16raw *>(lds);
     bf16raw *x = wp + C::LPP * C::XS;
     bf16raw *ph = x + kTile * C::XS;
+    float *nx = reinterpret_cast<float *>(ph + kTile * C::PS);      // [32] 1 / |x| (unit-norm option)
     const int bh = blockIdx.y, head = bh % a.H;
     const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, ln = lane & 31, h = lane >> 5;
     const int64_t t0 = static_cast<int64_t>(blockIdx.x) * kTile;
@@ -501,11 +511,12 @@ __global__ __launch_bounds__(kThreads) void hash_tap_kernel(KArgs a, const bf16r
         RowChunks<C, kTile> rows;
         fetch_rows<C, kTile>(X + static_cast<size_t>(bh) * a.N * C::D, t0, nvalid, rows);
         store_rows<C, kTile>(rows, x, nvalid);
+        if (UNIT) store_row_scales<C, kTile>(rows, nx);
     }
     __syncthreads();
     if (w < C::NG) {
         const int g = w;
-        const f32x16 z = project<C>(wp, x, g, ln, h);
+        const f32x16 z = project<C>(wp, x, g, ln, h, UNIT ? nx : nullptr);
         write_assignments<C>(z, g, ln, h, a.soft(), true, ph);
         if (ln < nvalid) {
 #pragma unroll
@@ -588,7 +599,7 @@ template <class C, int QG>
 hipError_t launch_totals(const Plan &p, KArgs a, const void *X, const void *Y, const void *O, const float *den_in,
                          hipStream_t st)
 {
-    auto kern = totals_kernel<C, QG>;
+    auto kern = p.unit_qk ? totals_kernel<C, QG, true> : totals_kernel<C, QG, false>;
     RACE_TRY(allow_lds(kern, TotalsLds<C>::total));
     ProfileScope prof(QG ? "stream_totals_qg" : "stream_totals_kv", st);
     hipLaunchKernelGGL(kern, dim3(p.nseg, p.BH), dim3(kThreads), TotalsLds<C>::total, st, a,
@@ -602,7 +613,7 @@ hipError_t launch_stream(const Plan &p, KArgs a, const void *Xr, const void *Xw,
                          const float *den_in, void *Out, float *den_out, hipStream_t st)
 {
     static const char *const names[] = {"stream_totals_kv", "stream_totals_qg", "stream_forward", "stream_grad_v"};
-    auto kern = stream_kernel<C, MODE>;
+    auto kern = p.unit_qk ? stream_kernel<C, MODE, true> : stream_kernel<C, MODE, false>;
     RACE_TRY(allow_lds(kern, StreamLds<C>::total));
     ProfileScope prof(names[MODE], st);
     hipLaunchKernelGGL(kern, dim3(p.nseg, p.BH), dim3(kThreads), StreamLds<C>::total, st, a,
@@ -635,11 +646,14 @@ template <class C, int SIDE>
 hipError_t launch_grad(const Plan &p, KArgs a, const void *Q, const void *K, const void *V, const void *O,
                        const float *den, const void *dO, void *dX, hipStream_t st)
 {
+    // (the chain rule of the unit-norm option is applied where dX is formed, which a table split moves to dz_matmul_kernel)
+    if (GradCfg<C>::TSPLIT > 1 && p.unit_qk) return hipErrorNotSupported;
     {
-        auto kern = grad_kernel<C, SIDE>;
-        RACE_TRY(allow_lds(kern, GradLds<C>::total));
+        auto kern = p.unit_qk ? grad_kernel<C, SIDE, true> : grad_kernel<C, SIDE, false>;
+        const int lds = p.unit_qk ? GradLds<C, true>::total : GradLds<C, false>::total;
+        RACE_TRY(allow_lds(kern, lds));
         ProfileScope prof(SIDE == 0 ? "grad_q" : "grad_k", st);
-        hipLaunchKernelGGL(kern, dim3(p.nseg, p.BH, GradCfg<C>::TSPLIT), dim3(kThreads), GradLds<C>::total, st, a,
+        hipLaunchKernelGGL(kern, dim3(p.nseg, p.BH, GradCfg<C>::TSPLIT), dim3(kThreads), lds, st, a,
                            static_cast<const bf16raw *>(Q), static_cast<const bf16raw *>(K),
                            static_cast<const bf16raw *>(V), static_cast<const bf16raw *>(O), den,
                            static_cast<const bf16raw *>(dO), a.dZ, static_cast<bf16raw *>(dX));
@@ -692,8 +706,8 @@ template <class C>
 hipError_t hash_t(const Plan &p, const void *X, uint8_t *codes, float *phi, char *ws, hipStream_t st)
 {
     KArgs a = make_kargs<C>(p, ws);
-    const size_t lds = (static_cast<size_t>(C::LPP) * C::XS + kTile * C::XS + kTile * C::PS) * 2;
-    auto kern = hash_tap_kernel<C>;
+    const size_t lds = (static_cast<size_t>(C::LPP) * C::XS + kTile * C::XS + kTile * C::PS) * 2 + kTile * 4;
+    auto kern = p.unit_qk ? hash_tap_kernel<C, true> : hash_tap_kernel<C, false>;
     RACE_TRY(allow_lds(kern, lds));
     hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>((p.N + kTile - 1) / kTile), p.BH), dim3(kThreads), lds, st, a,
                        static_cast<const bf16raw *>(X), codes, phi);

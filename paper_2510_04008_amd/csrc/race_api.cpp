@@ -174,6 +174,7 @@ race_status_t make_plan(const race_attn_desc_t *desc, Plan *pl)
     if (desc->causal != 0 && desc->causal != 1) return RACE_ERR_INVALID_ARG;
     if (desc->dtype != RACE_F32 && desc->dtype != RACE_BF16) return RACE_ERR_INVALID_ARG;
     if (desc->chunk < 0) return RACE_ERR_INVALID_ARG;
+    if (desc->unit_qk != 0 && desc->unit_qk != 1) return RACE_ERR_INVALID_ARG;
     if (desc->P > 8 || desc->d > 256 || desc->d % 8 != 0) return RACE_ERR_UNSUPPORTED;
     if (desc->L > 4096 || static_cast<int64_t>(desc->B) * desc->H > 65535) return RACE_ERR_UNSUPPORTED;
     if (static_cast<int64_t>(desc->B) * desc->H * desc->L > 65535) return RACE_ERR_UNSUPPORTED;
@@ -182,7 +183,7 @@ race_status_t make_plan(const race_attn_desc_t *desc, Plan *pl)
     Plan p{};
     p.B = desc->B; p.H = desc->H; p.BH = desc->B * desc->H; p.d = desc->d; p.L = desc->L; p.P = desc->P;
     p.R = 1 << desc->P; p.LP = p.L * p.P; p.LR = p.L * p.R; p.N = desc->N; p.beta = desc->sharpening;
-    p.causal = desc->causal; p.dtype = desc->dtype;
+    p.causal = desc->causal; p.dtype = desc->dtype; p.unit_qk = desc->unit_qk;
 
     const char *force = std::getenv("RACE_ATTN_FORCE_GENERIC");
     const bool forced = force && force[0] == '1';

@@ -33,6 +33,7 @@ __device__ __forceinline__ void store_elem(bf16_t *p, size_t i, float v)
 
 struct Args {
     int H, L, P, R, d, LP, nseg, causal, TT;
+    int unit;            // 1: rows of Q and K are divided by their Euclidean norms before the projection
     int64_t N, seg_len;
     float beta;
     const float *W;      // (H, L*P, d)
@@ -42,7 +43,7 @@ struct Args {
 // S     [R][d+1]   bucket statistics of this table (value sums | mass)
 // xa,xb [TT][d]    rows of the two hashed tensors
 // ya,yb [TT][d+1]  rows of the two accumulated tensors ([V | 1] and [dO/e | -(dO.O)/e])
-// ha,hb            per-token hash data of the two hashed tensors: s, p, q, u [TT][P] each, phi [TT][R]
+// ha,hb            per-token hash data of the two hashed tensors: s, p, q, u, z [TT][P] each, phi [TT][R], inv [TT]
 // dphi  [R], dz [P]
 struct Smem {
     float *S, *xa, *xb, *ya, *yb, *ha, *hb, *dphi, *dz;
@@ -54,21 +55,23 @@ struct Smem {
         xb = base;                base += a.TT * a.d;
         ya = base;                base += a.TT * d1;
         yb = base;                base += a.TT * d1;
-        ha = base;                base += a.TT * (4 * a.P + a.R);
-        hb = base;                base += a.TT * (4 * a.P + a.R);
+        ha = base;                base += a.TT * (5 * a.P + a.R + 1);
+        hb = base;                base += a.TT * (5 * a.P + a.R + 1);
         dphi = base;              base += a.R;
         dz = base;
     }
 };
 inline size_t smem_floats(int R, int d, int P, int TT)
 {
-    return static_cast<size_t>(R) * (d + 1) + 2 * TT * d + 2 * TT * (d + 1) + 2 * TT * (4 * P + R) + R + P;
+    return static_cast<size_t>(R) * (d + 1) + 2 * TT * d + 2 * TT * (d + 1) + 2 * TT * (5 * P + R + 1) + R + P;
 }
 
 struct HashView {
-    float *s, *p, *q, *u, *phi;     // s = 1 - tanh^2(z), p/q = mass on the +1/-1 side of each bit
+    float *s, *p, *q, *u, *z, *phi; // s = 1 - tanh^2(z), p/q = mass on the +1/-1 side of each bit, u = tanh z
+    float *inv;                     // 1 / max(|x|, floor) of the row (unit-norm option), else 1
     __device__ HashView(float *h, const Args &a)
-        : s(h), p(h + a.TT * a.P), q(h + 2 * a.TT * a.P), u(h + 3 * a.TT * a.P), phi(h + 4 * a.TT * a.P) {}
+        : s(h), p(h + a.TT * a.P), q(h + 2 * a.TT * a.P), u(h + 3 * a.TT * a.P), z(h + 4 * a.TT * a.P),
+          phi(h + 5 * a.TT * a.P), inv(h + 5 * a.TT * a.P + a.TT * a.R) {}
 };
 
 // rows [t0, t0+nt) of X -> xs[TT][d]
@@ -123,6 +126,11 @@ __device__ __forceinline__ float mass_ratio(float beta, float u)
     return expf(fmaxf(-2.0f * beta * fabsf(u), -1e30f));
 }
 
+// Unit-norm option (the setting of Theorem 1's proof, |Q_i| = |K_j| = 1): the factor that turns a row of squared
+// length ss into a unit vector; rows shorter than the floor are divided by the floor (a zero row stays zero).
+constexpr float kUnitFloor = 1e-12f;
+__device__ __forceinline__ float unit_scale(float ss) { return 1.0f / fmaxf(sqrtf(ss), kUnitFloor); }
+
 // softmax over corners exactly (the softmax denominator is prod_t 2 cosh(beta u_t)).
 __device__ void hash_rows(const Args &a, const float *Wl, const float *xs, int nt, HashView hv)
 {
@@ -130,11 +138,21 @@ __device__ void hash_rows(const Args &a, const float *Wl, const float *xs, int n
     const int sub = threadIdx.x & 3;
     for (int pair = threadIdx.x >> 2; pair < nt * a.P; pair += kThreads / 4) {
         const int tok = pair / a.P, t = pair - tok * a.P;
-        float z = 0.f;
-        for (int c = sub; c < a.d; c += 4) z = fmaf(Wl[t * a.d + c], xs[tok * a.d + c], z);
+        float z = 0.f, ss = 0.f;
+        for (int c = sub; c < a.d; c += 4) {
+            const float x = xs[tok * a.d + c];
+            z = fmaf(Wl[t * a.d + c], x, z);
+            ss = fmaf(x, x, ss);
+        }
         z += __shfl_xor(z, 1, 64);
         z += __shfl_xor(z, 2, 64);
+        ss += __shfl_xor(ss, 1, 64);
+        ss += __shfl_xor(ss, 2, 64);
         if (sub == 0) {
+            const float inv = a.unit ? unit_scale(ss) : 1.0f;
+            z *= inv;                                              // W (x / |x|)
+            if (t == 0) hv.inv[tok] = inv;
+            hv.z[pair] = z;
             const float u = tanhf(z);
             const float e = mass_ratio(a.beta, u);                  // in [0, 1]
             const float big = 1.0f / (1.0f + e), small = e / (1.0f + e);
@@ -184,6 +202,18 @@ __device__ void soft_hash_vjp(const Args &a, const float *phi, const float *sech
         dbeta_acc = fmaf(du, u[t], dbeta_acc);
     }
     __syncthreads();
+}
+
+// Chain rule through x -> x / |x| for one token and table: with g = W^T dz the cotangent of the unit vector,
+// dx = (g - xhat (xhat . g)) / |x|, and xhat . g = z . dz because z = W xhat.  Returns (1 / |x|, (z . dz) / |x|^2):
+// dx = .x * g - .y * x.  Without the option: (1, 0).
+__device__ __forceinline__ float2 unit_terms(const Args &a, const HashView &hv, int tok, const float *dz)
+{
+    if (!a.unit) return float2{1.f, 0.f};
+    const float inv = hv.inv[tok];
+    float radial = 0.f;
+    for (int t = 0; t < a.P; ++t) radial = fmaf(hv.z[tok * a.P + t], dz[t], radial);
+    return float2{inv, radial * inv * inv};
 }
 
 // Sum of the first P threads' dbeta_acc, in thread order, to one workspace slot (end of a gradient kernel).
@@ -362,10 +392,11 @@ __global__ __launch_bounds__(kThreads) void simple_bwd_query(Args a, const T *Q,
             }
             __syncthreads();
             soft_hash_vjp(a, hq.phi + tok * a.R, hq.s + tok * a.P, hq.u + tok * a.P, sm.dphi, sm.dz, dbeta_acc);
+            const float2 un = unit_terms(a, hq, tok, sm.dz);
             for (int c = threadIdx.x; c < a.d; c += kThreads) {
                 float acc = 0.f;
                 for (int t = 0; t < a.P; ++t) acc = fmaf(sm.dz[t], Wl[t * a.d + c], acc);
-                out[(t0 + tok) * a.d + c] = acc;
+                out[(t0 + tok) * a.d + c] = un.x * acc - un.y * sm.xb[tok * a.d + c];
             }
             __syncthreads();
         }
@@ -427,10 +458,11 @@ __global__ __launch_bounds__(kThreads) void simple_bwd_keyvalue(Args a, const T 
             }
             __syncthreads();
             soft_hash_vjp(a, phi, hk.s + tok * a.P, hk.u + tok * a.P, sm.dphi, sm.dz, dbeta_acc);
+            const float2 un = unit_terms(a, hk, tok, sm.dz);
             for (int c = threadIdx.x; c < a.d; c += kThreads) {
                 float acc = 0.f;
                 for (int t = 0; t < a.P; ++t) acc = fmaf(sm.dz[t], Wl[t * a.d + c], acc);
-                outK[(t0 + tok) * a.d + c] = acc;
+                outK[(t0 + tok) * a.d + c] = un.x * acc - un.y * sm.xa[tok * a.d + c];
             }
             __syncthreads();
         }
@@ -473,9 +505,16 @@ __global__ void simple_hash_tap(Args a, int BH, const T *X, uint8_t *codes, floa
     const float *Wl = a.W + (static_cast<size_t>(h) * a.LP + l * a.P) * a.d;
     float p[8], q[8];
     unsigned code = 0;
+    float inv = 1.f;
+    if (a.unit) {
+        float ss = 0.f;
+        for (int c = 0; c < a.d; ++c) { const float x = load_elem(X, row * a.d + c); ss = fmaf(x, x, ss); }
+        inv = unit_scale(ss);
+    }
     for (int t = 0; t < a.P; ++t) {
         float z = 0.f;
         for (int c = 0; c < a.d; ++c) z = fmaf(Wl[t * a.d + c], load_elem(X, row * a.d + c), z);
+        z *= inv;
         code |= (z >= 0.f ? 1u : 0u) << t;
         const float u = tanhf(z);
         const float e = mass_ratio(a.beta, u);
@@ -519,7 +558,7 @@ __global__ void simple_bucket_tap(Args a, int BH, const float *state, float *A, 
 constexpr int kDecodeThreads = 1024;
 
 template <typename T>
-__global__ __launch_bounds__(kDecodeThreads) void decode_step_kernel(int H, int L, int P, int d, float beta, const float *W,
+__global__ __launch_bounds__(kDecodeThreads) void decode_step_kernel(int H, int L, int P, int d, float beta, int unit, const float *W,
                                                                      const T *q, const T *k, const T *v, float *state,
                                                                      T *o, float *den)
 {
@@ -528,8 +567,8 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_step_kernel(int H, int 
     const int TL = (d + 63) & ~63, TF = kDecodeThreads / TL, NWV = TL / 64;
     const int tid = threadIdx.x, slot = tid / TL, c = tid % TL, lane = tid & 63, wv = c >> 6;
     const int bh = blockIdx.x, h = bh % H;
-    float *zred = lds;                              // [TF][2P][NWV] partial projections
-    float *pq = zred + TF * 2 * P * NWV;            // [TF][2P][2]   per-bit masses (+1 side, -1 side)
+    float *zred = lds;                              // [TF][2P+2][NWV] partial projections, then the rows' squared lengths
+    float *pq = zred + TF * (2 * P + 2) * NWV;      // [TF][2P][2]   per-bit masses (+1 side, -1 side)
     float *phi = pq + TF * 2 * P * 2;               // [TF][2][R]    assignments of the query (0) and the key (1)
     float *numred = phi + TF * 2 * R;               // [TF][d]       numerators per slot
     float *dred = numred + TF * d;                  // [16]          normaliser per wavefront
@@ -542,23 +581,28 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_step_kernel(int H, int 
         const int l = l0 + slot;
         const bool on = active && l < L;
         const float *Wl = W + (static_cast<size_t>(h) * L + (on ? l : 0)) * P * d;
-        for (int t = 0; t < P; ++t) {
-            const float w = (on && c < d) ? Wl[t * d + c] : 0.f;
-            float a = w * xq, b = w * xk;
+        for (int t = 0; t <= P; ++t) {              // t = P: the squared lengths |q|^2, |k|^2 instead of a projection
+            const float w = (on && c < d) ? (t < P ? Wl[t * d + c] : 1.f) : 0.f;
+            float a = w * xq * (t < P ? 1.f : xq), b = w * xk * (t < P ? 1.f : xk);
 #pragma unroll
             for (int m = 32; m >= 1; m >>= 1) {
                 a += __shfl_xor(a, m, 64);
                 b += __shfl_xor(b, m, 64);
             }
             if (active && lane == 0) {
-                zred[(slot * 2 * P + t) * NWV + wv] = a;
-                zred[(slot * 2 * P + P + t) * NWV + wv] = b;
+                zred[(slot * (2 * P + 2) + 2 * t) * NWV + wv] = a;
+                zred[(slot * (2 * P + 2) + 2 * t + 1) * NWV + wv] = b;
             }
         }
         __syncthreads();
         if (on && c < 2 * P) {                      // per-bit masses of the query (c < P) and of the key
-            float z = 0.f;
-            for (int i = 0; i < NWV; ++i) z += zred[(slot * 2 * P + c) * NWV + i];
+            const int side = c / P, t = c % P;
+            float z = 0.f, ss = 0.f;
+            for (int i = 0; i < NWV; ++i) {
+                z += zred[(slot * (2 * P + 2) + 2 * t + side) * NWV + i];
+                ss += zred[(slot * (2 * P + 2) + 2 * P + side) * NWV + i];
+            }
+            if (unit) z *= unit_scale(ss);
             const float u = tanhf(z);
             const float e = mass_ratio(beta, u);
             const float big = 1.0f / (1.0f + e), small = e / (1.0f + e);
@@ -627,7 +671,7 @@ Args make_args(const Plan &p, const char *ws)
     Args a;
     a.H = p.H; a.L = p.L; a.P = p.P; a.R = p.R; a.d = p.d; a.LP = p.LP;
     a.nseg = p.nseg; a.causal = p.causal; a.TT = pick_tile(p.R, p.d, p.P);
-    a.N = p.N; a.seg_len = p.seg_len; a.beta = p.beta;
+    a.N = p.N; a.seg_len = p.seg_len; a.beta = p.beta; a.unit = p.unit_qk;
     a.W = reinterpret_cast<const float *>(ws + p.off_W);
     return a;
 }
@@ -770,12 +814,12 @@ hipError_t decode_step(const Plan &p, const float *W, const void *q, const void 
                        void *o, float *den, hipStream_t st)
 {
     const int TL = (p.d + 63) & ~63, TF = kDecodeThreads / TL;
-    const size_t lds = (static_cast<size_t>(TF) * 2 * p.P * (TL / 64) + TF * 4 * p.P + TF * 2 * p.R + TF * p.d + 16) * sizeof(float);
+    const size_t lds = (static_cast<size_t>(TF) * (2 * p.P + 2) * (TL / 64) + TF * 4 * p.P + TF * 2 * p.R + TF * p.d + 16) * sizeof(float);
     if (p.dtype == RACE_F32)
-        hipLaunchKernelGGL((decode_step_kernel<float>), dim3(p.BH), dim3(kDecodeThreads), lds, st, p.H, p.L, p.P, p.d, p.beta, W,
+        hipLaunchKernelGGL((decode_step_kernel<float>), dim3(p.BH), dim3(kDecodeThreads), lds, st, p.H, p.L, p.P, p.d, p.beta, p.unit_qk, W,
                            (const float *)q, (const float *)k, (const float *)v, state, (float *)o, den);
     else
-        hipLaunchKernelGGL((decode_step_kernel<bf16_t>), dim3(p.BH), dim3(kDecodeThreads), lds, st, p.H, p.L, p.P, p.d, p.beta, W,
+        hipLaunchKernelGGL((decode_step_kernel<bf16_t>), dim3(p.BH), dim3(kDecodeThreads), lds, st, p.H, p.L, p.P, p.d, p.beta, p.unit_qk, W,
                            (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v, state, (bf16_t *)o, den);
     return hipGetLastError();
 }

@@ -26,8 +26,9 @@ class Workload:
     sharpening: float
     causal: bool
     dtype: str            # "f32" or "bf16"
-    normalize_qk: bool = False
+    normalize_qk: bool = False     # input recipe: rows of Q and K are generated with unit length
     chunk: int = 0
+    unit_qk: bool = False          # descriptor option: the layer divides the rows of Q and K by their norms
 
     @property
     def torch_dtype(self):
@@ -35,7 +36,7 @@ class Workload:
 
     def scaled(self, N: int, name: str = None) -> "Workload":
         return Workload(name or ("%s@N=%d" % (self.name, N)), self.B, self.H, N, self.d, self.L, self.P,
-                        self.sharpening, self.causal, self.dtype, self.normalize_qk, self.chunk)
+                        self.sharpening, self.causal, self.dtype, self.normalize_qk, self.chunk, self.unit_qk)
 
 
 # The five benchmark configurations.

@@ -16,7 +16,7 @@ TOL = {"f32": 1e-4, "bf16": 2e-2}
 
 def desc_of(w: synth.Workload):
     return ra.make_desc(w.B, w.H, w.N, w.d, w.L, w.P, w.sharpening, w.causal,
-                        ra.RACE_F32 if w.dtype == "f32" else ra.RACE_BF16, w.chunk)
+                        ra.RACE_F32 if w.dtype == "f32" else ra.RACE_BF16, w.chunk, w.unit_qk)
 
 
 def to_f64(t: torch.Tensor) -> np.ndarray:
@@ -55,9 +55,13 @@ def run_gpu(w: synth.Workload, tensors=None, seeds=None, saved=False):
 def run_oracle(w: synth.Workload, g):
     W = oracle_w(w, g["seeds"])
     Q, K, V, dO = (to_f64(g[n]) for n in ("Q", "K", "V", "dO"))
-    O, den = oracle_stream.forward(Q, K, V, W, w.sharpening, w.L, w.P, w.causal)
+    # the unit-norm option is the map x -> x / |x| in front of the layer and its chain rule behind the backward pass
+    Qu, Ku = (ro.unit_rows(Q), ro.unit_rows(K)) if w.unit_qk else (Q, K)
+    O, den = oracle_stream.forward(Qu, Ku, V, W, w.sharpening, w.L, w.P, w.causal)
     # the backward pass is a function of (Q, K, V, O, den, dO); feed it the oracle's own O and den
-    dQ, dK, dV = oracle_stream.backward(Q, K, V, W, w.sharpening, w.L, w.P, w.causal, O, den, dO)
+    dQ, dK, dV = oracle_stream.backward(Qu, Ku, V, W, w.sharpening, w.L, w.P, w.causal, O, den, dO)
+    if w.unit_qk:
+        dQ, dK = ro.unit_rows_vjp(Q, dQ), ro.unit_rows_vjp(K, dK)
     return dict(O=O, den=den, dQ=dQ, dK=dK, dV=dV)
 
 
@@ -91,6 +95,8 @@ def check_dbeta(w: synth.Workload, tol=None, verbose=True, scale="max"):
         assert torch.equal(a, b)
     W = oracle_w(w, g["seeds"])
     Q, K, V, dO = (to_f64(g[n]) for n in ("Q", "K", "V", "dO"))
+    if w.unit_qk:
+        Q, K = ro.unit_rows(Q), ro.unit_rows(K)
     O, den = oracle_stream.forward(Q, K, V, W, w.sharpening, w.L, w.P, w.causal)
     *_, ref = oracle_stream.backward(Q, K, V, W, w.sharpening, w.L, w.P, w.causal, O, den, dO, with_beta=True)
     got = to_f64(dbeta)

@@ -51,6 +51,19 @@ def test_invalid_descriptors_are_rejected(bad):
     assert st == ra.RACE_ERR_INVALID_ARG
 
 
+def test_unit_norm_option_is_a_flag():
+    d = _desc()
+    assert d.unit_qk == 0 and ra.race_attn_workspace_bytes(d) > 0
+    d1 = _desc(unit_qk=True)
+    assert d1.unit_qk == 1 and ra.race_attn_workspace_bytes(d1) == ra.race_attn_workspace_bytes(d)
+    d1.unit_qk = 2
+    assert ra.race_attn_workspace_bytes(d1) == 0
+    fake = ctypes.c_void_p(256)
+    seeds = (ctypes.c_uint64 * 2)(1, 2)
+    st = ra.lib().race_attn_fwd(ctypes.byref(d1), fake, fake, fake, seeds, fake, fake, fake, 1 << 40, None)
+    assert st == ra.RACE_ERR_INVALID_ARG
+
+
 def test_infinite_temperature_is_the_hard_hash_forward_only():
     d = _desc(sharpening=float("inf"))
     need = ra.race_attn_workspace_bytes(d)
