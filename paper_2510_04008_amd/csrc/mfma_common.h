@@ -271,7 +271,7 @@ __device__ __forceinline__ void store_row_scales(const RowChunks<C, ROWS> &r, fl
     }
 }
 
-// Read-out cotangent rows: gn = dO / e (e = L * Den) as bf16 rows, ge[row] = -(dO . O) / e as fp32.
+// Read-out cotangent rows: gn = dO / e (e = L * Den) as bf16 rows, ge[row] = -(gn . O) as fp32 (= -(dO . O) / e).
 template <class C, int ROWS>
 struct CotChunks {
     RowChunks<C, ROWS> g, o;
@@ -306,17 +306,18 @@ __device__ __forceinline__ void store_cotangent(const CotChunks<C, ROWS> &r, bf1
         float dot = 0.f;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const float g0 = bf_lo(gw[e]), g1 = bf_hi(gw[e]);
-            dot = fmaf(g0, bf_lo(ow[e]), dot);
-            dot = fmaf(g1, bf_hi(ow[e]), dot);
-            out[e] = pack2(g0 * inv, g1 * inv);
+            out[e] = pack2(bf_lo(gw[e]) * inv, bf_hi(gw[e]) * inv);
+            // the extra column is formed from the rounded cotangents the matrix products will see: for a row of the
+            // statistics made of few keys, V_j . gn + ge = (V_j - O_i) . gn then cancels as it does in exact arithmetic
+            dot = fmaf(bf_lo(out[e]), bf_lo(ow[e]), dot);
+            dot = fmaf(bf_hi(out[e]), bf_hi(ow[e]), dot);
         }
         if (row < ROWS) store_chunk<STRIDE, IL>(dst, row, ch, u32x4{out[0], out[1], out[2], out[3]});
         if (ge) {
             // the CPR threads of one row are consecutive lanes
 #pragma unroll
             for (int m = C::CPR / 2; m >= 1; m >>= 1) dot += __shfl_xor(dot, m, 64);
-            if (ch == 0 && row < ROWS) ge[row] = -dot * inv;
+            if (ch == 0 && row < ROWS) ge[row] = -dot;
         }
     }
 }
