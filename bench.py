@@ -11,6 +11,7 @@ before the timed region starts.  Prints ONE JSON line on stdout.
 from __future__ import annotations
 
 import argparse
+import dataclasses
 import json
 import os
 import sys
@@ -72,6 +73,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--bwd-recompute", action="store_true",
                     help="time race_attn_bwd (derives the key/value statistics again) instead of race_attn_bwd_saved")
+    ap.add_argument("--unit-qk", action="store_true",
+                    help="descriptor option unit_qk: the layer divides the rows of Q and K by their norms (not the headline workload)")
     ap.add_argument("--no-attainable", action="store_true", help="skip the copy / MFMA-loop calibration launches")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="before the warm-up, run one plain copy kernel of this many MiB (scale for byte counters)")
@@ -91,11 +94,13 @@ def main() -> int:
     if args.tokens:
         w = w.scaled(args.tokens)
     if args.chunk >= 0:
-        w = synth.Workload(w.name, w.B, w.H, w.N, w.d, w.L, w.P, w.sharpening, w.causal, w.dtype, w.normalize_qk, args.chunk)
+        w = dataclasses.replace(w, chunk=args.chunk)
+    if args.unit_qk:
+        w = dataclasses.replace(w, name=w.name + "+unit_qk", unit_qk=True)
     dev = "cuda:0"
     torch.cuda.set_device(0)
     desc = ra.make_desc(w.B, w.H, w.N, w.d, w.L, w.P, w.sharpening, w.causal,
-                        ra.RACE_F32 if w.dtype == "f32" else ra.RACE_BF16, w.chunk)
+                        ra.RACE_F32 if w.dtype == "f32" else ra.RACE_BF16, w.chunk, w.unit_qk)
     family = ra.race_attn_kernel_family(desc)
     if family == 0:
         raise SystemExit("unsupported workload")
@@ -192,8 +197,11 @@ def main() -> int:
         b_sample = 1                                   # one batch element is enough for a rate
         host = [t[:b_sample, :, :n0].float().cpu().numpy().astype(np.float64) for t in (Q, K, V, dO)]
         tc = time.perf_counter()
-        Oo, deno = oracle_stream.forward(host[0], host[1], host[2], Wm, w.sharpening, w.L, w.P, w.causal)
-        go = oracle_stream.backward(host[0], host[1], host[2], Wm, w.sharpening, w.L, w.P, w.causal, Oo, deno, host[3])
+        hq, hk = (ro.unit_rows(host[0]), ro.unit_rows(host[1])) if w.unit_qk else (host[0], host[1])
+        Oo, deno = oracle_stream.forward(hq, hk, host[2], Wm, w.sharpening, w.L, w.P, w.causal)
+        go = oracle_stream.backward(hq, hk, host[2], Wm, w.sharpening, w.L, w.P, w.causal, Oo, deno, host[3])
+        if w.unit_qk:
+            go = (ro.unit_rows_vjp(host[0], go[0]), ro.unit_rows_vjp(host[1], go[1]), go[2])
         cpu_s = time.perf_counter() - tc
         cpu_baseline = {"value": b_sample * n0 / cpu_s, "unit": "tokens/s", "cores": oracle_stream.threads(),
                         "kind": "oracle",
@@ -214,7 +222,7 @@ def main() -> int:
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "N": w.N, "d": w.d, "L": w.L, "P": w.P,
-                   "sharpening": w.sharpening, "causal": w.causal, "kernel_family": family,
+                   "sharpening": w.sharpening, "causal": w.causal, "unit_qk": w.unit_qk, "kernel_family": family,
                    "backward": "race_attn_bwd" if args.bwd_recompute else "race_attn_bwd_saved"},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,

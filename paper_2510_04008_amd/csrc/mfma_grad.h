@@ -86,8 +86,9 @@ struct GradLds {
     static constexpr int dz = wp + C::LPP * C::XS * 2;                  // [32][DZS] bf16
     static constexpr int sr = dz + kTile * DZS * 2;                     // [32] fp32 extra column of reader-Y
     static constexpr int sw = sr + kTile * 4;                           // [32] fp32 extra column of writer-Y
-    static constexpr int nrm = sw + kTile * 4;                          // [2][32] fp32: 1 / |x| of the reader and writer rows (unit-norm option)
-    static constexpr int rad = nrm + (UNIT ? 2 * kTile * 4 : 0);        // [kWaves][32] fp32: per-wavefront parts of z . dz per token (same option)
+    static constexpr int nrm = sw + kTile * 4;                          // [2][2][32] fp32: 1 / |x| of the reader and writer rows (unit-norm option),
+                                                                        // two buffers used by alternate tiles
+    static constexpr int rad = nrm + (UNIT ? 4 * kTile * 4 : 0);        // [kWaves][32] fp32: per-wavefront parts of z . dz per token (same option)
     static constexpr int PMS = UNIT ? 5 * C::PP + (C::PP == 8 ? 4 : 8)  // floats per (table, token): p, q, sech^2, tanh (, z), each padded
                                     : 4 * C::PP + 4;                    // to PP; the tail makes PMS / 4 odd, which keeps 16-byte reads of
                                                                         // 16 tokens on distinct banks
@@ -102,7 +103,10 @@ struct GradLds {
     static constexpr int phw = yw + kTile * C::YS * 2;                  // [32][PST] writer assignments
     static constexpr int SS = 40;                                       // bf16 row stride of the output staging tiles
     static constexpr int stg = phw + kTile * C::PST * 2;                // [NT][32][SS] bf16: dX tiles on their way out
-    static constexpr int total = stg + (G::TSPLIT == 1 ? C::NT * kTile * SS * 2 : 0);
+    static constexpr int xr2 = stg + (G::TSPLIT == 1 ? C::NT * kTile * SS * 2 : 0);   // [32][XS]: second buffer of the reader rows (unit-norm
+                                                                        // option: the dX wavefronts still read a tile's rows while the others
+                                                                        // store the next tile's)
+    static constexpr int total = xr2 + (UNIT ? kTile * C::XS * 2 : 0);
     static_assert(total <= 160 * 1024, "LDS budget");
 };
 
@@ -118,11 +122,11 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
     bf16raw *dz = reinterpret_cast<bf16raw *>(lds + S::dz);
     float *sr = reinterpret_cast<float *>(lds + S::sr);
     float *sw = reinterpret_cast<float *>(lds + S::sw);
-    float *nrm = reinterpret_cast<float *>(lds + S::nrm);
+    float *nrm0 = reinterpret_cast<float *>(lds + S::nrm);
     float *rad = reinterpret_cast<float *>(lds + S::rad);
     float *pm = reinterpret_cast<float *>(lds + S::pm);
     bf16raw *yr = reinterpret_cast<bf16raw *>(lds + S::yr);
-    bf16raw *xr = reinterpret_cast<bf16raw *>(lds + S::xr);
+    bf16raw *xr0 = reinterpret_cast<bf16raw *>(lds + S::xr);
     bf16raw *xw = reinterpret_cast<bf16raw *>(lds + S::xw);
     bf16raw *yw = reinterpret_cast<bf16raw *>(lds + S::yw);
     bf16raw *phw = reinterpret_cast<bf16raw *>(lds + S::phw);
@@ -201,6 +205,9 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
     for (int it = 0; it < ntiles; ++it) {
         const int64_t t0 = tile_t0(it);
         const int nvalid = tile_nv(t0);
+        // unit-norm option: alternate tiles use alternate buffers for the reader's rows and the scales
+        bf16raw *xr = (UNIT && (it & 1)) ? reinterpret_cast<bf16raw *>(lds + S::xr2) : xr0;
+        float *nrm = nrm0 + ((UNIT && (it & 1)) ? 2 * kTile : 0);
 
         // ---- registers -> LDS
         store_rows<C, kTile>(pre_r, xr, nvalid);
@@ -531,9 +538,9 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
         }
         GRAD_PHASE(12)
         // no barrier here: the next step's loads-to-LDS touch none of dz, pm, part or the staging tiles, and its
-        // production (which rewrites pm) comes after the next barrier -- except with the unit-norm option, where the
-        // dX wavefronts have just read the reader's rows and scales, which the next step's first stores overwrite
-        if (UNIT) __syncthreads();
+        // production (which rewrites pm) comes after the next barrier.  (With the unit-norm option the dX wavefronts
+        // have just read the reader's rows and scales: the next step stores into the other buffer, and the step after
+        // that comes after barriers these wavefronts take part in.)
     }
     // ---- cotangent of beta: lanes -> wavefront (shuffles) -> workgroup (LDS, wavefront order) -> one workspace slot
     {
