@@ -50,7 +50,9 @@ struct Cfg {
     static constexpr bool PAD = PAD_;
     static constexpr int R = 1 << P, LR = L * R;
     static constexpr int PP = P > 4 ? 8 : 4;            // hyperplanes per table, padded
-    static constexpr int TPG = 32 / PP;                 // tables per 32-row projection group
+    // tables per 32-row projection group: as many as fit, or (shapes with fewer tables) the tables there are, spread
+    // over both lane halves; the group's remaining rows are padding
+    static constexpr int TPG = (32 / PP < L + (L & 1)) ? 32 / PP : L + (L & 1);
     static constexpr int TPL = TPG / 2;                 // tables per lane (per half-wave)
     static constexpr int NG = (L + TPG - 1) / TPG;      // projection groups
     static constexpr int LPP = NG * 32;                 // padded projection rows

@@ -163,7 +163,7 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
             *reinterpret_cast<u32x4 *>(wp + row * C::XS + ch * 8) = *reinterpret_cast<const u32x4 *>(src + row * C::D + ch * 8);
         }
     }
-    if (G::TABLES * C::R != G::ROWS) {
+    if (G::TABLES * C::R != G::ROWS || C::TPG * C::PP < 32) {
         // projection slots of tables that do not exist are never written below: they must be zeros for dX = dz . W
         for (int i = tid; i < kTile * S::DZS; i += kThreads) dz[i] = 0;
     }

@@ -724,8 +724,9 @@ uint16_t host_bf16(float x)
 
 // W (H, L*P, D) -> Wp (H, LPP, D) and WpT (H, D, LPP) in projection-group order: row rho of group g
 // belongs to the lane half hh = (rho / 4) % 2; with a = rho / 8 and b = rho % 4 the half's slots (a, b)
-// hold, for 8-padded tables, table 2*hh + a/2 and hyperplane 4*(a%2) + b; for 4-padded tables, table
-// 4*hh + a and hyperplane b.  Rows of padding are zero.
+// hold, for 8-padded tables, the half's table a/2 and hyperplane 4*(a%2) + b; for 4-padded tables, the half's
+// table a and hyperplane b; the half's table j is table TPL*hh + j of the group.  Rows of padding (slots beyond
+// the half's TPL tables, tables and hyperplanes the problem does not have) are zero.
 template <class C>
 void pack_t(const Plan &p, const float *W, void *image)
 {
@@ -734,12 +735,12 @@ void pack_t(const Plan &p, const float *W, void *image)
     for (int hd = 0; hd < p.H; ++hd) {
         for (int row = 0; row < C::LPP; ++row) {
             const int g = row / 32, rho = row % 32, a = rho / 8, hh = (rho / 4) % 2, b = rho % 4;
-            const int tl = (C::PP == 8) ? 2 * hh + a / 2 : 4 * hh + a;
+            const int j = (C::PP == 8) ? a / 2 : a;
             const int t = (C::PP == 8) ? 4 * (a % 2) + b : b;
-            const int table = g * C::TPG + tl;
+            const int table = g * C::TPG + C::TPL * hh + j;
             for (int c = 0; c < C::D; ++c) {
                 float v = 0.f;
-                if (table < p.L && t < p.P) v = W[(static_cast<size_t>(hd) * p.LP + table * p.P + t) * C::D + c];
+                if (j < C::TPL && table < p.L && t < p.P) v = W[(static_cast<size_t>(hd) * p.LP + table * p.P + t) * C::D + c];
                 const uint16_t bits = host_bf16(v);
                 wp[(static_cast<size_t>(hd) * C::LPP + row) * C::D + c] = bits;
                 wpt[(static_cast<size_t>(hd) * C::D + c) * C::LPP + row] = bits;
