@@ -406,16 +406,18 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
         if (intra && has_rows) {
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
-                const float4 g0 = *reinterpret_cast<const float4 *>(sw + 16 * s + 8 * h);
-                const float4 g1 = *reinterpret_cast<const float4 *>(sw + 16 * s + 8 * h + 4);
+                float4 g0 = {1.f, 1.f, 1.f, 1.f}, g1 = g0;          // SIDE 0: the extra column of [V | 1] is one
+                if (SIDE == 1) {
+                    g0 = *reinterpret_cast<const float4 *>(sw + 16 * s + 8 * h);
+                    g1 = *reinterpret_cast<const float4 *>(sw + 16 * s + 8 * h + 4);
+                }
                 u32x4 ay[C::NT];
 #pragma unroll
                 for (int mtc = 0; mtc < C::NT; ++mtc) ay[mtc] = lds_tr_plain<true>(yw, C::YS, 16 * s, 32 * mtc, ln, h);
 #pragma unroll
                 for (int mr = 0; mr < G::MTG; ++mr) {
                     const u32x4 bp = lds_tr_plain<true>(phw, C::PST, 16 * s, r_own + 32 * mr, ln, h);
-                    macc[mr] += bf_lo(bp.x) * g0.x + bf_hi(bp.x) * g0.y + bf_lo(bp.y) * g0.z + bf_hi(bp.y) * g0.w +
-                                bf_lo(bp.z) * g1.x + bf_hi(bp.z) * g1.y + bf_lo(bp.w) * g1.z + bf_hi(bp.w) * g1.w;
+                    macc[mr] += SIDE == 1 ? wsum8(bp, g0, g1) : sum8(bp);
 #pragma unroll
                     for (int mtc = 0; mtc < C::NT; ++mtc) ST[mr][mtc] = mma(ay[mtc], bp, ST[mr][mtc]);
                 }

@@ -151,8 +151,7 @@ void totals_kernel(KArgs a, const bf16raw *X, const bf16raw *Y, const bf16raw *O
             for (int mt = 0; mt < C::MT; ++mt) {
                 const u32x4 ap = lds_tr_plain<true>(ph, C::PST, 16 * s, r_own + 32 * mt, ln, h);
                 if (mass_owner<C>(mt, cg))      // the extra column (bucket mass, or its cotangent): shared out over the column groups
-                    macc[mt] += bf_lo(ap.x) * g0.x + bf_hi(ap.x) * g0.y + bf_lo(ap.y) * g0.z + bf_hi(ap.y) * g0.w +
-                                bf_lo(ap.z) * g1.x + bf_hi(ap.z) * g1.y + bf_lo(ap.w) * g1.z + bf_hi(ap.w) * g1.w;
+                    macc[mt] += wsum8(ap, g0, g1);
 #pragma unroll
                 for (int nt = 0; nt < C::NTW; ++nt) Sacc[mt][nt] = mma(ap, by[nt], Sacc[mt][nt]);
             }
