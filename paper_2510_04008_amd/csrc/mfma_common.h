@@ -223,14 +223,19 @@ struct RowChunks {
 // Every lane loads, unconditionally: rows past the end of the tile (nvalid >= 1 rows are real) re-read the last real
 // row and are zeroed when they are stored.  (A load under a condition, into registers cleared first, makes the
 // compiler wait for every load in flight before the clearing moves: the loads of a tile would complete one by one.)
-template <class C, int ROWS>
+// SBASE: the address as a uniform base plus a 32-bit byte offset per lane, which lets the loads take their base from
+// scalar registers (10-15 vector registers fewer in the gradient kernel, which needs them; the stream and totals
+// kernels measured 1-4 % slower with it and keep the plain form).
+template <class C, int ROWS, bool SBASE = false>
 __device__ __forceinline__ void fetch_rows(const bf16raw *X, int64_t t0, int nvalid, RowChunks<C, ROWS> &r)
 {
+    const char *base = reinterpret_cast<const char *>(X + t0 * C::D);
 #pragma unroll
     for (int k = 0; k < RowChunks<C, ROWS>::N; ++k) {
         const int c = threadIdx.x + k * kThreads, row = c / C::CPR, ch = c % C::CPR;
         const int rr = row < nvalid ? row : nvalid - 1;
-        r.v[k] = *reinterpret_cast<const u32x4 *>(X + (t0 + rr) * C::D + ch * 8);
+        if (SBASE) r.v[k] = *reinterpret_cast<const u32x4 *>(base + static_cast<uint32_t>((rr * C::D + ch * 8) * 2));
+        else r.v[k] = *reinterpret_cast<const u32x4 *>(X + (t0 + rr) * C::D + ch * 8);
     }
 }
 
@@ -290,16 +295,19 @@ struct CotChunks {
     float den[RowChunks<C, ROWS>::N];
 };
 
-template <class C, int ROWS>
+template <class C, int ROWS, bool SBASE = false>
 __device__ __forceinline__ void fetch_cotangent(const bf16raw *dO, const bf16raw *O, const float *den, int64_t t0,
                                                 int nvalid, CotChunks<C, ROWS> &r)
 {
-    fetch_rows<C, ROWS>(dO, t0, nvalid, r.g);
-    fetch_rows<C, ROWS>(O, t0, nvalid, r.o);
+    fetch_rows<C, ROWS, SBASE>(dO, t0, nvalid, r.g);
+    fetch_rows<C, ROWS, SBASE>(O, t0, nvalid, r.o);
+    const char *dbase = reinterpret_cast<const char *>(den + t0);
 #pragma unroll
     for (int k = 0; k < RowChunks<C, ROWS>::N; ++k) {
         const int row = (threadIdx.x + k * kThreads) / C::CPR;
-        r.den[k] = den[t0 + (row < nvalid ? row : nvalid - 1)];
+        const int rr = row < nvalid ? row : nvalid - 1;
+        if (SBASE) r.den[k] = *reinterpret_cast<const float *>(dbase + static_cast<uint32_t>(rr * 4));
+        else r.den[k] = den[t0 + rr];
     }
 }
 

@@ -75,6 +75,26 @@ struct GradCfg {
     // in-tile term: a wavefront of its own if one is left, else the last reader
     static constexpr int TT = DISJ ? (NW + NR < kWaves ? NW + NR : kWaves - 1) : kWaves - 1 - NGW;
     static_assert(NW <= kWaves && RD0 + NR <= kWaves, "production roles must fit the wavefronts");
+    // dX = dz . W of a tile is formed one step late, next to the production of the following tile, by the wavefronts
+    // with the lightest production roles: first those without a role, then the in-tile term's, then writers,
+    // readers last (the higher wavefront first within a class).  dx_tile(w) = column tile of wavefront w, or -1.
+    static constexpr int role_weight(int w)
+    {
+        return (w >= RD0 && w < RD0 + NR) ? 3 : (w < NW ? 2 : (w == TT ? 1 : 0));
+    }
+    static constexpr int dx_tile(int w)
+    {
+        int taken = 0;
+        for (int weight = 0; weight <= 3; ++weight) {
+            for (int v = kWaves - 1; v >= 0; --v) {
+                if (role_weight(v) != weight) continue;
+                if (taken == C::NT) return -1;
+                if (v == w) return taken;
+                ++taken;
+            }
+        }
+        return -1;
+    }
 };
 
 // UNIT: the unit-norm option's extras (row scales, parts of z . dz, and z next to the per-bit masses).
@@ -193,12 +213,60 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
     auto fetch = [&](int it) {
         const int64_t t0 = tile_t0(it);
         const int nv = tile_nv(t0);
-        fetch_rows<C, kTile>(Xr, t0, nv, pre_r);
-        if (intra) fetch_rows<C, kTile>(Xw, t0, nv, pre_w);
-        if (SIDE == 1 || intra) fetch_rows<C, kTile>(V, t0, nv, pre_v);
-        if (SIDE == 0 || intra) fetch_cotangent<C, kTile>(dO, O, den, t0, nv, pre_c);
+        fetch_rows<C, kTile, true>(Xr, t0, nv, pre_r);
+        if (intra) fetch_rows<C, kTile, true>(Xw, t0, nv, pre_w);
+        if (SIDE == 1 || intra) fetch_rows<C, kTile, true>(V, t0, nv, pre_v);
+        if (SIDE == 0 || intra) fetch_cotangent<C, kTile, true>(dO, O, den, t0, nv, pre_c);
     };
     if (ntiles > 0) fetch(0);
+
+    // ---- dX = dz . W for one tile (the chain rule through W): a wavefront forms the transposed 32 x 32 tile of its
+    //      column tile nt (lane = token, registers = columns 32 nt + acc_row(v, h)), stages it in its own corner of
+    //      LDS and stores 16-byte row pieces; nobody else touches that corner.  Called one step late (after the
+    //      next tile's first barrier, which also publishes dz), so that it runs next to the production phase
+    //      instead of keeping everybody waiting at the end of the tile; xr_t, nrm_t: the tile's reader rows and scales
+    //      (unit-norm option).
+    static_assert(C::NT <= kWaves, "one wavefront per column tile");
+    auto dx_stage = [&](int nt, int64_t t0, int nvalid, const bf16raw *xr_t, const float *nrm_t) __attribute__((always_inline)) {
+        const int lo = opaque(lane);                     // addresses below are rebuilt per tile, not kept in registers
+        const int lno = lo & 31, ho = lo >> 5;
+        f32x16 acc = {0};
+#pragma unroll
+        for (int s = 0; s < C::LPP / 16; ++s)
+            acc = mma(lds_tr_plain(wp, C::XS, 16 * s, 32 * nt, lno, ho), lds128(dz + lno * S::DZS + 16 * s + 8 * ho), acc);
+        if (UNIT) {
+            float cp = 0.f;                              // (z . dz) / |x|^2 of token lno, parts in wavefront order
+#pragma unroll
+            for (int i = 0; i < kWaves; ++i) cp += rad[i * kTile + lno];
+            cp *= nrm_t[lno];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const u32x2 xv = *reinterpret_cast<const u32x2 *>(xr_t + lno * C::XS + 32 * nt + 8 * k + 4 * ho);
+                acc[4 * k] = fmaf(-cp, bf_lo(xv.x), acc[4 * k]);
+                acc[4 * k + 1] = fmaf(-cp, bf_hi(xv.x), acc[4 * k + 1]);
+                acc[4 * k + 2] = fmaf(-cp, bf_lo(xv.y), acc[4 * k + 2]);
+                acc[4 * k + 3] = fmaf(-cp, bf_hi(xv.y), acc[4 * k + 3]);
+            }
+        }
+        bf16raw *sg = stg + nt * kTile * S::SS;
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            *reinterpret_cast<u32x2 *>(sg + lno * S::SS + 8 * k + 4 * ho) =
+                u32x2{pack2(acc[4 * k], acc[4 * k + 1]), pack2(acc[4 * k + 2], acc[4 * k + 3])};
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            const int row = (lo >> 2) + 16 * kk, ch = lo & 3;
+            const u32x4 piece = *reinterpret_cast<const u32x4 *>(sg + row * S::SS + 8 * ch);
+            if (row < nvalid) *reinterpret_cast<u32x4 *>(dX + (t0 + row) * C::D + 32 * nt + 8 * ch) = piece;
+        }
+    };
+    // this wavefront's column tile of dX (-1: none), by table look-up over the compile-time assignment
+    int my_dx = -1;
+#pragma unroll
+    for (int v = 0; v < kWaves; ++v)
+        if (w == v) my_dx = G::dx_tile(v);
+    auto tile_xr = [&](int it) { return (UNIT && (it & 1)) ? reinterpret_cast<bf16raw *>(lds + S::xr2) : xr0; };
+    auto tile_nrm = [&](int it) { return nrm0 + ((UNIT && (it & 1)) ? 2 * kTile : 0); };
 
     float dbeta_acc = 0.f;    // this lane's share of the cotangent of beta: sum of (E_t - m (p_t - q_t)) tanh z_t
     GRAD_PHASE_DECL
@@ -206,8 +274,8 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
         const int64_t t0 = tile_t0(it);
         const int nvalid = tile_nv(t0);
         // unit-norm option: alternate tiles use alternate buffers for the reader's rows and the scales
-        bf16raw *xr = (UNIT && (it & 1)) ? reinterpret_cast<bf16raw *>(lds + S::xr2) : xr0;
-        float *nrm = nrm0 + ((UNIT && (it & 1)) ? 2 * kTile : 0);
+        bf16raw *xr = tile_xr(it);
+        float *nrm = tile_nrm(it);
 
         // ---- registers -> LDS
         store_rows<C, kTile>(pre_r, xr, nvalid);
@@ -228,6 +296,13 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
         GRAD_PHASE(0)
         __syncthreads();
         GRAD_PHASE(1)
+        if constexpr (G::TSPLIT == 1) {
+            if (it > 0 && my_dx >= 0) {
+                const int64_t tp = tile_t0(it - 1);
+                dx_stage(my_dx, tp, tile_nv(tp), tile_xr(it - 1), tile_nrm(it - 1));
+            }
+        }
+        GRAD_PHASE(12)
 
         // extra columns as bf16 (hi, lo) pairs: three products hi*hi + hi*lo + lo*hi keep 16 mantissa bits
         float sr_hi, sr_lo;
@@ -487,49 +562,10 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
             if (h == 0) rad[w * kTile + ln] = radial;
         }
         GRAD_PHASE(9)
-        __syncthreads();
         GRAD_PHASE(11)
-
-        if constexpr (G::TSPLIT == 1) {
-            // ---- dX = dz . W for this tile (the chain rule through W): wavefront nt forms the transposed 32 x 32 tile
-            //      (lane = token, registers = columns 32 nt + acc_row(v, h)), stages it in its own corner of
-            //      LDS and stores 16-byte row pieces; nobody else touches that corner, so no barrier is needed
-            static_assert(C::NT <= kWaves, "one wavefront per column tile");
-            if (w < C::NT) {
-                const int nt = w;
-                const int lo = opaque(lane);                     // addresses below are rebuilt per tile, not kept in registers
-                const int lno = lo & 31, ho = lo >> 5;
-                f32x16 acc = {0};
-#pragma unroll
-                for (int s = 0; s < C::LPP / 16; ++s)
-                    acc = mma(lds_tr_plain(wp, C::XS, 16 * s, 32 * nt, lno, ho), lds128(dz + lno * S::DZS + 16 * s + 8 * ho), acc);
-                if (UNIT) {
-                    float cp = 0.f;                              // (z . dz) / |x|^2 of token lno, parts in wavefront order
-#pragma unroll
-                    for (int i = 0; i < kWaves; ++i) cp += rad[i * kTile + lno];
-                    cp *= nrm[lno];
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        const u32x2 xv = *reinterpret_cast<const u32x2 *>(xr + lno * C::XS + 32 * nt + 8 * k + 4 * ho);
-                        acc[4 * k] = fmaf(-cp, bf_lo(xv.x), acc[4 * k]);
-                        acc[4 * k + 1] = fmaf(-cp, bf_hi(xv.x), acc[4 * k + 1]);
-                        acc[4 * k + 2] = fmaf(-cp, bf_lo(xv.y), acc[4 * k + 2]);
-                        acc[4 * k + 3] = fmaf(-cp, bf_hi(xv.y), acc[4 * k + 3]);
-                    }
-                }
-                bf16raw *sg = stg + nt * kTile * S::SS;
-#pragma unroll
-                for (int k = 0; k < 4; ++k)
-                    *reinterpret_cast<u32x2 *>(sg + lno * S::SS + 8 * k + 4 * ho) =
-                        u32x2{pack2(acc[4 * k], acc[4 * k + 1]), pack2(acc[4 * k + 2], acc[4 * k + 3])};
-#pragma unroll
-                for (int kk = 0; kk < 2; ++kk) {
-                    const int row = (lo >> 2) + 16 * kk, ch = lo & 3;
-                    const u32x4 piece = *reinterpret_cast<const u32x4 *>(sg + row * S::SS + 8 * ch);
-                    if (row < nvalid) *reinterpret_cast<u32x4 *>(dX + (t0 + row) * C::D + 32 * nt + 8 * ch) = piece;
-                }
-            }
-        } else {
+        // (dX of this tile is formed after the next step's first barrier, see dx_stage)
+        if constexpr (G::TSPLIT != 1) {
+            __syncthreads();
             // ---- this workgroup's columns of dZ (projection rows of its groups) -> workspace, 16-byte pieces
             if (tid < kTile * G::NGW * 4) {
                 const int row = tid / (G::NGW * 4), ch = tid % (G::NGW * 4);
@@ -538,11 +574,19 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
                         *reinterpret_cast<const u32x4 *>(dz + row * S::DZS + 8 * ch);
             }
         }
-        GRAD_PHASE(12)
-        // no barrier here: the next step's loads-to-LDS touch none of dz, pm, part or the staging tiles, and its
-        // production (which rewrites pm) comes after the next barrier.  (With the unit-norm option the dX wavefronts
-        // have just read the reader's rows and scales: the next step stores into the other buffer, and the step after
-        // that comes after barriers these wavefronts take part in.)
+        // no barrier here: the next step's loads-to-LDS touch none of dz, pm, part or the staging tiles, its production
+        // (which rewrites pm) comes after the next barrier, and so does this tile's dX, which reads dz (rewritten only after
+        // two more barriers) and, with the unit-norm option, this tile's reader rows and scales (the next step stores into
+        // the other buffer, the step after that only after barriers the dX wavefronts take part in).
+    }
+    if constexpr (G::TSPLIT == 1) {
+        if (ntiles > 0) {
+            __syncthreads();        // the last tile's dz is visible
+            if (my_dx >= 0) {
+                const int64_t tp = tile_t0(ntiles - 1);
+                dx_stage(my_dx, tp, tile_nv(tp), tile_xr(ntiles - 1), tile_nrm(ntiles - 1));
+            }
+        }
     }
     // ---- cotangent of beta: lanes -> wavefront (shuffles) -> workgroup (LDS, wavefront order) -> one workspace slot
     {
