@@ -23,6 +23,7 @@ if ROOT not in sys.path:
 
 # MI355X published peaks
 PEAK_BF16_FLOPS = 2.5e15
+PEAK_FP32_VECTOR_FLOPS = 157.3e12      # the generic kernel family computes on the vector ALUs in fp32
 PEAK_HBM_BYTES = 8.0e12
 
 
@@ -47,6 +48,10 @@ def kernel_shares(w):
         "grad_q": U + proj / 2,              # dphi_Q, the chain rule through the soft assignment, dQ = dz . W
         "grad_k": U + proj / 2,              # dphi_K, same
         "stream_totals_kv": 0.0, "stream_totals_qg": 0.0, "segment_scan": 0.0,
+        # generic family: one replay kernel forward; the key/value kernel forms dV and dK
+        "simple_fwd_replay": proj + 2 * U,
+        "simple_bwd_keyvalue": proj + 2 * U + U + proj / 2,
+        "simple_bwd_query": U + proj / 2,
     }
 
 
@@ -183,8 +188,10 @@ def main() -> int:
         achieved = flops / avg_s / 1e12
         measured = MEASURED_TRAFFIC.get((w.dtype, w.d, w.L, w.P, bool(w.causal)), {}).get(name)
         traffic = measured * token_heads if measured is not None else None      # bytes per launch
-        roofline = {"kernel": name, "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_FLOPS / 1e12,
-                    "unit": "TFLOP/s", "frac": achieved / (PEAK_BF16_FLOPS / 1e12), "traffic": traffic,
+        mfma = family == 2
+        peak = (PEAK_BF16_FLOPS if mfma else PEAK_FP32_VECTOR_FLOPS) / 1e12
+        roofline = {"kernel": name, "bound": "mfma" if mfma else "alu", "achieved": achieved, "peak": peak,
+                    "unit": "TFLOP/s", "frac": achieved / peak, "traffic": traffic,
                     "avg_launch_ms": 1e3 * avg_s, "algorithmic_flops_per_launch": flops}
 
     cpu_baseline = None

@@ -196,10 +196,11 @@ race_status_t make_plan(const race_attn_desc_t *desc, Plan *pl)
 
     const int64_t n = p.N > 0 ? p.N : 1;
     if (p.family == kFamilySimple) {
-        // enough workgroups to fill 256 CUs a few times over, segments of at least 64 tokens
+        // enough workgroups to fill 256 CUs a few times over, segments of at least 16 tokens (the kernels take the
+        // tokens of a segment one after the other: short sequences want many short segments)
         int64_t want = (2048 + static_cast<int64_t>(p.BH) * p.L - 1) / (static_cast<int64_t>(p.BH) * p.L);
         int64_t len = desc->chunk > 0 ? desc->chunk : (n + want - 1) / want;
-        if (desc->chunk == 0 && len < 64) len = 64;
+        if (desc->chunk == 0 && len < 16) len = 16;
         len = (len + 7) / 8 * 8;
         p.seg_len = len;
         p.nseg = static_cast<int>((n + len - 1) / len);

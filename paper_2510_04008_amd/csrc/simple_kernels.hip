@@ -702,13 +702,25 @@ hipError_t fwd_impl(const Plan &p, const T *Q, const T *K, const T *V, T *O, flo
     const size_t elems = static_cast<size_t>(p.R) * (p.d + 1);
     RACE_TRY(allow_lds(simple_totals<T, 0>, lds));
     RACE_TRY(allow_lds(simple_fwd_replay<T>, lds));
-    hipLaunchKernelGGL((simple_totals<T, 0>), grid, dim3(kThreads), lds, st, a, K, V,
-                       static_cast<const T *>(nullptr), static_cast<const float *>(nullptr), state);
-    hipLaunchKernelGGL(simple_scan, dim3(blocks_for(elems, 256), p.BH * p.L), dim3(256), 0, st, state, p.nseg,
-                       elems, p.causal ? 0 : 2);
-    hipLaunchKernelGGL((simple_fwd_replay<T>), grid, dim3(kThreads), lds, st, a, Q, K, V, state, part);
+    {
+        ProfileScope prof("simple_totals_kv", st);
+        hipLaunchKernelGGL((simple_totals<T, 0>), grid, dim3(kThreads), lds, st, a, K, V,
+                           static_cast<const T *>(nullptr), static_cast<const float *>(nullptr), state);
+    }
+    {
+        ProfileScope prof("simple_scan", st);
+        hipLaunchKernelGGL(simple_scan, dim3(blocks_for(elems, 256), p.BH * p.L), dim3(256), 0, st, state, p.nseg,
+                           elems, p.causal ? 0 : 2);
+    }
+    {
+        ProfileScope prof("simple_fwd_replay", st);
+        hipLaunchKernelGGL((simple_fwd_replay<T>), grid, dim3(kThreads), lds, st, a, Q, K, V, state, part);
+    }
     const size_t total = static_cast<size_t>(p.BH) * p.N * p.d;
-    hipLaunchKernelGGL((simple_fwd_combine<T>), dim3(blocks_for(total, 256)), dim3(256), 0, st, a, p.BH, part, O, den);
+    {
+        ProfileScope prof("simple_fwd_combine", st);
+        hipLaunchKernelGGL((simple_fwd_combine<T>), dim3(blocks_for(total, 256)), dim3(256), 0, st, a, p.BH, part, O, den);
+    }
     return hipGetLastError();
 }
 
@@ -731,18 +743,39 @@ hipError_t bwd_impl(const Plan &p, const T *Q, const T *K, const T *V, const T *
     RACE_TRY(allow_lds(simple_totals<T, 1>, lds));
     RACE_TRY(allow_lds(simple_bwd_query<T>, lds));
     RACE_TRY(allow_lds(simple_bwd_keyvalue<T>, lds));
-    hipLaunchKernelGGL((simple_totals<T, 0>), grid, dim3(kThreads), lds, st, a, K, V,
-                       static_cast<const T *>(nullptr), static_cast<const float *>(nullptr), stateS);
-    hipLaunchKernelGGL(simple_scan, sgrid, dim3(256), 0, st, stateS, p.nseg, elems, p.causal ? 0 : 2);
-    hipLaunchKernelGGL((simple_totals<T, 1>), grid, dim3(kThreads), lds, st, a, Q, dO, O, den, stateD);
-    hipLaunchKernelGGL(simple_scan, sgrid, dim3(256), 0, st, stateD, p.nseg, elems, p.causal ? 1 : 2);
-    hipLaunchKernelGGL((simple_bwd_query<T>), grid, dim3(kThreads), lds, st, a, Q, K, V, O, den, dO, stateS, pQ,
-                       dbeta_part);
-    hipLaunchKernelGGL((simple_bwd_keyvalue<T>), grid, dim3(kThreads), lds, st, a, Q, K, V, O, den, dO, stateD, pK, pV,
-                       dbeta_part);
+    {
+        ProfileScope prof("simple_totals_kv", st);
+        hipLaunchKernelGGL((simple_totals<T, 0>), grid, dim3(kThreads), lds, st, a, K, V,
+                           static_cast<const T *>(nullptr), static_cast<const float *>(nullptr), stateS);
+    }
+    {
+        ProfileScope prof("simple_scan", st);
+        hipLaunchKernelGGL(simple_scan, sgrid, dim3(256), 0, st, stateS, p.nseg, elems, p.causal ? 0 : 2);
+    }
+    {
+        ProfileScope prof("simple_totals_qg", st);
+        hipLaunchKernelGGL((simple_totals<T, 1>), grid, dim3(kThreads), lds, st, a, Q, dO, O, den, stateD);
+    }
+    {
+        ProfileScope prof("simple_scan", st);
+        hipLaunchKernelGGL(simple_scan, sgrid, dim3(256), 0, st, stateD, p.nseg, elems, p.causal ? 1 : 2);
+    }
+    {
+        ProfileScope prof("simple_bwd_query", st);
+        hipLaunchKernelGGL((simple_bwd_query<T>), grid, dim3(kThreads), lds, st, a, Q, K, V, O, den, dO, stateS, pQ,
+                           dbeta_part);
+    }
+    {
+        ProfileScope prof("simple_bwd_keyvalue", st);
+        hipLaunchKernelGGL((simple_bwd_keyvalue<T>), grid, dim3(kThreads), lds, st, a, Q, K, V, O, den, dO, stateD, pK,
+                           pV, dbeta_part);
+    }
     const size_t total = static_cast<size_t>(p.BH) * p.N * p.d;
-    hipLaunchKernelGGL((simple_bwd_combine<T>), dim3(blocks_for(total, 256)), dim3(256), 0, st, a, p.BH, pQ, pK, pV,
-                       dQ, dK, dV);
+    {
+        ProfileScope prof("simple_bwd_combine", st);
+        hipLaunchKernelGGL((simple_bwd_combine<T>), dim3(blocks_for(total, 256)), dim3(256), 0, st, a, p.BH, pQ, pK, pV,
+                           dQ, dK, dV);
+    }
     if (dbeta) RACE_TRY(reduce_dbeta(p, dbeta_part, dbeta, st));
     return hipGetLastError();
 }
