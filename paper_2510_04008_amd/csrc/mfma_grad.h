@@ -98,7 +98,8 @@ struct GradCfg {
 };
 
 // UNIT: the unit-norm option's extras (row scales, parts of z . dz, and z next to the per-bit masses).
-template <class C, bool UNIT>
+// INTRA: the causal variant, whose tiles also feed the statistics: the writer's rows, assignments and the in-tile term.
+template <class C, bool UNIT, bool INTRA>
 struct GradLds {
     using G = GradCfg<C>;
     static constexpr int wp = 0;                                        // [LPP][XS] bf16
@@ -117,12 +118,12 @@ struct GradLds {
     static constexpr int part = pm + PMT * kTile * PMS * 4;             // [kWaves][32][8] fp32: partial (m, G_t) of table shares
     static constexpr int yr = part + (G::WPT > 1 ? kWaves * kTile * 8 * 4 : 0);   // [32][XS] reader-Y rows, pair-interleaved columns
     static constexpr int ttop = yr + kTile * C::XS * 2;                 // [2][64] x 16 B: masked in-tile term as MFMA operands
-    static constexpr int xr = (ttop + 2 * 64 * 16 + 255) & ~255;        // [32][XS]
+    static constexpr int xr = (ttop + (INTRA ? 2 * 64 * 16 : 0) + 255) & ~255;        // [32][XS]
     static constexpr int xw = xr + kTile * C::XS * 2;
-    static constexpr int yw = xw + kTile * C::XS * 2;                   // [32][YS] writer-Y rows, pair-interleaved columns
-    static constexpr int phw = yw + kTile * C::YS * 2;                  // [32][PST] writer assignments
+    static constexpr int yw = xw + (INTRA ? kTile * C::XS * 2 : 0);     // [32][YS] writer-Y rows, pair-interleaved columns
+    static constexpr int phw = yw + (INTRA ? kTile * C::YS * 2 : 0);    // [32][PST] writer assignments
     static constexpr int SS = 40;                                       // bf16 row stride of the output staging tiles
-    static constexpr int stg = phw + kTile * C::PST * 2;                // [NT][32][SS] bf16: dX tiles on their way out
+    static constexpr int stg = phw + (INTRA ? kTile * C::PST * 2 : 0);  // [NT][32][SS] bf16: dX tiles on their way out
     static constexpr int xr2 = stg + (G::TSPLIT == 1 ? C::NT * kTile * SS * 2 : 0);   // [32][XS]: second buffer of the reader rows (unit-norm
                                                                         // option: the dX wavefronts still read a tile's rows while the others
                                                                         // store the next tile's)
@@ -130,12 +131,21 @@ struct GradLds {
     static_assert(total <= 160 * 1024, "LDS budget");
 };
 
-template <class C, int SIDE, bool UNIT>
-__global__ __launch_bounds__(kThreads)
+// Wavefronts per SIMD the gradient kernel is compiled for.  The non-causal variant of a shape whose wavefronts carry
+// at most two accumulator tiles of statistics fits 128 registers and 80 KB of LDS, which lets two workgroups share a CU
+// (its tiles are independent of each other: nothing but latency to hide).
+template <class C, bool UNIT, bool INTRA>
+constexpr int grad_waves_per_simd()
+{
+    return (!INTRA && GradCfg<C>::MTG * C::NT <= 2 && GradLds<C, UNIT, INTRA>::total <= 80 * 1024) ? 4 : 2;
+}
+
+template <class C, int SIDE, bool UNIT, bool INTRA>
+__global__ __launch_bounds__(kThreads, (grad_waves_per_simd<C, UNIT, INTRA>()))
 void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, const bf16raw *O,
                  const float *den, const bf16raw *dO, bf16raw *dZ, bf16raw *dX)
 {
-    using S = GradLds<C, UNIT>;
+    using S = GradLds<C, UNIT, INTRA>;
     using G = GradCfg<C>;
     extern __shared__ __attribute__((aligned(256))) unsigned char lds[];
     bf16raw *wp = reinterpret_cast<bf16raw *>(lds + S::wp);
@@ -163,7 +173,7 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
     // backward pass through the soft assignment: the tables (or the share of one table) behind this wavefront's rows
     const int tl0 = (w * G::RW) / C::R;              // first table, counted inside the workgroup
     const int ro = (w * G::RW) % C::R;               // first corner of the share (0 unless a table spans several wavefronts)
-    const bool intra = a.causal;
+    constexpr bool intra = INTRA;
     // shapes with fewer than 8 x 32 bucket rows: only the first NRW wavefronts carry statistics; the others take
     // part in the production, the loads and dX
     const bool has_rows = G::NRW == kWaves || w < G::NRW;

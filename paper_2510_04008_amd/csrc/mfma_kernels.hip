@@ -648,8 +648,10 @@ hipError_t launch_grad(const Plan &p, KArgs a, const void *Q, const void *K, con
     // (the chain rule of the unit-norm option is applied where dX is formed, which a table split moves to dz_matmul_kernel)
     if (GradCfg<C>::TSPLIT > 1 && p.unit_qk) return hipErrorNotSupported;
     {
-        auto kern = p.unit_qk ? grad_kernel<C, SIDE, true> : grad_kernel<C, SIDE, false>;
-        const int lds = p.unit_qk ? GradLds<C, true>::total : GradLds<C, false>::total;
+        auto kern = p.causal ? (p.unit_qk ? grad_kernel<C, SIDE, true, true> : grad_kernel<C, SIDE, false, true>)
+                             : (p.unit_qk ? grad_kernel<C, SIDE, true, false> : grad_kernel<C, SIDE, false, false>);
+        const int lds = p.causal ? (p.unit_qk ? GradLds<C, true, true>::total : GradLds<C, false, true>::total)
+                                 : (p.unit_qk ? GradLds<C, true, false>::total : GradLds<C, false, false>::total);
         RACE_TRY(allow_lds(kern, lds));
         ProfileScope prof(SIDE == 0 ? "grad_q" : "grad_k", st);
         hipLaunchKernelGGL(kern, dim3(p.nseg, p.BH, GradCfg<C>::TSPLIT), dim3(kThreads), lds, st, a,
