@@ -199,7 +199,10 @@ struct StreamLds {
     static_assert(total <= 160 * 1024, "LDS budget");
 };
 
-template <class C, int MODE, bool UNIT>
+// NC: the non-causal variant only (the in-tile term and the update are compiled out, which frees registers); the
+// other variant reads the flag at run time (with the flag known to be set the compiler's schedule of the causal
+// kernels needed more registers: the 128-register shapes spilled).
+template <class C, int MODE, bool UNIT, bool NC>
 __global__ __launch_bounds__(kThreads, C::STREAM_WAVES_PER_SIMD)
 void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw *Y, const bf16raw *Oin,
                    const float *den_in, bf16raw *Out, float *den_out)
@@ -222,7 +225,7 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
     const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, ln = lane & 31, h = lane >> 5;
     const int rg = w % C::RG, cg = w / C::RG;
     const int r_own = rg * C::LRW, c_own = cg * C::DW;
-    const bool intra = a.causal;                      // the tile's own keys take part
+    const bool intra = NC ? false : a.causal != 0;    // causal: the tile's own keys take part
 
     const size_t base = static_cast<size_t>(bh) * a.N * C::D;
     Xr += base; Xw += base; Y += base; Out += base;
@@ -612,7 +615,8 @@ hipError_t launch_stream(const Plan &p, KArgs a, const void *Xr, const void *Xw,
                          const float *den_in, void *Out, float *den_out, hipStream_t st)
 {
     static const char *const names[] = {"stream_totals_kv", "stream_totals_qg", "stream_forward", "stream_grad_v"};
-    auto kern = p.unit_qk ? stream_kernel<C, MODE, true> : stream_kernel<C, MODE, false>;
+    auto kern = p.causal ? (p.unit_qk ? stream_kernel<C, MODE, true, false> : stream_kernel<C, MODE, false, false>)
+                         : (p.unit_qk ? stream_kernel<C, MODE, true, true> : stream_kernel<C, MODE, false, true>);
     RACE_TRY(allow_lds(kern, StreamLds<C>::total));
     ProfileScope prof(names[MODE], st);
     hipLaunchKernelGGL(kern, dim3(p.nseg, p.BH), dim3(kThreads), StreamLds<C>::total, st, a,
