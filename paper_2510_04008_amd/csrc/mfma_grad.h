@@ -78,16 +78,21 @@ struct GradCfg {
     // dX = dz . W of a tile is formed one step late, next to the production of the following tile, by the wavefronts
     // with the lightest production roles: first those without a role, then the in-tile term's, then writers,
     // readers last (the higher wavefront first within a class).  dx_tile(w) = column tile of wavefront w, or -1.
-    static constexpr int role_weight(int w)
+    // The non-causal variant has no writer and no in-tile term: its readers start at wavefront 0 and take one table of
+    // the lane each if the wavefronts suffice.
+    static constexpr int RJ_NC = NGW * C::TPL <= kWaves ? C::TPL : 1;
+    static constexpr int NR_NC = NGW * RJ_NC;
+    static constexpr int role_weight(int w, bool causal)
     {
+        if (!causal) return w < NR_NC ? 3 : 0;
         return (w >= RD0 && w < RD0 + NR) ? 3 : (w < NW ? 2 : (w == TT ? 1 : 0));
     }
-    static constexpr int dx_tile(int w)
+    static constexpr int dx_tile(int w, bool causal)
     {
         int taken = 0;
         for (int weight = 0; weight <= 3; ++weight) {
             for (int v = kWaves - 1; v >= 0; --v) {
-                if (role_weight(v) != weight) continue;
+                if (role_weight(v, causal) != weight) continue;
                 if (taken == C::NT) return -1;
                 if (v == w) return taken;
                 ++taken;
@@ -274,7 +279,7 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
     int my_dx = -1;
 #pragma unroll
     for (int v = 0; v < kWaves; ++v)
-        if (w == v) my_dx = G::dx_tile(v);
+        if (w == v) my_dx = G::dx_tile(v, INTRA);
     auto tile_xr = [&](int it) { return (UNIT && (it & 1)) ? reinterpret_cast<bf16raw *>(lds + S::xr2) : xr0; };
     auto tile_nrm = [&](int it) { return nrm0 + ((UNIT && (it & 1)) ? 2 * kTile : 0); };
 
@@ -330,13 +335,14 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
             write_assignments<C, C::PST>(zw, th * G::NGW + pg, ln, h, a.soft(), ln < nvalid, phw, pj, C::TPL, as * kShare,
                                  (as + 1) * kShare);
         }
-        if (w >= G::RD0 && w < G::RD0 + G::NR) {
-            const int pg = (w - G::RD0) % G::NGW, rj = (w - G::RD0) / G::NGW;
+        constexpr int kRd0 = INTRA ? G::RD0 : 0, kNr = INTRA ? G::NR : G::NR_NC, kRj = INTRA ? G::RJ : G::RJ_NC;
+        if (w >= kRd0 && w < kRd0 + kNr) {
+            const int pg = (w - kRd0) % G::NGW, rj = (w - kRd0) / G::NGW;
             const f32x16 zr = project<C>(wp, xr, th * G::NGW + pg, ln, h, UNIT ? nrm : nullptr);
 #pragma unroll
             for (int j = 0; j < C::TPL; ++j) {
                 if ((th * G::NGW + pg) * C::TPG + h * C::TPL + j >= C::L) break;
-                if (j % G::RJ != rj) continue;
+                if (j % kRj != rj) continue;
                 float p[C::PP], q[C::PP], s2[C::PP], u[C::PP], zz[C::PP];
 #pragma unroll
                 for (int t = 0; t < C::PP; ++t) {
