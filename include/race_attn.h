@@ -35,6 +35,9 @@
  *     aligned, at least race_attn_workspace_bytes() bytes; contents are scratch).  The
  *     library allocates no device memory, never synchronises the stream and launches all
  *     work on the given stream.  Calls that share a workspace must be stream-ordered.
+ *   - The host keeps one pinned image of the packed W per distinct (proj_seeds, H, d, L, P, dtype) for the life of
+ *     the process (asynchronous copies and captured graphs may read it at any time; a few KB to ~100 KB each).
+ *     The 4097th distinct combination in one process is refused with RACE_ERR_HIP.
  *   - Every argument is checked before anything is launched; on any error status other
  *     than RACE_ERR_HIP the outputs are untouched.  N == 0 is a valid no-op.
  *   - Arithmetic: products of bf16 operands are accumulated in fp32; the fp32 element
@@ -55,7 +58,9 @@ typedef enum {
     RACE_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, non-finite beta, bad enum   */
     RACE_ERR_UNSUPPORTED = 2, /* a valid shape outside what the kernels were built for         */
     RACE_ERR_WORKSPACE = 3,   /* workspace null, misaligned or smaller than required           */
-    RACE_ERR_HIP = 4          /* a HIP call failed; text from race_attn_last_error()           */
+    RACE_ERR_HIP = 4,         /* a HIP call failed; text from race_attn_last_error()           */
+    RACE_ERR_NOT_READY = 5    /* a call that prepares this one has not been made (see the entry
+                                 point); text from race_attn_last_error()                       */
 } race_status_t;
 
 typedef enum { RACE_F32 = 0, RACE_BF16 = 1 } race_dtype_t;
@@ -104,9 +109,8 @@ race_status_t race_attn_bwd(const race_attn_desc_t *desc, const void *Q, const v
                             const uint64_t *proj_seeds, void *dQ, void *dK, void *dV,
                             void *workspace, size_t workspace_bytes, race_stream_t stream);
 
-/* The same backward pass, which also returns the cotangent of the temperature: the paper trains beta
- * (Section 4, "we treat beta ... as a trainable parameter"), and with W fixed and random it is the layer's only
- * parameter.  The corner logits of Algorithm 1, step 4 are beta * (tanh(W x) . v_r), so
+/* The same backward pass, which also returns the cotangent of the temperature: the paper's experiments train
+ * beta (Section 4), and with W fixed and random it is the layer's only parameter.  The corner logits of Algorithm 1, step 4 are beta * (tanh(W x) . v_r), so
  * d(loss)/d(beta) = sum over Q and K tokens, tables and corners of dlogit_r * (tanh(W x) . v_r).
  * dbeta: DEVICE float (B, H), one partial derivative per (batch, head), written (not accumulated); the
  * derivative with respect to a beta shared by all of them is the sum of the entries.  NULL = not wanted, which
@@ -186,7 +190,8 @@ race_status_t race_attn_step(const race_attn_desc_t *desc, const void *q, const 
 /* Static, never-null description of a status code. */
 const char *race_status_string(race_status_t status);
 
-/* Text of the most recent HIP failure seen by the calling thread ("" if none). */
+/* Text of the most recent failure that has one, as seen by the calling thread ("" if none): the HIP error behind
+ * RACE_ERR_HIP, the reason for RACE_ERR_NOT_READY. */
 const char *race_attn_last_error(void);
 
 /* Which kernel family a descriptor is served by: 0 = invalid/unsupported, 1 = generic fp32-math

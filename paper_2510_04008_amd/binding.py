@@ -12,7 +12,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "librace_attn.so")
 
-RACE_OK, RACE_ERR_INVALID_ARG, RACE_ERR_UNSUPPORTED, RACE_ERR_WORKSPACE, RACE_ERR_HIP = range(5)
+RACE_OK, RACE_ERR_INVALID_ARG, RACE_ERR_UNSUPPORTED, RACE_ERR_WORKSPACE, RACE_ERR_HIP, RACE_ERR_NOT_READY = range(6)
 RACE_F32, RACE_BF16 = 0, 1
 
 
@@ -28,7 +28,7 @@ class RaceAttnError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
         text = lib().race_status_string(status).decode()
-        detail = lib().race_attn_last_error().decode() if status == RACE_ERR_HIP else ""
+        detail = lib().race_attn_last_error().decode() if status in (RACE_ERR_HIP, RACE_ERR_NOT_READY, RACE_ERR_WORKSPACE) else ""
         super().__init__("%s: %s%s" % (where, text, (" (" + detail + ")") if detail else ""))
 
 

@@ -50,11 +50,13 @@ struct Plan {
 // Validates desc and fills plan.  Returns RACE_OK, RACE_ERR_INVALID_ARG or RACE_ERR_UNSUPPORTED.
 race_status_t make_plan(const race_attn_desc_t *desc, Plan *plan);
 
-// Host: pinned, immutable image of W for (seeds, L, P, d, dtype) in the layout of `family`.
-// Returns nullptr if pinned memory cannot be allocated.
-const void *projection_image(const Plan &plan, const uint64_t *seeds, size_t *bytes);
-// Host: plain (H, L*P, d) expansion into caller memory.
-void expand_projection_host(int H, int L, int P, int d, int dtype, const uint64_t *seeds, float *out);
+// Host: pinned, immutable image of W for (seeds, L, P, d, dtype) in the layout of `family`.  Images live until the
+// process ends (a pending asynchronous copy or a captured graph may still read one), so the pointer stays valid.
+// may_allocate == false: only looks the image up.  Returns nullptr if the image is not there and may not be made,
+// if the cache is full (kMaxProjectionImages distinct keys) or if pinned memory cannot be allocated; *why then
+// names the reason (static string).
+constexpr size_t kMaxProjectionImages = 4096;
+const void *projection_image(const Plan &plan, const uint64_t *seeds, size_t *bytes, bool may_allocate, const char **why);
 
 // Brackets one kernel launch with HIP events on its stream while profiling is enabled (benchmark aid).
 struct ProfileScope {

@@ -80,7 +80,6 @@ struct CacheKey {
 struct CacheEntry { void *pinned; size_t bytes; };
 std::mutex g_cache_mutex;
 std::map<CacheKey, CacheEntry> g_cache;
-constexpr size_t kMaxCacheEntries = 64;
 
 }  // namespace
 
@@ -103,23 +102,31 @@ void expand_projection_host(int H, int L, int P, int d, int dtype, const uint64_
     }
 }
 
-const void *projection_image(const Plan &p, const uint64_t *seeds, size_t *bytes)
+// An image is never freed or moved once made: an asynchronous copy that was enqueued from it, or a captured graph
+// that holds such a copy, may read it at any later time.  The cache is therefore bounded by refusing new keys, not
+// by evicting old ones (an image is a few KB to ~100 KB).
+const void *projection_image(const Plan &p, const uint64_t *seeds, size_t *bytes, bool may_allocate, const char **why)
 {
     CacheKey key{p.family, p.dtype, p.H, p.L, p.P, p.d, std::vector<uint64_t>(seeds, seeds + p.H)};
     std::lock_guard<std::mutex> lock(g_cache_mutex);
     auto it = g_cache.find(key);
     if (it == g_cache.end()) {
-        if (g_cache.size() >= kMaxCacheEntries) {
-            // images may still be the source of an asynchronous copy: drain the device first
-            (void)hipDeviceSynchronize();
-            for (auto &e : g_cache) (void)hipHostFree(e.second.pinned);
-            g_cache.clear();
+        if (!may_allocate) {
+            *why = "the projection image of these seeds and this shape has not been prepared by an earlier call";
+            return nullptr;
+        }
+        if (g_cache.size() >= kMaxProjectionImages) {
+            *why = "projection image cache full (4096 distinct combinations of seeds and shape in this process)";
+            return nullptr;
         }
         std::vector<float> W(static_cast<size_t>(p.H) * p.LP * p.d);
         expand_projection_host(p.H, p.L, p.P, p.d, p.dtype, seeds, W.data());
         CacheEntry e;
         e.bytes = p.bytes_W;
-        if (hipHostMalloc(&e.pinned, e.bytes, hipHostMallocDefault) != hipSuccess) return nullptr;
+        if (hipHostMalloc(&e.pinned, e.bytes, hipHostMallocDefault) != hipSuccess) {
+            *why = "hipHostMalloc(projection image) failed";
+            return nullptr;
+        }
         if (p.family == kFamilyMfma) mfma_pack_projection(p, W.data(), e.pinned);
         else std::memcpy(e.pinned, W.data(), W.size() * sizeof(float));
         it = g_cache.emplace(std::move(key), e).first;
@@ -261,11 +268,15 @@ bool any_equal(std::initializer_list<const void *> outs, std::initializer_list<c
     return false;
 }
 
-race_status_t upload_projection(const Plan &p, const uint64_t *seeds, char *ws, hipStream_t st)
+race_status_t upload_projection(const Plan &p, const uint64_t *seeds, char *ws, hipStream_t st, bool may_allocate = true)
 {
     size_t bytes = 0;
-    const void *img = projection_image(p, seeds, &bytes);
-    if (!img) return hip_failed(hipErrorOutOfMemory, "hipHostMalloc(projection image)");
+    const char *why = "";
+    const void *img = projection_image(p, seeds, &bytes, may_allocate, &why);
+    if (!img) {
+        g_last_error = why;
+        return may_allocate ? RACE_ERR_HIP : RACE_ERR_NOT_READY;
+    }
     hipError_t e = hipMemcpyAsync(ws + p.off_W, img, bytes, hipMemcpyHostToDevice, st);
     if (e != hipSuccess) return hip_failed(e, "hipMemcpyAsync(projection image)");
     return RACE_OK;
@@ -503,6 +514,7 @@ const char *race_status_string(race_status_t status)
     case RACE_ERR_UNSUPPORTED: return "unsupported shape";
     case RACE_ERR_WORKSPACE: return "workspace null, misaligned or too small";
     case RACE_ERR_HIP: return "HIP call failed";
+    case RACE_ERR_NOT_READY: return "a call that prepares this one has not been made";
     }
     return "unknown status";
 }

@@ -26,8 +26,8 @@ def test_library_exports_every_declared_symbol():
 
 def test_status_strings():
     lib = ra.lib()
-    texts = [lib.race_status_string(i).decode() for i in range(6)]
-    assert texts[0] == "ok" and len(set(texts)) == 6 and all(texts)
+    texts = [lib.race_status_string(i).decode() for i in range(7)]
+    assert texts[0] == "ok" and len(set(texts)) == 7 and all(texts)
     assert lib.race_attn_last_error().decode() == ""
 
 
@@ -196,3 +196,4 @@ def test_decode_entry_points_check_arguments_on_the_host():
     assert lib.race_attn_state_init(ctypes.byref(d), p[0], p[1], seeds, None, ok_ws, 1 << 30, None) == E
     assert lib.race_attn_state_init(ctypes.byref(d), p[0], p[1], seeds, p[0], ok_ws, 1 << 30, None) == E
     assert lib.race_attn_state_init(ctypes.byref(d), p[0], p[1], seeds, p[2], ok_ws, 0, None) == ra.RACE_ERR_WORKSPACE
+
