@@ -99,6 +99,27 @@ race_status_t race_attn_fwd(const race_attn_desc_t *desc, const void *Q, const v
                             const uint64_t *proj_seeds, void *O, float *den,
                             void *workspace, size_t workspace_bytes, race_stream_t stream);
 
+/* For callers that cannot allocate (code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc): race_attn_fwd without a workspace argument.  The kernels are race_attn_fwd's; their scratch (the
+ * packed W and the per-segment bucket statistics) lives in an array of 32 MiB that is part of the library's code
+ * object, one copy per GPU, held until the process ends.  The call allocates nothing, on the host or on the device.
+ *   - Size limit: if the workspace race_attn_fwd would use exceeds the array, the sequence is cut into fewer, longer
+ *     scan segments (desc->chunk doubled as often as needed; O and den then differ from race_attn_fwd's by the
+ *     rounding of a different summation order only); a problem that does not fit even as one segment per
+ *     (batch, head) returns RACE_ERR_WORKSPACE.  At d = 128, L = 8, P = 6 a segment's statistics take 258 KiB, so
+ *     B*H*segments <= 126.
+ *   - The pinned host image of W for (proj_seeds, shape) must exist already, because making it allocates: any
+ *     earlier call of another entry point with the same H, d, L, P, dtype and proj_seeds (race_attn_fwd,
+ *     race_attn_debug_hash, ...) leaves it in the library's host cache for the life of the process.  Otherwise
+ *     RACE_ERR_NOT_READY, and nothing is launched.
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different streams or
+ *     threads) race; stream-ordered calls are fine.  Nothing in the array needs clearing between calls (every
+ *     element read by a kernel has been written earlier in the same call).
+ * Everything else (arguments, outputs, errors) is as for race_attn_fwd.  There is no race_attn_bwd_saved on this
+ * scratch: the next call overwrites it. */
+race_status_t race_attn_fwd_static(const race_attn_desc_t *desc, const void *Q, const void *K, const void *V,
+                                   const uint64_t *proj_seeds, void *O, float *den, race_stream_t stream);
+
 /* Backward pass of the same operator: given dO = d(loss)/dO, O and den from race_attn_fwd on the
  * same inputs, writes dQ, dK, dV.  The paper trains through the differentiable soft assignment
  * (Section 3.3) and prints no gradient; the formulas are the chain rule through Algorithms 1/2:
@@ -191,7 +212,7 @@ race_status_t race_attn_step(const race_attn_desc_t *desc, const void *q, const 
 const char *race_status_string(race_status_t status);
 
 /* Text of the most recent failure that has one, as seen by the calling thread ("" if none): the HIP error behind
- * RACE_ERR_HIP, the reason for RACE_ERR_NOT_READY. */
+ * RACE_ERR_HIP, the reason for RACE_ERR_NOT_READY, the limit behind race_attn_fwd_static's RACE_ERR_WORKSPACE. */
 const char *race_attn_last_error(void);
 
 /* Which kernel family a descriptor is served by: 0 = invalid/unsupported, 1 = generic fp32-math

@@ -51,6 +51,8 @@ def lib() -> ctypes.CDLL:
         L.race_attn_kernel_family.restype = ctypes.c_int
         L.race_attn_fwd.argtypes = [dp, vp, vp, vp, u64p, vp, fp, vp, ctypes.c_size_t, vp]
         L.race_attn_fwd.restype = ctypes.c_int
+        L.race_attn_fwd_static.argtypes = [dp, vp, vp, vp, u64p, vp, fp, vp]
+        L.race_attn_fwd_static.restype = ctypes.c_int
         L.race_attn_bwd.argtypes = [dp, vp, vp, vp, vp, fp, vp, u64p, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.race_attn_bwd.restype = ctypes.c_int
         L.race_attn_bwd_beta.argtypes = [dp, vp, vp, vp, vp, fp, vp, u64p, vp, vp, vp, fp, vp, ctypes.c_size_t, vp]
@@ -163,6 +165,19 @@ def race_attn_fwd(desc: RaceAttnDesc, Q, K, V, proj_seeds: Sequence[int], O=None
                              O.data_ptr(), den.data_ptr(), workspace.data_ptr(), nbytes, _stream(stream))
     if st != RACE_OK:
         raise RaceAttnError(st, "race_attn_fwd")
+    return O, den
+
+
+def race_attn_fwd_static(desc: RaceAttnDesc, Q, K, V, proj_seeds: Sequence[int], O, den, stream=None):
+    """race_attn_fwd on the library's built-in scratch array; the caller passes every output (nothing is allocated)."""
+    torch = _torch()
+    for t, n in ((Q, "Q"), (K, "K"), (V, "V"), (O, "O")):
+        _check_tensor(t, desc, n)
+    _check_tensor(den, desc, "den", (desc.B, desc.H, desc.N), torch.float32)
+    st = lib().race_attn_fwd_static(ctypes.byref(desc), Q.data_ptr(), K.data_ptr(), V.data_ptr(), _seeds(proj_seeds),
+                                    O.data_ptr(), den.data_ptr(), _stream(stream))
+    if st != RACE_OK:
+        raise RaceAttnError(st, "race_attn_fwd_static")
     return O, den
 
 

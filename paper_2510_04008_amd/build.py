@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librace_attn.so")
-SOURCES = ["race_api.cpp", "simple_kernels.hip", "mfma_kernels.hip"]
+SOURCES = ["race_api.cpp", "simple_kernels.hip", "mfma_kernels.hip", "static_scratch.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
     "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,

@@ -58,6 +58,12 @@ race_status_t make_plan(const race_attn_desc_t *desc, Plan *plan);
 constexpr size_t kMaxProjectionImages = 4096;
 const void *projection_image(const Plan &plan, const uint64_t *seeds, size_t *bytes, bool may_allocate, const char **why);
 
+// The library's own device scratch for race_attn_fwd_static (static_scratch.hip): a fixed array in the code object.
+constexpr size_t kStaticScratchBytes = static_cast<size_t>(32) << 20;
+hipError_t static_scratch(void **ptr);     // device address of the current device's copy
+// Host: plain (H, L*P, d) expansion into caller memory.
+void expand_projection_host(int H, int L, int P, int d, int dtype, const uint64_t *seeds, float *out);
+
 // Brackets one kernel launch with HIP events on its stream while profiling is enabled (benchmark aid).
 struct ProfileScope {
     ProfileScope(const char *name, hipStream_t st);

@@ -322,6 +322,47 @@ race_status_t race_attn_fwd(const race_attn_desc_t *desc, const void *Q, const v
     return e == hipSuccess ? RACE_OK : hip_failed(e, "race_attn_fwd launch");
 }
 
+// The forward pass on the library's own scratch array: same kernels, same arguments, no allocation of any kind.
+race_status_t race_attn_fwd_static(const race_attn_desc_t *desc, const void *Q, const void *K, const void *V,
+                                   const uint64_t *proj_seeds, void *O, float *den, race_stream_t stream)
+{
+    Plan p;
+    race_status_t s = make_plan(desc, &p);
+    if (s != RACE_OK) return s;
+    if (p.N == 0) return RACE_OK;
+    if (!Q || !K || !V || !proj_seeds || !O || !den) return RACE_ERR_INVALID_ARG;
+    if (any_equal({O, den}, {Q, K, V, O, den})) return RACE_ERR_INVALID_ARG;
+    // Fewer, longer scan segments until the forward's share of the workspace (W, the segment statistics and, for the
+    // generic kernels, the per-table partial results) fits the array; a caller's own desc->chunk is kept as the
+    // smallest segment length tried.
+    race_attn_desc_t fit = *desc;
+    for (;;) {
+        const size_t need = (p.family == kFamilyMfma) ? p.off_stateB : p.off_dbeta;
+        if (need <= kStaticScratchBytes) break;
+        if (p.nseg <= 1) {
+            g_last_error = "race_attn_fwd_static: the problem needs more than the 32 MiB of built-in scratch; use race_attn_fwd with a workspace";
+            return RACE_ERR_WORKSPACE;
+        }
+        fit.chunk = p.seg_len * 2;
+        if ((s = make_plan(&fit, &p)) != RACE_OK) return s;
+    }
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    // the image must be there already: making it would allocate pinned host memory
+    size_t bytes = 0;
+    const char *why = "";
+    if (!projection_image(p, proj_seeds, &bytes, false, &why)) {
+        g_last_error = std::string("race_attn_fwd_static: ") + why;
+        return RACE_ERR_NOT_READY;
+    }
+    void *scratch = nullptr;
+    hipError_t e = static_scratch(&scratch);
+    if (e != hipSuccess) return hip_failed(e, "hipGetSymbolAddress(static scratch)");
+    char *ws = static_cast<char *>(scratch);
+    if ((s = upload_projection(p, proj_seeds, ws, st, false)) != RACE_OK) return s;
+    e = (p.family == kFamilyMfma) ? mfma_fwd(p, Q, K, V, O, den, ws, st) : simple_fwd(p, Q, K, V, O, den, ws, st);
+    return e == hipSuccess ? RACE_OK : hip_failed(e, "race_attn_fwd_static launch");
+}
+
 race_status_t race_attn_bwd(const race_attn_desc_t *desc, const void *Q, const void *K, const void *V,
                             const void *O, const float *den, const void *dO, const uint64_t *proj_seeds,
                             void *dQ, void *dK, void *dV, void *workspace, size_t workspace_bytes,

@@ -197,3 +197,26 @@ def test_decode_entry_points_check_arguments_on_the_host():
     assert lib.race_attn_state_init(ctypes.byref(d), p[0], p[1], seeds, p[0], ok_ws, 1 << 30, None) == E
     assert lib.race_attn_state_init(ctypes.byref(d), p[0], p[1], seeds, p[2], ok_ws, 0, None) == ra.RACE_ERR_WORKSPACE
 
+
+def test_forward_on_built_in_scratch_checks_everything_on_the_host():
+    """race_attn_fwd_static (for callers that cannot allocate) validates like race_attn_fwd, refuses seeds whose pinned
+    image no earlier call has made (making it would allocate) and problems beyond its 32 MiB array: all before any
+    device call, so this runs without a GPU."""
+    lib = ra.lib()
+    d = _desc()
+    p = [ctypes.c_void_p(256 * (i + 1)) for i in range(6)]
+    seeds = (ctypes.c_uint64 * 2)(0xABCDEF12345, 77)          # used nowhere else in this process
+    E = ra.RACE_ERR_INVALID_ARG
+    assert lib.race_attn_fwd_static(None, p[0], p[1], p[2], seeds, p[3], p[4], None) == E
+    assert lib.race_attn_fwd_static(ctypes.byref(d), None, p[1], p[2], seeds, p[3], p[4], None) == E
+    assert lib.race_attn_fwd_static(ctypes.byref(d), p[0], p[1], p[2], None, p[3], p[4], None) == E
+    assert lib.race_attn_fwd_static(ctypes.byref(d), p[0], p[1], p[2], seeds, p[1], p[4], None) == E
+    assert lib.race_attn_fwd_static(ctypes.byref(_desc(P=9)), p[0], p[1], p[2], seeds, p[3], p[4], None) == ra.RACE_ERR_UNSUPPORTED
+    assert lib.race_attn_fwd_static(ctypes.byref(_desc(N=0)), None, None, None, None, None, None, None) == ra.RACE_OK
+    assert lib.race_attn_fwd_static(ctypes.byref(d), p[0], p[1], p[2], seeds, p[3], p[4], None) == ra.RACE_ERR_NOT_READY
+    assert b"not been prepared" in lib.race_attn_last_error()
+    # 200 heads of the headline shape need 200 x 258 KiB of statistics even with one segment each
+    big = ra.make_desc(1, 200, 4096, 128, 8, 6, 8.0, True, ra.RACE_BF16)
+    many = (ctypes.c_uint64 * 200)(*range(200))
+    assert lib.race_attn_fwd_static(ctypes.byref(big), p[0], p[1], p[2], many, p[3], p[4], None) == ra.RACE_ERR_WORKSPACE
+    assert b"32 MiB" in lib.race_attn_last_error()
