@@ -219,6 +219,12 @@ const char *race_attn_last_error(void);
  * kernels, 2 = bf16 MFMA kernels.  Informational (benchmarks and tests report it). */
 int race_attn_kernel_family(const race_attn_desc_t *desc);
 
+/* Tokens per scan segment the library uses for this descriptor (desc->chunk rounded to what the kernels take, or
+ * the library's own choice for chunk = 0): segment s covers tokens [s * len, min(N, (s + 1) * len)), and the
+ * statistics at segment boundaries are what the prefix scan of Algorithm 2's cumulative arrays hands from one
+ * workgroup to the next.  Informational (tests place their windows across these boundaries).  0 = invalid. */
+int64_t race_attn_segment_tokens(const race_attn_desc_t *desc);
+
 /* Benchmark aid (no passage of the paper; callers: benchmarks and profilers).  While enabled for the
  * calling thread, every kernel the library launches is bracketed by a pair of HIP events recorded on the
  * call's own stream.  race_attn_profile_read() waits for the recorded events, adds up the elapsed time per

@@ -79,11 +79,16 @@ static void soft_hash_vjp(const double *Wl, int d, int P, double beta, const dou
 
 int race_oracle_threads(void) { return oracle_threads(); }
 
-/* Forward.  Returns 0 on success, 1 on allocation failure. */
-int race_oracle_forward(int B, int H, long N, int d, int L, int P, double beta, int causal,
-                        const double *Q, const double *K, const double *V, const double *W,
-                        double *O, double *den)
+/* Forward.  Returns 0 on success, 1 on allocation failure, 2 on a bad argument.
+ * state: NULL, or (B*H, L, R, d+1) doubles, per bucket row the d value sums then the mass (Algorithm 2's
+ * cumulative arrays): the scan starts from it and leaves the arrays after the last token there, so that a long
+ * sequence can be run slice by slice in bounded memory (causal only: Algorithm 1's statistics are over all N).
+ * The additions are the same, in the same order, whether a sequence is run whole or in slices. */
+int race_oracle_forward_carry(int B, int H, long N, int d, int L, int P, double beta, int causal,
+                              const double *Q, const double *K, const double *V, const double *W,
+                              double *state, double *O, double *den)
 {
+    if (state && !causal) return 2;
     const int R = 1 << P;
     const int BH = B * H;
     int group = (oracle_threads() + L - 1) / L;       /* heads processed together */
@@ -104,12 +109,14 @@ int race_oracle_forward(int B, int H, long N, int d, int L, int P, double beta, 
                 const double *v = V + (size_t)bh * N * d;
                 const double *Wl = W + ((size_t)h * L + l) * P * d;
                 double *out = part + ((size_t)gi * L + l) * per_tab;   /* [N][d+1]: num | den */
-                double *A = (double *)calloc((size_t)R * (d + 1), sizeof(double));
+                double *A = state ? state + ((size_t)bh * L + l) * R * (d + 1)
+                                  : (double *)calloc((size_t)R * (d + 1), sizeof(double));
                 double *phi = (double *)malloc(sizeof(double) * (R + P));
                 if (!A || !phi) {
 #pragma omp atomic write
                     fail = 1;
-                    free(A); free(phi);
+                    if (!state) free(A);
+                    free(phi);
                     continue;
                 }
                 double *u = phi + R;
@@ -140,7 +147,8 @@ int race_oracle_forward(int B, int H, long N, int d, int L, int P, double beta, 
                         for (int c = 0; c <= d; ++c) o[c] += phi[r] * row[c];
                     }
                 }
-                free(A); free(phi);
+                if (!state) free(A);
+                free(phi);
             }
         }
         /* Num = (1/L) sum_l num_l, Den = (1/L) sum_l den_l, O = Num / Den */
@@ -166,13 +174,27 @@ int race_oracle_forward(int B, int H, long N, int d, int L, int P, double beta, 
     return fail;
 }
 
-/* Backward of loss = sum(dO * O).  O and den are the oracle's own forward results.
- * dbeta: (B*H) cotangents of the temperature, one per (batch, head). */
-int race_oracle_backward(int B, int H, long N, int d, int L, int P, double beta, int causal,
-                         const double *Q, const double *K, const double *V, const double *W,
-                         const double *O, const double *den, const double *dO,
-                         double *dQ, double *dK, double *dV, double *dbeta)
+int race_oracle_forward(int B, int H, long N, int d, int L, int P, double beta, int causal,
+                        const double *Q, const double *K, const double *V, const double *W,
+                        double *O, double *den)
 {
+    return race_oracle_forward_carry(B, H, N, d, L, P, beta, causal, Q, K, V, W, NULL, O, den);
+}
+
+/* Backward of loss = sum(dO * O), given O and den of the forward pass on the same inputs.
+ * dbeta: (B*H) cotangents of the temperature, one per (batch, head).
+ * Slices of a long causal sequence: S_state / dS_state are NULL or (B*H, L, R, d+1) doubles, the prefix statistics
+ * (B | A) before the slice's first token and the suffix statistics (dB | dA) of the read-out cotangents after its
+ * last token; each pass starts from its array and leaves it advanced over the slice.  do_query runs pass 1 (dQ),
+ * do_keyvalue pass 2 (dK, dV): a sliced run sweeps the slices left to right with do_query, then right to left with
+ * do_keyvalue.  A pass that is not run leaves zeros in its outputs, and dbeta holds the share of the passes run. */
+int race_oracle_backward_carry(int B, int H, long N, int d, int L, int P, double beta, int causal,
+                               const double *Q, const double *K, const double *V, const double *W,
+                               const double *O, const double *den, const double *dO,
+                               double *S_state, double *dS_state, int do_query, int do_keyvalue,
+                               double *dQ, double *dK, double *dV, double *dbeta)
+{
+    if ((S_state || dS_state || !do_query || !do_keyvalue) && !causal) return 2;
     const int R = 1 << P;
     const int BH = B * H;
     int group = (oracle_threads() + L - 1) / L;
@@ -212,13 +234,16 @@ int race_oracle_backward(int B, int H, long N, int d, int L, int P, double beta,
                 double *pQ = part + (((size_t)gi * L + l) * 3 + 0) * per_tab;
                 double *pK = part + (((size_t)gi * L + l) * 3 + 1) * per_tab;
                 double *pV = part + (((size_t)gi * L + l) * 3 + 2) * per_tab;
-                double *S = (double *)calloc((size_t)R * (d + 1), sizeof(double));    /* B | A  */
-                double *dS = (double *)calloc((size_t)R * (d + 1), sizeof(double));   /* dB | dA */
+                const size_t soff = ((size_t)bh * L + l) * R * (d + 1);
+                double *S = S_state ? S_state + soff : (double *)calloc((size_t)R * (d + 1), sizeof(double));      /* B | A  */
+                double *dS = dS_state ? dS_state + soff : (double *)calloc((size_t)R * (d + 1), sizeof(double));   /* dB | dA */
                 double *phi = (double *)malloc(sizeof(double) * (2 * R + P));
                 if (!S || !dS || !phi) {
 #pragma omp atomic write
                     fail = 1;
-                    free(S); free(dS); free(phi);
+                    if (!S_state) free(S);
+                    if (!dS_state) free(dS);
+                    free(phi);
                     continue;
                 }
                 double *dphi = phi + R, *u = phi + 2 * R;
@@ -239,7 +264,7 @@ int race_oracle_backward(int B, int H, long N, int d, int L, int P, double beta,
                     }
                 }
                 /* pass 1, left to right: prefix statistics -> cotangent of phi_Q -> dQ */
-                for (long i = 0; i < N; ++i) {
+                for (long i = 0; do_query && i < N; ++i) {
                     if (causal) {
                         soft_hash(k + i * d, Wl, d, P, beta, u, phi);
                         for (int r = 0; r < R; ++r) {
@@ -258,7 +283,7 @@ int race_oracle_backward(int B, int H, long N, int d, int L, int P, double beta,
                     soft_hash_vjp(Wl, d, P, beta, u, phi, dphi, pQ + i * d, &db);
                 }
                 /* pass 2, right to left: suffix statistics of the read-out cotangents -> dV, dK */
-                for (long j = N - 1; j >= 0; --j) {
+                for (long j = N - 1; do_keyvalue && j >= 0; --j) {
                     if (causal) {
                         soft_hash(q + j * d, Wl, d, P, beta, u, phi);
                         for (int r = 0; r < R; ++r) {
@@ -279,7 +304,9 @@ int race_oracle_backward(int B, int H, long N, int d, int L, int P, double beta,
                     soft_hash_vjp(Wl, d, P, beta, u, phi, dphi, pK + j * d, &db);
                 }
                 pbeta[(size_t)gi * L + l] = db;
-                free(S); free(dS); free(phi);
+                if (!S_state) free(S);
+                if (!dS_state) free(dS);
+                free(phi);
             }
         }
 #pragma omp parallel for collapse(2) schedule(static)
@@ -306,4 +333,13 @@ int race_oracle_backward(int B, int H, long N, int d, int L, int P, double beta,
     }
     free(part); free(gn); free(pbeta);
     return fail;
+}
+
+int race_oracle_backward(int B, int H, long N, int d, int L, int P, double beta, int causal,
+                         const double *Q, const double *K, const double *V, const double *W,
+                         const double *O, const double *den, const double *dO,
+                         double *dQ, double *dK, double *dV, double *dbeta)
+{
+    return race_oracle_backward_carry(B, H, N, d, L, P, beta, causal, Q, K, V, W, O, den, dO, NULL, NULL, 1, 1,
+                                      dQ, dK, dV, dbeta);
 }

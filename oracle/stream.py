@@ -23,6 +23,10 @@ def _load():
         lib.race_oracle_forward.restype = ctypes.c_int
         lib.race_oracle_backward.argtypes = common + [dp] * 11
         lib.race_oracle_backward.restype = ctypes.c_int
+        lib.race_oracle_forward_carry.argtypes = common + [dp] * 7
+        lib.race_oracle_forward_carry.restype = ctypes.c_int
+        lib.race_oracle_backward_carry.argtypes = common + [dp] * 9 + [ctypes.c_int, ctypes.c_int] + [dp] * 4
+        lib.race_oracle_backward_carry.restype = ctypes.c_int
         lib.race_oracle_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -66,3 +70,46 @@ def backward(Q, K, V, W, beta, L, P, causal, O, den, dO, with_beta: bool = False
     if rc:
         raise MemoryError("race_oracle_backward")
     return (dQ, dK, dV, dbeta) if with_beta else (dQ, dK, dV)
+
+
+def new_state(B, H, L, P, d):
+    """Zeroed carried statistics (B, H, L, R, d+1): per bucket row the d sums, then the mass."""
+    return np.zeros((B, H, L, 1 << P, d + 1))
+
+
+def forward_slice(Q, K, V, W, beta, L, P, state):
+    """Causal forward over one slice of a longer sequence (Algorithm 2 continued): starts from `state` (updated in
+    place to the statistics after the slice's last token).  Returns O and Den of the slice."""
+    Q, K, V, W = _c(Q), _c(K), _c(V), _c(W)
+    B, H, N, d = Q.shape
+    assert state.shape == (B, H, L, 1 << P, d + 1) and state.dtype == np.float64 and state.flags.c_contiguous
+    O = np.empty_like(Q)
+    den = np.empty((B, H, N))
+    rc = _load().race_oracle_forward_carry(B, H, N, d, L, P, float(beta), 1, _p(Q), _p(K), _p(V), _p(W), _p(state),
+                                           _p(O), _p(den))
+    if rc:
+        raise MemoryError("race_oracle_forward_carry rc=%d" % rc)
+    return O, den
+
+
+def backward_slice(Q, K, V, W, beta, L, P, O, den, dO, prefix_state=None, suffix_state=None):
+    """Causal backward over one slice.  prefix_state given: runs the query pass from it (the statistics of the keys
+    and values before the slice; advanced in place) and returns dQ.  suffix_state given: runs the key/value pass
+    from it (the statistics of the read-out cotangents after the slice; advanced in place) and returns dK, dV.
+    Returns (dQ or None, dK or None, dV or None)."""
+    Q, K, V, W, O, den, dO = map(_c, (Q, K, V, W, O, den, dO))
+    B, H, N, d = Q.shape
+    for st in (prefix_state, suffix_state):
+        assert st is None or (st.shape == (B, H, L, 1 << P, d + 1) and st.dtype == np.float64 and st.flags.c_contiguous)
+    dQ, dK, dV = np.empty_like(Q), np.empty_like(Q), np.empty_like(Q)
+    dbeta = np.zeros((B, H))
+    null = ctypes.POINTER(ctypes.c_double)()
+    rc = _load().race_oracle_backward_carry(B, H, N, d, L, P, float(beta), 1, _p(Q), _p(K), _p(V), _p(W), _p(O), _p(den),
+                                            _p(dO), _p(prefix_state) if prefix_state is not None else null,
+                                            _p(suffix_state) if suffix_state is not None else null,
+                                            int(prefix_state is not None), int(suffix_state is not None),
+                                            _p(dQ), _p(dK), _p(dV), _p(dbeta))
+    if rc:
+        raise MemoryError("race_oracle_backward_carry rc=%d" % rc)
+    return (dQ if prefix_state is not None else None, dK if suffix_state is not None else None,
+            dV if suffix_state is not None else None)

@@ -49,6 +49,8 @@ def lib() -> ctypes.CDLL:
         L.race_attn_workspace_bytes.restype = ctypes.c_size_t
         L.race_attn_kernel_family.argtypes = [dp]
         L.race_attn_kernel_family.restype = ctypes.c_int
+        L.race_attn_segment_tokens.argtypes = [dp]
+        L.race_attn_segment_tokens.restype = ctypes.c_int64
         L.race_attn_fwd.argtypes = [dp, vp, vp, vp, u64p, vp, fp, vp, ctypes.c_size_t, vp]
         L.race_attn_fwd.restype = ctypes.c_int
         L.race_attn_fwd_static.argtypes = [dp, vp, vp, vp, u64p, vp, fp, vp]
@@ -138,6 +140,10 @@ def race_attn_workspace_bytes(desc: RaceAttnDesc) -> int:
 
 def race_attn_kernel_family(desc: RaceAttnDesc) -> int:
     return int(lib().race_attn_kernel_family(ctypes.byref(desc)))
+
+
+def race_attn_segment_tokens(desc: RaceAttnDesc) -> int:
+    return int(lib().race_attn_segment_tokens(ctypes.byref(desc)))
 
 
 def race_attn_expand_projection(desc: RaceAttnDesc, proj_seeds: Sequence[int]) -> np.ndarray:

@@ -303,6 +303,13 @@ int race_attn_kernel_family(const race_attn_desc_t *desc)
     return p.family;
 }
 
+int64_t race_attn_segment_tokens(const race_attn_desc_t *desc)
+{
+    Plan p;
+    if (make_plan(desc, &p) != RACE_OK) return 0;
+    return p.seg_len;
+}
+
 race_status_t race_attn_fwd(const race_attn_desc_t *desc, const void *Q, const void *K, const void *V,
                             const uint64_t *proj_seeds, void *O, float *den, void *workspace,
                             size_t workspace_bytes, race_stream_t stream)

@@ -1,9 +1,7 @@
 """GPU parity of the bf16 MFMA kernel family against the fp64 oracle, through the C ABI.
 
-Small and medium cases are compared element by element.  The long-context configurations are run
-at full size in the launch configuration the benchmark times, and checked (a) on a prefix, which in
-the causal case depends on no later token, against the oracle, and (b) through properties that hold
-at any size.
+Small and medium cases are compared element by element (the long-context configurations at full size are in
+test_gpu_long_context.py).
 """
 import numpy as np
 import pytest
@@ -131,63 +129,11 @@ def test_determinism_and_invariants():
     assert leak["O"][:, :, :1700].abs().max().item() == 0.0                   # nothing flows from the future
 
 
-def _long_context(w, n0):
-    """Full-size run in the benchmark's launch configuration; prefix parity and size-free properties."""
-    assert _is_mfma(w)
-    Q, K, V, dO = synth.make_inputs(w, "cuda", on_device_rng=True)
-    g = run_gpu(w, (Q, K, V, dO), saved=True)
-    W = oracle_w(w, g["seeds"])
-    host = [to_f64(t[:, :, :n0]) for t in (Q, K, V, dO)]
-    O, den = oracle_stream.forward(host[0], host[1], host[2], W, w.sharpening, w.L, w.P, True)
-    dQ = oracle_stream.backward(host[0], host[1], host[2], W, w.sharpening, w.L, w.P, True, O, den, host[3])[0]
-    errs = dict(O=rel_err(g["O"][:, :, :n0], O), den=rel_err(g["den"][:, :, :n0], den), dQ=rel_err(g["dQ"][:, :, :n0], dQ))
-    print(w.name, "prefix %d:" % n0, " ".join("%s=%.2e" % kv for kv in errs.items()), flush=True)
-    for n, e in errs.items():
-        assert e < TOL["bf16"], (n, e)
-    # the same ratio per 1024-token block near the end of the prefix (late rows of O are small)
-    blk = slice(n0 - 1024, n0)
-    assert rel_err(g["O"][:, :, blk], O[:, :, blk]) < TOL["bf16"]
-    for n in ("O", "den", "dQ", "dK", "dV"):
-        assert torch.isfinite(g[n][:, :, ::4097].float()).all(), n
-    assert (g["den"][:, :, ::1000] > 0).all()
-    # rows of the attention matrix sum to one: total value gradient equals total upstream gradient
-    tot = torch.zeros((w.B, w.H, w.d), dtype=torch.float64, device="cuda")
-    ref = torch.zeros_like(tot)
-    step = 1 << 20
-    for s in range(0, w.N, step):
-        tot += g["dV"][:, :, s:s + step].double().sum(dim=2)
-        ref += dO[:, :, s:s + step].double().sum(dim=2)
-    scale = dO.float().abs().max().item() * (w.N ** 0.5)
-    assert (tot - ref).abs().max().item() < 2e-2 * scale
-    del g
-    # constant values come back as that constant at every position
-    V.fill_(1.0)
-    d = desc_of(w)
-    O1, _ = ra.race_attn_fwd(d, Q, K, V, synth.projection_seeds(w))
-    torch.cuda.synchronize()
-    for s in range(0, w.N, step):
-        assert (O1[:, :, s:s + step].float() - 1.0).abs().max().item() < 1e-2
-
-
-def test_config4_causal_4m_tokens_sampled():
-    _long_context(synth.C4, 16384)
-
-
-def test_config5_causal_12m_tokens_sampled():
-    _long_context(synth.C5, 16384)
-
-
-@pytest.mark.parametrize("w", [synth.G22, synth.G44], ids=lambda w: w.name)
-def test_paper_grid_1m_tokens_sampled(w):
-    # the paper's own scaling grid at N = 2^20, on the padded 64-row shape, in the benchmark's launch configuration
-    _long_context(w, 16384)
-
-
 def test_beta_cotangent_headline_shape():
     from parity_util import check_dbeta
     check_dbeta(Workload("m-beta-1", 1, 2, 1000, 128, 8, 6, 8.0, True, "bf16", normalize_qk=True, chunk=256))
     # raw N(0,1) rows saturate three quarters of the bits: ~75 000 terms of both signs cancel to a sum of order one
-    check_dbeta(Workload("m-beta-2", 1, 2, 777, 128, 8, 6, 8.0, True, "bf16", chunk=256), scale="l1")
+    check_dbeta(Workload("m-beta-2", 1, 2, 777, 128, 8, 6, 8.0, True, "bf16", chunk=256))
     check_dbeta(Workload("m-beta-3", 1, 2, 1000, 128, 8, 6, 8.0, False, "bf16", normalize_qk=True, chunk=256))
 
 

@@ -32,20 +32,10 @@ def test_padded_shapes_forward_backward(P, L, d, causal):
 
 def test_padded_shape_raw_inputs_and_batch():
     # raw N(0,1) rows (|z| ~ 11: saturated tanh).  At beta = 8 and only 4 x 16 buckets the first few causal tokens
-    # can have Den ~ 1e-9 (query and the handful of keys before it share no bucket): their gradients are zero or
-    # tiny by cancellation of terms scaled by 1/Den, and the bf16 operands leave a residue of 2^-9 of those terms.
-    # Beyond the first 64 tokens the tensors' tolerance holds; the whole tensor is checked at beta = 2.
+    # have Den ~ 1e-9 (query and the handful of keys before it share no bucket); every token is compared
     w = Workload("pad-raw", 2, 3, 1000, 128, 4, 4, 8.0, True, "bf16", chunk=128)
     assert ra.race_attn_kernel_family(desc_of(w)) == 2
-    from parity_util import run_gpu, run_oracle
-    g = run_gpu(w)
-    r = run_oracle(w, g)
-    for n in ("O", "den", "dV"):
-        assert np.abs(to_f64(g[n]) - r[n]).max() < TOL["bf16"] * np.abs(r[n]).max(), n
-    for n in ("dQ", "dK"):
-        err = np.abs(to_f64(g[n]) - r[n])[:, :, 64:].max()
-        print("pad-raw %s beyond token 64: %.2e" % (n, err / np.abs(r[n]).max()), flush=True)
-        assert err < TOL["bf16"] * np.abs(r[n]).max(), n
+    check_case(w)
     check_case(Workload("pad-raw-beta2", 2, 3, 1000, 128, 4, 4, 2.0, True, "bf16", chunk=128))
 
 
@@ -77,8 +67,8 @@ def test_padded_shape_taps_report_the_problems_own_corners():
 def test_padded_shape_beta_cotangent_and_decode_prefill():
     # a mild temperature: the terms do not cancel much and the tensors' measure applies
     check_dbeta(Workload("pad-beta-mild", 1, 2, 900, 128, 4, 4, 1.0, True, "bf16", normalize_qk=True, chunk=256))
-    check_dbeta(Workload("pad-beta", 1, 2, 900, 128, 4, 4, 4.0, True, "bf16", normalize_qk=True, chunk=256), scale="l1")
-    check_dbeta(Workload("pad-beta-33", 1, 2, 900, 128, 3, 3, 4.0, False, "bf16", normalize_qk=True), scale="l1")
+    check_dbeta(Workload("pad-beta", 1, 2, 900, 128, 4, 4, 4.0, True, "bf16", normalize_qk=True, chunk=256))
+    check_dbeta(Workload("pad-beta-33", 1, 2, 900, 128, 3, 3, 4.0, False, "bf16", normalize_qk=True))
     # the decoding state of a padded problem has the problem's own shape
     w = Workload("pad-state", 1, 2, 600, 128, 3, 3, 4.0, True, "bf16", normalize_qk=True)
     _, K, V, _ = synth.make_inputs(w, "cuda")

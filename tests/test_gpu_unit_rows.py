@@ -69,7 +69,7 @@ def test_backward_on_the_forward_workspace():
     W_("unit-dbeta-headline", 1, 2, 600, 128, 8, 6, 2.0, True, "bf16", chunk=256),
 ], ids=lambda w: w.name)
 def test_temperature_cotangent(w):
-    check_dbeta(w, scale="l1")
+    check_dbeta(w)
 
 
 @pytest.mark.parametrize("w", [
