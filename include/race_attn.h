@@ -106,8 +106,8 @@ race_status_t race_attn_fwd(const race_attn_desc_t *desc, const void *Q, const v
  *   - Size limit: if the workspace race_attn_fwd would use exceeds the array, the sequence is cut into fewer, longer
  *     scan segments (desc->chunk doubled as often as needed; O and den then differ from race_attn_fwd's by the
  *     rounding of a different summation order only); a problem that does not fit even as one segment per
- *     (batch, head) returns RACE_ERR_WORKSPACE.  At d = 128, L = 8, P = 6 a segment's statistics take 258 KiB, so
- *     B*H*segments <= 126.
+ *     (batch, head) returns RACE_ERR_WORKSPACE.  At d = 128, L = 8, P = 6 (bf16) a segment's statistics take 258 KiB
+ *     and the hashed rows of Q and K 384 bytes per token and head: B*H*(segments * 258 KiB + N * 384 B) < 32 MiB.
  *   - The pinned host image of W for (proj_seeds, shape) must exist already, because making it allocates: any
  *     earlier call of another entry point with the same H, d, L, P, dtype and proj_seeds (race_attn_fwd,
  *     race_attn_debug_hash, ...) leaves it in the library's host cache for the life of the process.  Otherwise

@@ -38,12 +38,16 @@ struct Plan {
     size_t bytes_state;
     size_t off_part;    // per-table partial results (simple family only)
     size_t bytes_part;
+    size_t off_massQ;   // MFMA family: the hashed rows of Q and of K, (BH, N, Lc * Pc) fp32 each (one float per token,
+    size_t off_massK;   // table and hyperplane: the per-bit soft-hash masses every pass rebuilds phi from)
+    size_t bytes_mass;
+    size_t fwd_bytes;   // the leading part of the workspace that the forward pass uses
     size_t off_dbeta;   // partial cotangents of beta: (2 sides, BH, dbeta_parts) fp32, backward only
     size_t bytes_dbeta;
     int dbeta_parts;    // partial sums per (side, batch*head): one per workgroup of the gradient kernels
     size_t total;
-    // backward only: the workspace still holds the forward's projection image and segment-start key/value
-    // statistics (set by race_attn_bwd_saved for the families that can use them)
+    // backward only: the workspace still holds the forward's projection image, hashed rows and segment-start
+    // key/value statistics (set by race_attn_bwd_saved for the families that can use them)
     int fwd_state_kept;
 };
 
@@ -103,7 +107,7 @@ hipError_t zero_floats(float *dst, size_t n, hipStream_t st);
 #endif
 // The exact shape if compiled, else the padded instantiation with the fewest bucket rows that covers (d, L, P).
 bool mfma_pick(int d, int L, int P, int *Lc, int *Pc, int *pad);
-size_t mfma_scratch_bytes(const Plan &p);      // backward-pass scratch beyond the two state areas
+size_t mfma_hashed_bytes(const Plan &p);       // bytes of the hashed rows of one tensor
 size_t mfma_projection_bytes(const Plan &p);
 void mfma_pack_projection(const Plan &p, const float *W, void *image);   // host
 hipError_t mfma_fwd(const Plan &p, const void *Q, const void *K, const void *V, void *O, float *den,

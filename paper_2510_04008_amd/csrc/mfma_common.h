@@ -83,6 +83,12 @@ struct Cfg {
                                                         // 16-byte row writes and transposing reads both 2-way at most)
     static constexpr int ZS = LPP + 8;                  // [token][padded projection] tiles
     static constexpr int STATE = LR * (D + 1);          // floats per saved state: B [LR][D] then A [LR]
+    // hashed form of a row (see bit_code()): one float per (table, hyperplane), L * P per token
+    static constexpr int LP = L * P;
+    static constexpr int MS = LP + 2;                   // [token][LP] tiles of them in LDS: an even stride whose half is odd keeps the 8-byte
+                                                        // reads of 32 consecutive tokens on distinct banks
+    static constexpr int MCH = LP / 4;                  // 16-byte chunks per token
+    static_assert(P % 2 == 0 && LP % 4 == 0 && (MS / 2) % 2 == 1, "hashed rows are read as pairs of floats");
     static_assert(RG >= 1 && LR % (32 * RG) == 0 && NT % CG == 0 && NTW >= 1, "bucket rows and columns over the wavefronts");
     static_assert(D % 64 == 0 && P >= 4, "shape (assignments are written for pairs of high-bit indices)");
     static_assert(4 % NG == 0 && NG <= 4, "projection groups must divide four wavefronts");
@@ -120,7 +126,7 @@ struct KArgs {
     const bf16raw *Wp;     // (H, LPP, D) bf16, rows in projection-group order
     const bf16raw *WpT;    // (H, D, LPP) bf16
     float *state;          // (BH, nseg, STATE) fp32
-    bf16raw *dZ;           // (BH, N, LPP) bf16: cotangents of the projections (backward only)
+    float *Mq, *Mk;        // (BH, N, L * P) fp32: the hashed rows of Q and K (hash_kernel writes them, every later pass reads them)
     float *dbeta_part;     // (2, BH, workgroups per head-batch) fp32: partial cotangents of beta (backward only)
 };
 
@@ -214,9 +220,10 @@ __device__ __forceinline__ u32x4 lds_tr_acc(const bf16raw *M, int stride, int k0
 // ---------------------------------------------------------------- global -> registers -> LDS tiles
 // A tile of ROWS rows is ROWS*CPR chunks of 16 bytes; thread t owns chunks t, t + 512, ...  Loads are
 // issued ahead of use (fetch) and written to LDS later (store), so that HBM latency overlaps arithmetic.
-template <class C, int ROWS>
+// (NTHR: the threads that share the tile, the first NTHR of the workgroup)
+template <class C, int ROWS, int NTHR = kThreads>
 struct RowChunks {
-    static constexpr int N = (ROWS * C::CPR + kThreads - 1) / kThreads;
+    static constexpr int N = (ROWS * C::CPR + NTHR - 1) / NTHR;
     u32x4 v[N];
 };
 
@@ -226,13 +233,13 @@ struct RowChunks {
 // SBASE: the address as a uniform base plus a 32-bit byte offset per lane, which lets the loads take their base from
 // scalar registers (10-15 vector registers fewer in the gradient kernel, which needs them; the stream and totals
 // kernels measured 1-4 % slower with it and keep the plain form).
-template <class C, int ROWS, bool SBASE = false>
-__device__ __forceinline__ void fetch_rows(const bf16raw *X, int64_t t0, int nvalid, RowChunks<C, ROWS> &r)
+template <class C, int ROWS, bool SBASE = false, int NTHR = kThreads>
+__device__ __forceinline__ void fetch_rows(const bf16raw *X, int64_t t0, int nvalid, RowChunks<C, ROWS, NTHR> &r)
 {
     const char *base = reinterpret_cast<const char *>(X + t0 * C::D);
 #pragma unroll
-    for (int k = 0; k < RowChunks<C, ROWS>::N; ++k) {
-        const int c = threadIdx.x + k * kThreads, row = c / C::CPR, ch = c % C::CPR;
+    for (int k = 0; k < RowChunks<C, ROWS, NTHR>::N; ++k) {
+        const int c = threadIdx.x + k * NTHR, row = c / C::CPR, ch = c % C::CPR;
         const int rr = row < nvalid ? row : nvalid - 1;
         if (SBASE) r.v[k] = *reinterpret_cast<const u32x4 *>(base + static_cast<uint32_t>((rr * C::D + ch * 8) * 2));
         else r.v[k] = *reinterpret_cast<const u32x4 *>(X + (t0 + rr) * C::D + ch * 8);
@@ -254,16 +261,51 @@ __device__ __forceinline__ void store_chunk(bf16raw *dst, int row, int ch, u32x4
 }
 
 // nvalid: rows of the tile that exist; the others are stored as zeros.
-template <class C, int ROWS, int STRIDE = C::XS, bool IL = false>
-__device__ __forceinline__ void store_rows(const RowChunks<C, ROWS> &r, bf16raw *dst, int nvalid)
+template <class C, int ROWS, int STRIDE = C::XS, bool IL = false, int NTHR = kThreads>
+__device__ __forceinline__ void store_rows(const RowChunks<C, ROWS, NTHR> &r, bf16raw *dst, int nvalid)
 {
     const int tid = opaque(static_cast<int>(threadIdx.x));       // keeps the tile addresses out of long-lived registers
 #pragma unroll
-    for (int k = 0; k < RowChunks<C, ROWS>::N; ++k) {
-        const int c = tid + k * kThreads, row = c / C::CPR, ch = c % C::CPR;
+    for (int k = 0; k < RowChunks<C, ROWS, NTHR>::N; ++k) {
+        const int c = tid + k * NTHR, row = c / C::CPR, ch = c % C::CPR;
         const bool real = row < nvalid;
         const u32x4 v = {real ? r.v[k].x : 0u, real ? r.v[k].y : 0u, real ? r.v[k].z : 0u, real ? r.v[k].w : 0u};
         if (row < ROWS) store_chunk<STRIDE, IL>(dst, row, ch, v);
+    }
+}
+
+// Hashed rows: a tile of ROWS tokens is ROWS * C::MCH chunks of 16 bytes, contiguous in memory; thread t owns chunks
+// t, t + 512, ... (most shapes: one, and not every thread has one).
+template <class C, int ROWS, int NTHR = kThreads>
+struct MassChunks {
+    static constexpr int N = (ROWS * C::MCH + NTHR - 1) / NTHR;
+    u32x4 v[N];
+};
+// SBASE: a uniform base plus a 32-bit byte offset per lane (see fetch_rows).
+template <class C, int ROWS, bool SBASE = false, int NTHR = kThreads>
+__device__ __forceinline__ void fetch_masses(const float *M, int64_t t0, int nvalid, MassChunks<C, ROWS, NTHR> &r)
+{
+    const char *base = reinterpret_cast<const char *>(M + t0 * C::LP);
+#pragma unroll
+    for (int k = 0; k < MassChunks<C, ROWS, NTHR>::N; ++k) {
+        const int c = threadIdx.x + k * NTHR, row = c / C::MCH, ch = c % C::MCH;
+        const int rr = row < nvalid ? row : nvalid - 1;         // (rows past the end re-read the last real row; their phi is zeroed)
+        if (SBASE) r.v[k] = *reinterpret_cast<const u32x4 *>(base + static_cast<uint32_t>((rr * C::LP + ch * 4) * 4));
+        else r.v[k] = *reinterpret_cast<const u32x4 *>(M + (t0 + rr) * C::LP + ch * 4);
+    }
+}
+template <class C, int ROWS, int NTHR = kThreads>
+__device__ __forceinline__ void store_masses(const MassChunks<C, ROWS, NTHR> &r, float *dst)
+{
+    const int tid = opaque(static_cast<int>(threadIdx.x));
+#pragma unroll
+    for (int k = 0; k < MassChunks<C, ROWS, NTHR>::N; ++k) {
+        const int c = tid + k * NTHR, row = c / C::MCH, ch = c % C::MCH;
+        if (row < ROWS) {
+            u32x2 *p = reinterpret_cast<u32x2 *>(dst + row * C::MS + ch * 4);
+            p[0] = u32x2{r.v[k].x, r.v[k].y};
+            p[1] = u32x2{r.v[k].z, r.v[k].w};
+        }
     }
 }
 
@@ -289,35 +331,35 @@ __device__ __forceinline__ void store_row_scales(const RowChunks<C, ROWS> &r, fl
 }
 
 // Read-out cotangent rows: gn = dO / e (e = L * Den) as bf16 rows, ge[row] = -(gn . O) as fp32 (= -(dO . O) / e).
-template <class C, int ROWS>
+template <class C, int ROWS, int NTHR = kThreads>
 struct CotChunks {
-    RowChunks<C, ROWS> g, o;
-    float den[RowChunks<C, ROWS>::N];
+    RowChunks<C, ROWS, NTHR> g, o;
+    float den[RowChunks<C, ROWS, NTHR>::N];
 };
 
-template <class C, int ROWS, bool SBASE = false>
+template <class C, int ROWS, bool SBASE = false, int NTHR = kThreads>
 __device__ __forceinline__ void fetch_cotangent(const bf16raw *dO, const bf16raw *O, const float *den, int64_t t0,
-                                                int nvalid, CotChunks<C, ROWS> &r)
+                                                int nvalid, CotChunks<C, ROWS, NTHR> &r)
 {
-    fetch_rows<C, ROWS, SBASE>(dO, t0, nvalid, r.g);
-    fetch_rows<C, ROWS, SBASE>(O, t0, nvalid, r.o);
+    fetch_rows<C, ROWS, SBASE, NTHR>(dO, t0, nvalid, r.g);
+    fetch_rows<C, ROWS, SBASE, NTHR>(O, t0, nvalid, r.o);
     const char *dbase = reinterpret_cast<const char *>(den + t0);
 #pragma unroll
-    for (int k = 0; k < RowChunks<C, ROWS>::N; ++k) {
-        const int row = (threadIdx.x + k * kThreads) / C::CPR;
+    for (int k = 0; k < RowChunks<C, ROWS, NTHR>::N; ++k) {
+        const int row = (threadIdx.x + k * NTHR) / C::CPR;
         const int rr = row < nvalid ? row : nvalid - 1;
         if (SBASE) r.den[k] = *reinterpret_cast<const float *>(dbase + static_cast<uint32_t>(rr * 4));
         else r.den[k] = den[t0 + rr];
     }
 }
 
-template <class C, int ROWS, int STRIDE = C::XS, bool IL = false>
-__device__ __forceinline__ void store_cotangent(const CotChunks<C, ROWS> &r, bf16raw *dst, float *ge, int L_real, int nvalid)
+template <class C, int ROWS, int STRIDE = C::XS, bool IL = false, int NTHR = kThreads>
+__device__ __forceinline__ void store_cotangent(const CotChunks<C, ROWS, NTHR> &r, bf16raw *dst, float *ge, int L_real, int nvalid)
 {
     const int tid = opaque(static_cast<int>(threadIdx.x));
 #pragma unroll
-    for (int k = 0; k < RowChunks<C, ROWS>::N; ++k) {
-        const int c = tid + k * kThreads, row = c / C::CPR, ch = c % C::CPR;
+    for (int k = 0; k < RowChunks<C, ROWS, NTHR>::N; ++k) {
+        const int c = tid + k * NTHR, row = c / C::CPR, ch = c % C::CPR;
         // rows past the end of the tile hold a copy of the last real row: they get zero cotangents
         const float inv = (row < nvalid && r.den[k] > 0.f) ? __builtin_amdgcn_rcpf(r.den[k] * static_cast<float>(L_real)) : 0.f;
         const uint32_t gw[4] = {r.g.v[k].x, r.g.v[k].y, r.g.v[k].z, r.g.v[k].w};
@@ -399,6 +441,28 @@ __device__ __forceinline__ void bit_masses(const f32x16 &z, int j, const Soft &s
     }
 }
 
+// The hashed form of one projection: c = +small or -small, where small = sigmoid(-2 beta |tanh z|) is the mass of the
+// bit's minor side and the sign bit tells which side that is (clear: z >= 0, the major side is +1).  One float per
+// (token, table, hyperplane) is all that the soft assignment of Algorithm 1, step 4 depends on: every pass after the
+// first rebuilds phi from it instead of projecting and exponentiating again.  beta = +infinity gives +-0 (the hard
+// hash); a padding hyperplane is +0 (all mass on the +1 side).
+__device__ __forceinline__ float bit_code(float zt, float beta)
+{
+    const float e2 = __expf(-2.0f * fabsf(zt));
+    const float ua = (1.0f - e2) * __builtin_amdgcn_rcpf(1.0f + e2);             // |tanh z|
+    const float e = __expf(fmaxf(-2.0f * beta * ua, -1e30f));                    // (-inf * 0 = NaN at z = 0: fmaxf returns -1e30)
+    const float small = e * __builtin_amdgcn_rcpf(1.0f + e);
+    return zt >= 0.f ? small : -small;
+}
+// masses on the +1 side (p) and the -1 side (q) from the hashed form
+__device__ __forceinline__ void code_masses(float c, float &p, float &q)
+{
+    const float small = fabsf(c), big = 1.0f - small;
+    const bool pos = (__float_as_uint(c) >> 31) == 0;
+    p = pos ? big : small;
+    q = pos ? small : big;
+}
+
 // phi over the low PLO bits (lo) and the high PHI bits (hi): phi[a * 2^PLO + b] = hi[a] * lo[b]
 // (the corner softmax is a product of per-bit two-point distributions).
 template <class C>
@@ -432,10 +496,15 @@ __device__ __forceinline__ void kron_factors(const float *p, const float *q, flo
 // written, which lets several wavefronts share the tables of one projection group.
 // If mass != null (bucket masses in the same pair-interleaved order), returns sum_r phi[r] * mass[r] over
 // what was written (the read-out of the bucket masses A by this token, i.e. its share of the normaliser).
-template <class C, int STRIDE = C::PS>
+// Two sources: the projections z of the lane's token (an accumulator of project()), or, if mrow != null, the hashed
+// row of the lane's token (C::LP floats, see bit_code()).
+// FENCE: a scheduling fence after every pair of high-bit indices (bounds the registers the compiler may spend on
+// interleaving them; kernels with registers to spare turn it off).
+template <class C, int STRIDE = C::PS, bool FENCE = true>
 __device__ __forceinline__ float write_assignments(const f32x16 &z, int g, int row, int h, const Soft &sf, bool valid,
                                                    bf16raw *ph, int j0 = 0, int jstep = 1, int a0 = 0,
-                                                   int a1 = 1 << C::PHI, const float *mass = nullptr)
+                                                   int a1 = 1 << C::PHI, const float *mass = nullptr,
+                                                   const float *mrow = nullptr)
 {
     static_assert(C::PLO == 3 && C::PHI >= 1, "eight low corners per high-bit index, indices in pairs");
     float dn = 0.f;
@@ -456,7 +525,17 @@ __device__ __forceinline__ float write_assignments(const f32x16 &z, int g, int r
             continue;
         }
         float p[C::P], q[C::P], lo[1 << C::PLO], hi[1 << C::PHI];
-        bit_masses<C>(z, j, sf, p, q, nullptr);
+        if (mrow) {
+            const float *src = mrow + opaque(table * C::P);
+#pragma unroll
+            for (int t = 0; t < C::P; t += 2) {
+                const float2 c2 = *reinterpret_cast<const float2 *>(src + t);
+                code_masses(c2.x, p[t], q[t]);
+                code_masses(c2.y, p[t + 1], q[t + 1]);
+            }
+        } else {
+            bit_masses<C>(z, j, sf, p, q, nullptr);
+        }
         kron_factors<C>(p, q, lo, hi);
 #pragma unroll
         for (int a = 0; a < (1 << C::PHI); a += 2) {
@@ -477,7 +556,7 @@ __device__ __forceinline__ float write_assignments(const f32x16 &z, int g, int r
                 *reinterpret_cast<u32x4 *>(prow + pos) =
                     u32x4{pack2(f[0], f[1]), pack2(f[2], f[3]), pack2(f[4], f[5]), pack2(f[6], f[7])};
             }
-            RACE_SCHED_FENCE();
+            if (FENCE) RACE_SCHED_FENCE();
         }
     }
     return dn;

@@ -1,16 +1,16 @@
 // grad_kernel: the two backward passes that contract the bucket statistics over the head dimension.
 // Register budget: with eight wavefronts of 256 registers a wavefront can carry up to 64 bucket rows x 128
 // columns of fp32 statistics (128 registers) next to its working set, i.e. 512 bucket rows per workgroup.
-// The workgroup then also forms dX = dz . W for its tile.  Shapes with more rows are split over TSPLIT
-// workgroups by tables (blockIdx.z): each computes dz for its own tables and writes it to the workspace;
-// dz_matmul_kernel then forms dX = dZ . W for all tables.
+// The workgroup then also forms dX = dz . W for its tile.  (Shapes with more bucket rows than that are not compiled.)
 //
 //   SIDE 0 (dQ), left to right, statistics S = (B | A) of (phi_K, [V | 1]) before/with token i:
 //       dphi_Q(i)[r] = S[r,:] . [dO_i/e_i | -(dO_i.O_i)/e_i]
 //   SIDE 1 (dK), right to left, statistics dS = (dB | dA) of (phi_Q, read-out cotangents) of tokens >= j:
 //       dphi_K(j)[r] = dS[r,:] . [V_j | 1]
 // followed in both cases by the chain rule through the corner softmax, tanh and W:  dx = W^T dz.
-// "reader" is the tensor whose gradient is produced, "writer" the tensor that feeds the statistics.
+// "reader" is the tensor whose gradient is produced, "writer" the tensor that feeds the statistics.  The writer's
+// assignments are rebuilt from its hashed rows (hash_kernel); the reader's rows are projected here, because the chain
+// rule needs tanh and its derivative next to the per-bit masses.
 //
 // The statistics are held transposed, tiles S^T[head column][bucket row], so that a tile's accumulator
 // registers are the B operand of the contraction over columns (lane = bucket row).  The in-tile part
@@ -55,7 +55,7 @@ struct GradCfg {
     static constexpr int TW = C::R >= 32 ? 1 : 32 / C::R;               // tables per tile
     static constexpr int KM = (C::R >= 32 ? 32 : C::R) / 8;             // groups of 8 corners per table and tile
     static constexpr int MB = KM == 4 ? 2 : (KM == 2 ? 1 : 0);          // corner bits 3.. that vary inside a tile
-    static_assert(MTG >= 1 && NRW >= 1 && TSPLIT >= 1 && TSPLIT * RW * NRW == C::LR, "bucket rows over wavefronts");
+    static_assert(MTG >= 1 && NRW >= 1 && TSPLIT == 1 && RW * NRW == C::LR, "all bucket rows of a head in one workgroup");
     static_assert(NRW == kWaves || TSPLIT == 1, "a workgroup with spare wavefronts holds all the rows");
     static_assert(C::NG % TSPLIT == 0 && kWaves % NGW == 0, "table split");
     static_assert(NGW * C::TPG * C::R >= ROWS, "a workgroup's rows are the tables of its projection groups");
@@ -124,12 +124,12 @@ struct GradLds {
     static constexpr int yr = part + (G::WPT > 1 ? kWaves * kTile * 8 * 4 : 0);   // [32][XS] reader-Y rows, pair-interleaved columns
     static constexpr int ttop = yr + kTile * C::XS * 2;                 // [2][64] x 16 B: masked in-tile term as MFMA operands
     static constexpr int xr = (ttop + (INTRA ? 2 * 64 * 16 : 0) + 255) & ~255;        // [32][XS]
-    static constexpr int xw = xr + kTile * C::XS * 2;
-    static constexpr int yw = xw + (INTRA ? kTile * C::XS * 2 : 0);     // [32][YS] writer-Y rows, pair-interleaved columns
+    static constexpr int mw = xr + kTile * C::XS * 2;                   // [32][MS] fp32: hashed writer rows
+    static constexpr int yw = (mw + (INTRA ? kTile * C::MS * 4 : 0) + 15) & ~15;     // [32][YS] writer-Y rows, pair-interleaved columns
     static constexpr int phw = yw + (INTRA ? kTile * C::YS * 2 : 0);    // [32][PST] writer assignments
     static constexpr int SS = 40;                                       // bf16 row stride of the output staging tiles
     static constexpr int stg = phw + (INTRA ? kTile * C::PST * 2 : 0);  // [NT][32][SS] bf16: dX tiles on their way out
-    static constexpr int xr2 = stg + (G::TSPLIT == 1 ? C::NT * kTile * SS * 2 : 0);   // [32][XS]: second buffer of the reader rows (unit-norm
+    static constexpr int xr2 = stg + C::NT * kTile * SS * 2;            // [32][XS]: second buffer of the reader rows (unit-norm
                                                                         // option: the dX wavefronts still read a tile's rows while the others
                                                                         // store the next tile's)
     static constexpr int total = xr2 + (UNIT ? kTile * C::XS * 2 : 0);
@@ -148,7 +148,7 @@ constexpr int grad_waves_per_simd()
 template <class C, int SIDE, bool UNIT, bool INTRA>
 __global__ __launch_bounds__(kThreads, (grad_waves_per_simd<C, UNIT, INTRA>()))
 void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, const bf16raw *O,
-                 const float *den, const bf16raw *dO, bf16raw *dZ, bf16raw *dX)
+                 const float *den, const bf16raw *dO, bf16raw *dX)
 {
     using S = GradLds<C, UNIT, INTRA>;
     using G = GradCfg<C>;
@@ -162,7 +162,7 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
     float *pm = reinterpret_cast<float *>(lds + S::pm);
     bf16raw *yr = reinterpret_cast<bf16raw *>(lds + S::yr);
     bf16raw *xr0 = reinterpret_cast<bf16raw *>(lds + S::xr);
-    bf16raw *xw = reinterpret_cast<bf16raw *>(lds + S::xw);
+    float *mw = reinterpret_cast<float *>(lds + S::mw);
     bf16raw *yw = reinterpret_cast<bf16raw *>(lds + S::yw);
     bf16raw *phw = reinterpret_cast<bf16raw *>(lds + S::phw);
     float *part = reinterpret_cast<float *>(lds + S::part);
@@ -172,7 +172,7 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
     constexpr bool kReverse = (SIDE == 1);
     const int seg = blockIdx.x, bh = blockIdx.y, head = bh % a.H;
     const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, ln = lane & 31, h = lane >> 5;
-    const int th = blockIdx.z;                       // which share of the tables this workgroup owns
+    constexpr int th = 0;                            // (a workgroup owns all the tables)
     const int r_base = th * G::ROWS;                 // its first bucket row
     const int r_own = r_base + w * G::RW;            // this wavefront's bucket rows
     // backward pass through the soft assignment: the tables (or the share of one table) behind this wavefront's rows
@@ -185,10 +185,10 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
 
     const size_t base = static_cast<size_t>(bh) * a.N * C::D;
     Q += base; K += base; V += base; O += base; dO += base;
-    dZ += static_cast<size_t>(bh) * a.N * C::LPP;
     dX += base;
     den += static_cast<size_t>(bh) * a.N;
-    const bf16raw *Xr = SIDE == 0 ? Q : K, *Xw = SIDE == 0 ? K : Q;
+    const bf16raw *Xr = SIDE == 0 ? Q : K;
+    const float *Mw = (SIDE == 0 ? a.Mk : a.Mq) + static_cast<size_t>(bh) * a.N * C::LP;
     const float *st = a.state + (static_cast<size_t>(bh) * a.nseg + seg) * C::STATE;
 
     {
@@ -223,13 +223,14 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
     auto tile_nv = [&](int64_t t0) { return (t_end - t0 < kTile) ? static_cast<int>(t_end - t0) : kTile; };
 
     // loads run ahead of the arithmetic: issued a step ahead, written to LDS at the next tile's start
-    RowChunks<C, kTile> pre_r, pre_w, pre_v;
+    RowChunks<C, kTile> pre_r, pre_v;
+    MassChunks<C, kTile> pre_w;
     CotChunks<C, kTile> pre_c;
     auto fetch = [&](int it) {
         const int64_t t0 = tile_t0(it);
         const int nv = tile_nv(t0);
         fetch_rows<C, kTile, true>(Xr, t0, nv, pre_r);
-        if (intra) fetch_rows<C, kTile, true>(Xw, t0, nv, pre_w);
+        if (intra) fetch_masses<C, kTile>(Mw, t0, nv, pre_w);
         if (SIDE == 1 || intra) fetch_rows<C, kTile, true>(V, t0, nv, pre_v);
         if (SIDE == 0 || intra) fetch_cotangent<C, kTile, true>(dO, O, den, t0, nv, pre_c);
     };
@@ -294,11 +295,8 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
 
         // ---- registers -> LDS
         store_rows<C, kTile>(pre_r, xr, nvalid);
-        if (intra) store_rows<C, kTile>(pre_w, xw, nvalid);
-        if (UNIT) {
-            store_row_scales<C, kTile>(pre_r, nrm);
-            if (intra) store_row_scales<C, kTile>(pre_w, nrm + kTile);
-        }
+        if (intra) store_masses<C, kTile>(pre_w, mw);
+        if (UNIT) store_row_scales<C, kTile>(pre_r, nrm);
         if (SIDE == 0) {
             store_cotangent<C, kTile, C::XS, true>(pre_c, yr, sr, a.L_real, nvalid);
             if (intra) store_rows<C, kTile, C::YS, true>(pre_v, yw, nvalid);
@@ -311,11 +309,9 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
         GRAD_PHASE(0)
         __syncthreads();
         GRAD_PHASE(1)
-        if constexpr (G::TSPLIT == 1) {
-            if (it > 0 && my_dx >= 0) {
-                const int64_t tp = tile_t0(it - 1);
-                dx_stage(my_dx, tp, tile_nv(tp), tile_xr(it - 1), tile_nrm(it - 1));
-            }
+        if (it > 0 && my_dx >= 0) {
+            const int64_t tp = tile_t0(it - 1);
+            dx_stage(my_dx, tp, tile_nv(tp), tile_xr(it - 1), tile_nrm(it - 1));
         }
         GRAD_PHASE(12)
 
@@ -331,9 +327,8 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
         if (intra && w < G::NW) {
             const int pg = w % G::NGW, pj = (w / G::NGW) % C::TPL, as = w / (G::NGW * C::TPL);
             constexpr int kShare = (1 << C::PHI) / G::AS;
-            const f32x16 zw = project<C>(wp, xw, th * G::NGW + pg, ln, h, UNIT ? nrm + kTile : nullptr);
-            write_assignments<C, C::PST>(zw, th * G::NGW + pg, ln, h, a.soft(), ln < nvalid, phw, pj, C::TPL, as * kShare,
-                                 (as + 1) * kShare);
+            write_assignments<C, C::PST>(f32x16{0}, th * G::NGW + pg, ln, h, a.soft(), ln < nvalid, phw, pj, C::TPL, as * kShare,
+                                         (as + 1) * kShare, nullptr, mw + ln * C::MS);
         }
         constexpr int kRd0 = INTRA ? G::RD0 : 0, kNr = INTRA ? G::NR : G::NR_NC, kRj = INTRA ? G::RJ : G::RJ_NC;
         if (w >= kRd0 && w < kRd0 + kNr) {
@@ -580,28 +575,16 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
         GRAD_PHASE(9)
         GRAD_PHASE(11)
         // (dX of this tile is formed after the next step's first barrier, see dx_stage)
-        if constexpr (G::TSPLIT != 1) {
-            __syncthreads();
-            // ---- this workgroup's columns of dZ (projection rows of its groups) -> workspace, 16-byte pieces
-            if (tid < kTile * G::NGW * 4) {
-                const int row = tid / (G::NGW * 4), ch = tid % (G::NGW * 4);
-                if (row < nvalid)
-                    *reinterpret_cast<u32x4 *>(dZ + (t0 + row) * C::LPP + th * G::NGW * 32 + 8 * ch) =
-                        *reinterpret_cast<const u32x4 *>(dz + row * S::DZS + 8 * ch);
-            }
-        }
         // no barrier here: the next step's loads-to-LDS touch none of dz, pm, part or the staging tiles, its production
         // (which rewrites pm) comes after the next barrier, and so does this tile's dX, which reads dz (rewritten only after
         // two more barriers) and, with the unit-norm option, this tile's reader rows and scales (the next step stores into
         // the other buffer, the step after that only after barriers the dX wavefronts take part in).
     }
-    if constexpr (G::TSPLIT == 1) {
-        if (ntiles > 0) {
-            __syncthreads();        // the last tile's dz is visible
-            if (my_dx >= 0) {
-                const int64_t tp = tile_t0(ntiles - 1);
-                dx_stage(my_dx, tp, tile_nv(tp), tile_xr(ntiles - 1), tile_nrm(ntiles - 1));
-            }
+    if (ntiles > 0) {
+        __syncthreads();        // the last tile's dz is visible
+        if (my_dx >= 0) {
+            const int64_t tp = tile_t0(ntiles - 1);
+            dx_stage(my_dx, tp, tile_nv(tp), tile_xr(ntiles - 1), tile_nrm(ntiles - 1));
         }
     }
     // ---- cotangent of beta: lanes -> wavefront (shuffles) -> workgroup (LDS, wavefront order) -> one workspace slot
@@ -614,57 +597,11 @@ void grad_kernel(KArgs a, const bf16raw *Q, const bf16raw *K, const bf16raw *V, 
         if (tid == 0) {
             float s = 0.f;
             for (int i = 0; i < kWaves; ++i) s += sr[i];
-            const int wgs = gridDim.x * gridDim.z;      // workgroups per (side, batch*head)
-            a.dbeta_part[(static_cast<size_t>(SIDE) * gridDim.y + bh) * wgs + seg * gridDim.z + th] = s;
+            const int wgs = gridDim.x;                  // workgroups per (side, batch*head)
+            a.dbeta_part[(static_cast<size_t>(SIDE) * gridDim.y + bh) * wgs + seg] = s;
         }
     }
     GRAD_PHASE_PRINT()
-}
-
-// dX = dZ . W: (N x LPP) . (LPP x d) per head; a workgroup of NT wavefronts takes kDzTiles tiles of 32 tokens.
-constexpr int kDzTiles = 8;
-template <class C>
-__global__ __launch_bounds__(64 * C::NT)
-void dz_matmul_kernel(KArgs a, const bf16raw *dZ, bf16raw *dX)
-{
-    constexpr int SS = 40;
-    __shared__ __attribute__((aligned(16))) bf16raw dz[kTile * C::ZS];
-    __shared__ __attribute__((aligned(16))) bf16raw stage[C::NT * kTile * SS];
-    const int bh = blockIdx.y, head = bh % a.H;
-    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, ln = lane & 31, h = lane >> 5;
-    dZ += static_cast<size_t>(bh) * a.N * C::LPP;
-    dX += static_cast<size_t>(bh) * a.N * C::D;
-    const bf16raw *wt = a.WpT + static_cast<size_t>(head) * C::D * C::LPP;     // [d][LPP]
-    const int nt = w;
-    u32x4 bw[C::LPP / 16];
-#pragma unroll
-    for (int s = 0; s < C::LPP / 16; ++s)
-        bw[s] = *reinterpret_cast<const u32x4 *>(wt + (32 * nt + ln) * C::LPP + 16 * s + 8 * h);
-    for (int k = 0; k < kDzTiles; ++k) {
-        const int64_t t0 = (static_cast<int64_t>(blockIdx.x) * kDzTiles + k) * kTile;
-        if (t0 >= a.N) break;
-        const int nvalid = (a.N - t0 < kTile) ? static_cast<int>(a.N - t0) : kTile;
-        __syncthreads();
-        for (int c = tid; c < kTile * (C::LPP / 8); c += 64 * C::NT) {
-            const int row = c / (C::LPP / 8), ch = c % (C::LPP / 8);
-            u32x4 v = {0, 0, 0, 0};
-            if (row < nvalid) v = *reinterpret_cast<const u32x4 *>(dZ + (t0 + row) * C::LPP + 8 * ch);
-            *reinterpret_cast<u32x4 *>(dz + row * C::ZS + 8 * ch) = v;
-        }
-        __syncthreads();
-        f32x16 acc = {0};
-#pragma unroll
-        for (int s = 0; s < C::LPP / 16; ++s) acc = mma(lds128(dz + ln * C::ZS + 16 * s + 8 * h), bw[s], acc);
-        bf16raw *sg = stage + w * kTile * SS;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) sg[acc_row(v, h) * SS + ln] = static_cast<bf16raw>(pack2(acc[v], 0.f) & 0xffffu);
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            const int row = (lane >> 2) + 16 * kk, ch = lane & 3;
-            const u32x4 piece = *reinterpret_cast<const u32x4 *>(sg + row * SS + 8 * ch);
-            if (row < nvalid) *reinterpret_cast<u32x4 *>(dX + (t0 + row) * C::D + 32 * nt + 8 * ch) = piece;
-        }
-    }
 }
 
 }  // namespace mfma

@@ -1,6 +1,8 @@
 // bf16 MFMA kernel family for RACE Attention on gfx950 (see mfma_common.h for the execution shape).
 //
 // Kernels
+//   hash_kernel      projection and per-bit soft-hash masses of every row of Q and K, once per call: the "hashed rows"
+//                    (one float per token, table and hyperplane) that every later pass rebuilds phi from.
 //   scan_kernel      "totals" of the statistics per segment, then an exclusive prefix (forward) or
 //                    suffix (backward) scan over segments turns them into segment-start states.
 //   stream_kernel    one pass over a segment carrying statistics [L*R][d] in accumulator registers
@@ -52,6 +54,98 @@ __device__ __forceinline__ void load_projection_matrix(const KArgs &a, int head,
     }
 }
 
+// ================================================================ hash_kernel
+// Algorithm 1, steps 2-4 up to the per-bit masses, for every row of Q (blockIdx.z + first == 0) or K (== 1):
+// z = W x on the matrix cores, then one float per (table, hyperplane), see bit_code().  No state is carried, so the
+// grid is over token ranges: many small workgroups that hide each other's latencies, unlike the scans that follow.
+template <class C>
+struct HashLds {
+    static constexpr int SLOTS = 4 / C::NG;                             // 32-token tiles per step (four wavefronts)
+    static constexpr int TT = 32 * SLOTS;
+    static constexpr int wp = 0;                                        // [LPP][XS] bf16
+    static constexpr int x = wp + C::LPP * C::XS * 2;                   // [TT][XS] bf16 rows
+    static constexpr int out = x + TT * C::XS * 2;                      // [TT][MS] fp32 hashed rows
+    static constexpr int nx = out + TT * C::MS * 4;                     // [TT] fp32: 1 / |x| (unit-norm option)
+    static constexpr int total = nx + TT * 4;
+};
+constexpr int kHashThreads = 256;
+constexpr int kHashTokens = 512;        // tokens per workgroup (amortises the load of W)
+
+template <class C, bool UNIT>
+__global__ __launch_bounds__(kHashThreads) void hash_kernel(KArgs a, const bf16raw *Xq, const bf16raw *Xk, int first)
+{
+    using S = HashLds<C>;
+    constexpr int TT = S::TT;
+    extern __shared__ __attribute__((aligned(256))) unsigned char lds[];
+    bf16raw *wp = reinterpret_cast<bf16raw *>(lds + S::wp);
+    bf16raw *xs = reinterpret_cast<bf16raw *>(lds + S::x);
+    float *out = reinterpret_cast<float *>(lds + S::out);
+    float *nx = reinterpret_cast<float *>(lds + S::nx);
+    const int which = static_cast<int>(blockIdx.z) + first;
+    const int bh = blockIdx.y, head = bh % a.H;
+    const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, ln = lane & 31, h = lane >> 5;
+    const bf16raw *X = (which ? Xk : Xq) + static_cast<size_t>(bh) * a.N * C::D;
+    float *M = (which ? a.Mk : a.Mq) + static_cast<size_t>(bh) * a.N * C::LP;
+    {
+        const bf16raw *src = a.Wp + static_cast<size_t>(head) * C::LPP * C::D;
+        for (int c = tid; c < C::LPP * C::CPR; c += kHashThreads) {
+            const int row = c / C::CPR, ch = c % C::CPR;
+            *reinterpret_cast<u32x4 *>(wp + row * C::XS + ch * 8) = *reinterpret_cast<const u32x4 *>(src + row * C::D + ch * 8);
+        }
+    }
+    const int64_t t_begin = static_cast<int64_t>(blockIdx.x) * kHashTokens;
+    const int64_t t_end = (t_begin + kHashTokens < a.N) ? t_begin + kHashTokens : a.N;
+    const Soft sf = a.soft();
+    for (int64_t t0 = t_begin; t0 < t_end; t0 += TT) {
+        const int nv = (t_end - t0 < TT) ? static_cast<int>(t_end - t0) : TT;
+        // rows -> LDS (rows past the end repeat the last one: their results are not stored)
+        for (int c = tid; c < TT * C::CPR; c += kHashThreads) {
+            const int row = c / C::CPR, ch = c % C::CPR;
+            const int rr = row < nv ? row : nv - 1;
+            const u32x4 v = *reinterpret_cast<const u32x4 *>(X + (t0 + rr) * C::D + ch * 8);
+            *reinterpret_cast<u32x4 *>(xs + row * C::XS + ch * 8) = v;
+            if (UNIT) {
+                const uint32_t xw[4] = {v.x, v.y, v.z, v.w};
+                float ss = 0.f;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) ss = dot2(xw[e], xw[e], ss);
+#pragma unroll
+                for (int m = C::CPR / 2; m >= 1; m >>= 1) ss += __shfl_xor(ss, m, 64);     // the chunks of a row sit in consecutive lanes
+                if (ch == 0) nx[row] = __builtin_amdgcn_rsqf(fmaxf(ss, 1e-24f));
+            }
+        }
+        __syncthreads();
+        {
+            const int slot = w / C::NG, g = w % C::NG;
+            const f32x16 z = project<C>(wp, xs + slot * 32 * C::XS, g, ln, h, UNIT ? nx + slot * 32 : nullptr);
+            float *orow = out + (slot * 32 + ln) * C::MS;
+#pragma unroll
+            for (int j = 0; j < C::TPL; ++j) {
+                const int table = g * C::TPG + h * C::TPL + j;
+                if (table >= C::L) break;
+                const bool real_table = !C::PAD || table < sf.L;
+#pragma unroll
+                for (int t = 0; t < C::P; t += 2) {
+                    float2 c2;
+                    c2.x = (real_table && (!C::PAD || t < sf.P)) ? bit_code(z[zslot<C>(j, t)], sf.beta) : 0.f;
+                    c2.y = (real_table && (!C::PAD || t + 1 < sf.P)) ? bit_code(z[zslot<C>(j, t + 1)], sf.beta) : 0.f;
+                    *reinterpret_cast<float2 *>(orow + table * C::P + t) = c2;
+                }
+            }
+        }
+        __syncthreads();
+        for (int c = tid; c < TT * C::MCH; c += kHashThreads) {
+            const int row = c / C::MCH, ch = c % C::MCH;
+            if (row < nv) {
+                const float2 lo = *reinterpret_cast<const float2 *>(out + row * C::MS + ch * 4);
+                const float2 hi = *reinterpret_cast<const float2 *>(out + row * C::MS + ch * 4 + 2);
+                *reinterpret_cast<float4 *>(M + (t0 + row) * C::LP + ch * 4) = float4{lo.x, lo.y, hi.x, hi.y};
+            }
+        }
+        // (the next step rewrites the row tile, which nobody reads any more, and `out` only after its first barrier)
+    }
+}
+
 // ================================================================ totals_kernel
 // Statistics of one segment from a zero start, 64 tokens per step (both halves of the workgroup hash
 // 32 tokens each).  QG == 0: (phi_K, [V | 1]), Algorithm 1 step 5.  QG == 1: (phi_Q, [dO/e | -(dO.O)/e]),
@@ -59,13 +153,11 @@ __device__ __forceinline__ void load_projection_matrix(const KArgs &a, int head,
 template <class C>
 struct TotalsLds {
     static constexpr int TT = 64;
-    static constexpr int wp = 0;                                        // [LPP][XS] bf16
-    static constexpr int x = wp + C::LPP * C::XS * 2;                   // [64][XS] hashed rows
-    static constexpr int y = x + TT * C::XS * 2;                        // [64][YS] accumulated rows
+    static constexpr int m = 0;                                         // [64][MS] fp32 hashed rows
+    static constexpr int y = m + TT * C::MS * 4;                        // [64][YS] accumulated rows
     static constexpr int ph = y + TT * C::YS * 2;                       // [64][PST] assignments
     static constexpr int ge = ph + TT * C::PST * 2;                     // [64] fp32
-    static constexpr int nx = ge + TT * 4;                              // [64] fp32: 1 / |x| of the hashed rows (unit-norm option)
-    static constexpr int total = nx + TT * 4;
+    static constexpr int total = ge + TT * 4;
     static_assert(total <= 160 * 1024, "LDS budget");
 };
 
@@ -73,30 +165,28 @@ struct TotalsLds {
 template <class C>
 __device__ __forceinline__ bool mass_owner(int mt, int cg) { return mt % C::CG == cg; }
 
-template <class C, int QG, bool UNIT>
+// M: the hashed rows of the tensor whose assignments feed the statistics (K forward, Q backward).
+template <class C, int QG>
 __global__ __launch_bounds__(kThreads, C::STREAM_WAVES_PER_SIMD)
-void totals_kernel(KArgs a, const bf16raw *X, const bf16raw *Y, const bf16raw *Oin, const float *den_in)
+void totals_kernel(KArgs a, const float *M, const bf16raw *Y, const bf16raw *Oin, const float *den_in)
 {
     using S = TotalsLds<C>;
     constexpr int TT = S::TT;
     extern __shared__ __attribute__((aligned(256))) unsigned char lds[];
-    bf16raw *wp = reinterpret_cast<bf16raw *>(lds + S::wp);
-    bf16raw *xs = reinterpret_cast<bf16raw *>(lds + S::x);
+    float *ms = reinterpret_cast<float *>(lds + S::m);
     bf16raw *ys = reinterpret_cast<bf16raw *>(lds + S::y);
     bf16raw *ph = reinterpret_cast<bf16raw *>(lds + S::ph);
     float *ge_lds = reinterpret_cast<float *>(lds + S::ge);
-    float *nx = reinterpret_cast<float *>(lds + S::nx);
 
-    const int seg = blockIdx.x, bh = blockIdx.y, head = bh % a.H;
+    const int seg = blockIdx.x, bh = blockIdx.y;
     const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, ln = lane & 31, h = lane >> 5;
     const int rg = w % C::RG, cg = w / C::RG;
     const int r_own = rg * C::LRW, c_own = cg * C::DW;
     const size_t base = static_cast<size_t>(bh) * a.N * C::D;
-    X += base; Y += base;
+    M += static_cast<size_t>(bh) * a.N * C::LP; Y += base;
     if (QG) { Oin += base; den_in += static_cast<size_t>(bh) * a.N; }
     float *st = a.state + (static_cast<size_t>(bh) * a.nseg + seg) * C::STATE;
 
-    load_projection_matrix<C>(a, head, wp);
     f32x16 Sacc[C::MT][C::NTW];
     float macc[C::MT];
 #pragma unroll
@@ -110,12 +200,13 @@ void totals_kernel(KArgs a, const bf16raw *X, const bf16raw *Y, const bf16raw *O
     const int nsteps = static_cast<int>((t_end - t_begin + TT - 1) / TT);
     auto step_nv = [&](int64_t t0) { return (t_end - t0 < TT) ? static_cast<int>(t_end - t0) : TT; };
 
-    RowChunks<C, TT> pre_x, pre_y;
+    MassChunks<C, TT> pre_m;
+    RowChunks<C, TT> pre_y;
     CotChunks<C, TT> pre_c;
     auto fetch = [&](int it) {
         const int64_t t0 = t_begin + static_cast<int64_t>(it) * TT;
         const int nv = step_nv(t0);
-        fetch_rows<C, TT>(X, t0, nv, pre_x);
+        fetch_masses<C, TT>(M, t0, nv, pre_m);
         if (QG) fetch_cotangent<C, TT>(Y, Oin, den_in, t0, nv, pre_c);
         else fetch_rows<C, TT>(Y, t0, nv, pre_y);
     };
@@ -124,8 +215,7 @@ void totals_kernel(KArgs a, const bf16raw *X, const bf16raw *Y, const bf16raw *O
     for (int it = 0; it < nsteps; ++it) {
         const int64_t t0 = t_begin + static_cast<int64_t>(it) * TT;
         const int nvalid = step_nv(t0);
-        store_rows<C, TT>(pre_x, xs, nvalid);
-        if (UNIT) store_row_scales<C, TT>(pre_x, nx);
+        store_masses<C, TT>(pre_m, ms);
         if (QG) store_cotangent<C, TT, C::YS>(pre_c, ys, ge_lds, a.L_real, nvalid);
         else store_rows<C, TT, C::YS>(pre_y, ys, nvalid);
         if (it + 1 < nsteps) fetch(it + 1);
@@ -133,8 +223,8 @@ void totals_kernel(KArgs a, const bf16raw *X, const bf16raw *Y, const bf16raw *O
         {
             // wavefront = (token half, projection group, share of the group's tables)
             const int half = w / 4, g = w % C::NG, jq = (w % 4) / C::NG;
-            const f32x16 z = project<C>(wp, xs + half * 32 * C::XS, g, ln, h, UNIT ? nx + half * 32 : nullptr);
-            write_assignments<C, C::PST>(z, g, half * 32 + ln, h, a.soft(), half * 32 + ln < nvalid, ph, jq, C::JSTEP);
+            write_assignments<C, C::PST>(f32x16{0}, g, half * 32 + ln, h, a.soft(), half * 32 + ln < nvalid, ph, jq, C::JSTEP, 0,
+                                         1 << C::PHI, nullptr, ms + (half * 32 + ln) * C::MS);
         }
         __syncthreads();
 #pragma unroll
@@ -179,61 +269,59 @@ void totals_kernel(KArgs a, const bf16raw *X, const bf16raw *Y, const bf16raw *O
 // whose assignments feed them (K forward, Q for dV), Y = rows accumulated (V forward, dO/e for dV).
 template <class C>
 struct StreamLds {
-    static constexpr int wp = 0;                                        // [LPP][XS] bf16
-    static constexpr int y = wp + C::LPP * C::XS * 2;                   // [32][YS] bf16: accumulated rows
+    static constexpr int y = 0;                                         // [32][YS] bf16: accumulated rows
     static constexpr int mass = y + kTile * C::YS * 2;                  // [LR] fp32: bucket masses A before this tile, pair-interleaved
     static constexpr int dnp = mass + C::LR * 4;                        // [4][2][32] fp32: mass read-outs per reader wavefront and lane half
-    static constexpr int nrm = dnp + 4 * 2 * kTile * 4;                 // [2][32] fp32: 1 / |x| of the reader and writer rows (unit-norm option)
-    static constexpr int area = (nrm + 2 * kTile * 4 + 255) & ~255;     // start of the aliased area
-    // phase A (production, contraction)
-    static constexpr int xr = area;                                     // [32][XS] reader rows
-    static constexpr int xw = xr + kTile * C::XS * 2;                   // [32][XS] writer rows
-    static constexpr int phr = xw + kTile * C::XS * 2;                  // [32][PS] reader assignments
+    static constexpr int mr = (dnp + 4 * 2 * kTile * 4 + 255) & ~255;   // [32][MS] fp32: hashed reader rows
+    static constexpr int mw = mr + kTile * C::MS * 4;                   // [32][MS] fp32: hashed writer rows
+    static constexpr int phr = (mw + kTile * C::MS * 4 + 15) & ~15;     // [32][PS] reader assignments
     static constexpr int phw = phr + kTile * C::PS * 2;                 // [32][PS] writer assignments
     static constexpr int endA = phw + kTile * C::PS * 2;
-    // phase B (reduction over the four bucket-row groups) reuses the same bytes
+    // reduction over the bucket-row groups.  Where LDS allows it has bytes of its own: the epilogue of a tile then runs
+    // next to the staging of the following tile instead of between two barriers of its own; otherwise it reuses the
+    // bytes of the assignment tiles.
     static constexpr int RS = C::D + 4;                                 // fp32 row stride: D numerators, 1 normaliser part
-    static constexpr int red = area;                                    // [RG][32][RS] fp32
-    static constexpr int endB = red + C::RG * kTile * RS * 4;
-    static constexpr int total = endA > endB ? endA : endB;
+    static constexpr int red_bytes = C::RG * kTile * RS * 4;            // [RG][32][RS] fp32
+    static constexpr bool kOwnRed = ((endA + 255) & ~255) + red_bytes <= 160 * 1024;
+    static constexpr int red = kOwnRed ? ((endA + 255) & ~255) : mr;
+    static constexpr int total = kOwnRed ? red + red_bytes : (endA > mr + red_bytes ? endA : mr + red_bytes);
     static_assert(total <= 160 * 1024, "LDS budget");
 };
 
 // NC: the non-causal variant only (the in-tile term and the update are compiled out, which frees registers); the
 // other variant reads the flag at run time (with the flag known to be set the compiler's schedule of the causal
 // kernels needed more registers: the 128-register shapes spilled).
-template <class C, int MODE, bool UNIT, bool NC>
+// Mr, Mw: the hashed rows of the reader and the writer tensor.
+template <class C, int MODE, bool NC>
 __global__ __launch_bounds__(kThreads, C::STREAM_WAVES_PER_SIMD)
-void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw *Y, const bf16raw *Oin,
+void stream_kernel(KArgs a, const float *Mr, const float *Mw, const bf16raw *Y, const bf16raw *Oin,
                    const float *den_in, bf16raw *Out, float *den_out)
 {
     using S = StreamLds<C>;
     extern __shared__ __attribute__((aligned(256))) unsigned char lds[];
-    bf16raw *wp = reinterpret_cast<bf16raw *>(lds + S::wp);
     bf16raw *ytile = reinterpret_cast<bf16raw *>(lds + S::y);
     float *mass = reinterpret_cast<float *>(lds + S::mass);
     float *dnp = reinterpret_cast<float *>(lds + S::dnp);
-    float *nrm = reinterpret_cast<float *>(lds + S::nrm);
-    bf16raw *xr = reinterpret_cast<bf16raw *>(lds + S::xr);
-    bf16raw *xw = reinterpret_cast<bf16raw *>(lds + S::xw);
+    float *mr = reinterpret_cast<float *>(lds + S::mr);
+    float *mw = reinterpret_cast<float *>(lds + S::mw);
     bf16raw *phr = reinterpret_cast<bf16raw *>(lds + S::phr);
     bf16raw *phw = reinterpret_cast<bf16raw *>(lds + S::phw);
     float *red = reinterpret_cast<float *>(lds + S::red);
 
     constexpr bool kReverse = (MODE == kGradV);
-    const int seg = blockIdx.x, bh = blockIdx.y, head = bh % a.H;
+    const int seg = blockIdx.x, bh = blockIdx.y;
     const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, ln = lane & 31, h = lane >> 5;
     const int rg = w % C::RG, cg = w / C::RG;
     const int r_own = rg * C::LRW, c_own = cg * C::DW;
     const bool intra = NC ? false : a.causal != 0;    // causal: the tile's own keys take part
 
     const size_t base = static_cast<size_t>(bh) * a.N * C::D;
-    Xr += base; Xw += base; Y += base; Out += base;
+    Mr += static_cast<size_t>(bh) * a.N * C::LP; Mw += static_cast<size_t>(bh) * a.N * C::LP;
+    Y += base; Out += base;
     if (MODE == kGradV) { Oin += base; den_in += static_cast<size_t>(bh) * a.N; }
     if (MODE == kForward) den_out += static_cast<size_t>(bh) * a.N;
     const float *st = a.state + (static_cast<size_t>(bh) * a.nseg + seg) * C::STATE;
 
-    load_projection_matrix<C>(a, head, wp);
     // statistics at the start of the segment
     f32x16 Sacc[C::MT][C::NTW];
     float macc[C::MT];                 // bucket masses (tiles mt % 2 == cg): per-half partial sums, lane n <-> row
@@ -257,14 +345,15 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
     auto tile_nv = [&](int64_t t0) { return (t_end - t0 < kTile) ? static_cast<int>(t_end - t0) : kTile; };
 
     // loads run one tile ahead of the arithmetic
-    RowChunks<C, kTile> pre_r, pre_w, pre_y;
+    MassChunks<C, kTile> pre_r, pre_w;
+    RowChunks<C, kTile> pre_y;
     CotChunks<C, kTile> pre_c;
     auto fetch = [&](int it) {
         const int64_t t0 = tile_t0(it);
         const int nv = tile_nv(t0);
-        fetch_rows<C, kTile>(Xr, t0, nv, pre_r);
+        fetch_masses<C, kTile>(Mr, t0, nv, pre_r);
         if (intra) {
-            fetch_rows<C, kTile>(Xw, t0, nv, pre_w);
+            fetch_masses<C, kTile>(Mw, t0, nv, pre_w);
             if (MODE == kGradV) fetch_cotangent<C, kTile>(Y, Oin, den_in, t0, nv, pre_c);
             else fetch_rows<C, kTile>(Y, t0, nv, pre_y);
         }
@@ -272,19 +361,56 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
     if (ntiles > 0) fetch(0);
 
     const float inv_tables = 1.0f / static_cast<float>(a.L_real);
+    // ---- epilogue of one tile: thread = (token, pieces of 4 columns: 4i.. and, for d = 128, 64 + 4i..; consecutive
+    //      threads read consecutive 16-byte pieces of the partials): sum, normalise, store
+    auto epilogue = [&](int64_t t0, int nvalid) __attribute__((always_inline)) {
+        {
+        constexpr int NP = C::D / 64;                // pieces of 4 columns per thread
+        const int tok = tid >> 4, c0 = (tid & 15) * 4;
+        float acc[NP][4];
+#pragma unroll
+        for (int c = 0; c < NP; ++c) acc[c][0] = acc[c][1] = acc[c][2] = acc[c][3] = 0.f;
+        float e = 0.f;
+#pragma unroll
+        for (int gg = 0; gg < 4; ++gg) {              // row groups (at most four) and the four reader wavefronts
+            const float *src = red + (gg * kTile + tok) * S::RS;
+            if (gg < C::RG) {
+#pragma unroll
+                for (int c = 0; c < NP; ++c) {
+                    const float4 p4 = *reinterpret_cast<const float4 *>(src + c0 + 64 * c);
+                    acc[c][0] += p4.x; acc[c][1] += p4.y; acc[c][2] += p4.z; acc[c][3] += p4.w;
+                }
+            }
+            if (MODE == kForward) {
+                const float dpart = dnp[gg * 64 + tok] + dnp[gg * 64 + 32 + tok];
+                e += gg < C::RG ? src[C::D] + dpart : dpart;
+            }
+        }
+        if (tok < nvalid) {
+            const float scale = (MODE == kForward) ? (e > 0.f ? __builtin_amdgcn_rcpf(e) : 0.f) : 1.0f;   // e = 0: hard hash, empty buckets
+            bf16raw *dst = Out + (t0 + tok) * C::D + c0;
+#pragma unroll
+            for (int c = 0; c < NP; ++c)
+                *reinterpret_cast<u32x2 *>(dst + 64 * c) =
+                    u32x2{pack2(acc[c][0] * scale, acc[c][1] * scale), pack2(acc[c][2] * scale, acc[c][3] * scale)};
+            if (MODE == kForward && (tid & 15) == 0) den_out[t0 + tok] = e * inv_tables;
+        }
+    }
+    };
     RACE_PHASE_DECL
     for (int it = 0; it < ntiles; ++it) {
         const int64_t t0 = tile_t0(it);
         const int nvalid = tile_nv(t0);
+        // (the reduction buffer has bytes of its own: the previous tile's epilogue runs here, next to this tile's staging)
+        if (S::kOwnRed && it > 0) {
+            const int64_t tp = tile_t0(it - 1);
+            epilogue(tp, tile_nv(tp));
+        }
 
         // ---- registers -> LDS, then start the next tile's loads
-        store_rows<C, kTile>(pre_r, xr, nvalid);
-        if (UNIT) {
-            store_row_scales<C, kTile>(pre_r, nrm);
-            if (intra) store_row_scales<C, kTile>(pre_w, nrm + kTile);
-        }
+        store_masses<C, kTile>(pre_r, mr);
         if (intra) {
-            store_rows<C, kTile>(pre_w, xw, nvalid);
+            store_masses<C, kTile>(pre_w, mw);
             if (MODE == kGradV) store_cotangent<C, kTile, C::YS>(pre_c, ytile, nullptr, a.L_real, nvalid);
             else store_rows<C, kTile, C::YS>(pre_y, ytile, nvalid);
         }
@@ -296,13 +422,12 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
         {
             const int side = w / 4, g = w % C::NG, jq = (w % 4) / C::NG;
             if (side == 0) {
-                const f32x16 z = project<C>(wp, xr, g, ln, h, UNIT ? nrm : nullptr);
-                const float dnl = write_assignments<C>(z, g, ln, h, a.soft(), true, phr, jq, C::JSTEP, 0, 1 << C::PHI,
-                                                       MODE == kForward ? mass : nullptr);
+                const float dnl = write_assignments<C>(f32x16{0}, g, ln, h, a.soft(), true, phr, jq, C::JSTEP, 0, 1 << C::PHI,
+                                                       MODE == kForward ? mass : nullptr, mr + ln * C::MS);
                 if (MODE == kForward) dnp[w * 64 + lane] = dnl;       // this lane's tables' share of the normaliser
             } else if (intra) {
-                const f32x16 z = project<C>(wp, xw, g, ln, h, UNIT ? nrm + kTile : nullptr);
-                write_assignments<C>(z, g, ln, h, a.soft(), ln < nvalid, phw, jq, C::JSTEP);
+                write_assignments<C>(f32x16{0}, g, ln, h, a.soft(), ln < nvalid, phw, jq, C::JSTEP, 0, 1 << C::PHI, nullptr,
+                                     mw + ln * C::MS);
             }
         }
         RACE_PHASE(2)
@@ -369,7 +494,7 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
         // the next tile's loads fly during the reduction and the epilogue (few registers are live there)
         if (it + 1 < ntiles) fetch(it + 1);
         RACE_PHASE(5)
-        __syncthreads();        // every wavefront is done with the tiles of this step
+        if (!S::kOwnRed) __syncthreads();       // every wavefront is done with the tiles of this step (whose bytes the partials reuse)
         RACE_PHASE(6)
 
         // ---- reduction over the bucket-row groups: partial read-outs through LDS, 16 bytes per store
@@ -396,43 +521,14 @@ void stream_kernel(KArgs a, const bf16raw *Xr, const bf16raw *Xw, const bf16raw 
         RACE_PHASE(7)
         __syncthreads();
         RACE_PHASE(8)
-        // ---- epilogue: thread = (token, pieces of 4 columns: 4i.. and, for d = 128, 64 + 4i..; consecutive
-        //      threads read consecutive 16-byte pieces of the partials): sum, normalise, store
-        {
-            constexpr int NP = C::D / 64;                // pieces of 4 columns per thread
-            const int tok = tid >> 4, c0 = (tid & 15) * 4;
-            float acc[NP][4];
-#pragma unroll
-            for (int c = 0; c < NP; ++c) acc[c][0] = acc[c][1] = acc[c][2] = acc[c][3] = 0.f;
-            float e = 0.f;
-#pragma unroll
-            for (int gg = 0; gg < 4; ++gg) {              // row groups (at most four) and the four reader wavefronts
-                const float *src = red + (gg * kTile + tok) * S::RS;
-                if (gg < C::RG) {
-#pragma unroll
-                    for (int c = 0; c < NP; ++c) {
-                        const float4 p4 = *reinterpret_cast<const float4 *>(src + c0 + 64 * c);
-                        acc[c][0] += p4.x; acc[c][1] += p4.y; acc[c][2] += p4.z; acc[c][3] += p4.w;
-                    }
-                }
-                if (MODE == kForward) {
-                    const float dpart = dnp[gg * 64 + tok] + dnp[gg * 64 + 32 + tok];
-                    e += gg < C::RG ? src[C::D] + dpart : dpart;
-                }
-            }
-            if (tok < nvalid) {
-                const float scale = (MODE == kForward) ? (e > 0.f ? __builtin_amdgcn_rcpf(e) : 0.f) : 1.0f;   // e = 0: hard hash, empty buckets
-                bf16raw *dst = Out + (t0 + tok) * C::D + c0;
-#pragma unroll
-                for (int c = 0; c < NP; ++c)
-                    *reinterpret_cast<u32x2 *>(dst + 64 * c) =
-                        u32x2{pack2(acc[c][0] * scale, acc[c][1] * scale), pack2(acc[c][2] * scale, acc[c][3] * scale)};
-                if (MODE == kForward && (tid & 15) == 0) den_out[t0 + tok] = e * inv_tables;
-            }
-        }
+        if (!S::kOwnRed) epilogue(t0, nvalid);
         RACE_PHASE(9)
-        __syncthreads();
+        if (!S::kOwnRed) __syncthreads();
         RACE_PHASE(10)
+    }
+    if (S::kOwnRed && ntiles > 0) {
+        const int64_t tp = tile_t0(ntiles - 1);
+        epilogue(tp, tile_nv(tp));
     }
     RACE_PHASE_PRINT("stream")
 }
@@ -592,35 +688,45 @@ KArgs make_kargs(const Plan &p, char *ws)
     a.Wp = reinterpret_cast<const bf16raw *>(ws + p.off_W);
     a.WpT = a.Wp + static_cast<size_t>(p.H) * C::LPP * C::D;
     a.state = reinterpret_cast<float *>(ws + p.off_stateA);
-    a.dZ = reinterpret_cast<bf16raw *>(ws + p.off_part);
+    a.Mq = reinterpret_cast<float *>(ws + p.off_massQ);
+    a.Mk = reinterpret_cast<float *>(ws + p.off_massK);
     a.dbeta_part = reinterpret_cast<float *>(ws + p.off_dbeta);
     return a;
 }
 
+// Hashed rows of Q (first == 0) and/or K: `count` tensors starting with `first`.
+template <class C>
+hipError_t launch_hash(const Plan &p, KArgs a, const void *Q, const void *K, int first, int count, hipStream_t st)
+{
+    auto kern = p.unit_qk ? hash_kernel<C, true> : hash_kernel<C, false>;
+    RACE_TRY(allow_lds(kern, HashLds<C>::total));
+    ProfileScope prof("hash_rows", st);
+    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>((p.N + kHashTokens - 1) / kHashTokens), p.BH, count), dim3(kHashThreads),
+                       HashLds<C>::total, st, a, static_cast<const bf16raw *>(Q), static_cast<const bf16raw *>(K), first);
+    return hipGetLastError();
+}
+
 template <class C, int QG>
-hipError_t launch_totals(const Plan &p, KArgs a, const void *X, const void *Y, const void *O, const float *den_in,
+hipError_t launch_totals(const Plan &p, KArgs a, const float *M, const void *Y, const void *O, const float *den_in,
                          hipStream_t st)
 {
-    auto kern = p.unit_qk ? totals_kernel<C, QG, true> : totals_kernel<C, QG, false>;
+    auto kern = totals_kernel<C, QG>;
     RACE_TRY(allow_lds(kern, TotalsLds<C>::total));
     ProfileScope prof(QG ? "stream_totals_qg" : "stream_totals_kv", st);
-    hipLaunchKernelGGL(kern, dim3(p.nseg, p.BH), dim3(kThreads), TotalsLds<C>::total, st, a,
-                       static_cast<const bf16raw *>(X), static_cast<const bf16raw *>(Y),
-                       static_cast<const bf16raw *>(O), den_in);
+    hipLaunchKernelGGL(kern, dim3(p.nseg, p.BH), dim3(kThreads), TotalsLds<C>::total, st, a, M,
+                       static_cast<const bf16raw *>(Y), static_cast<const bf16raw *>(O), den_in);
     return hipGetLastError();
 }
 
 template <class C, int MODE>
-hipError_t launch_stream(const Plan &p, KArgs a, const void *Xr, const void *Xw, const void *Y, const void *O,
+hipError_t launch_stream(const Plan &p, KArgs a, const float *Mr, const float *Mw, const void *Y, const void *O,
                          const float *den_in, void *Out, float *den_out, hipStream_t st)
 {
     static const char *const names[] = {"stream_totals_kv", "stream_totals_qg", "stream_forward", "stream_grad_v"};
-    auto kern = p.causal ? (p.unit_qk ? stream_kernel<C, MODE, true, false> : stream_kernel<C, MODE, false, false>)
-                         : (p.unit_qk ? stream_kernel<C, MODE, true, true> : stream_kernel<C, MODE, false, true>);
+    auto kern = p.causal ? stream_kernel<C, MODE, false> : stream_kernel<C, MODE, true>;
     RACE_TRY(allow_lds(kern, StreamLds<C>::total));
     ProfileScope prof(names[MODE], st);
-    hipLaunchKernelGGL(kern, dim3(p.nseg, p.BH), dim3(kThreads), StreamLds<C>::total, st, a,
-                       static_cast<const bf16raw *>(Xr), static_cast<const bf16raw *>(Xw),
+    hipLaunchKernelGGL(kern, dim3(p.nseg, p.BH), dim3(kThreads), StreamLds<C>::total, st, a, Mr, Mw,
                        static_cast<const bf16raw *>(Y), static_cast<const bf16raw *>(O), den_in,
                        static_cast<bf16raw *>(Out), den_out);
     return hipGetLastError();
@@ -637,40 +743,29 @@ template <class C>
 hipError_t fwd_t(const Plan &p, const void *Q, const void *K, const void *V, void *O, float *den, char *ws, hipStream_t st)
 {
     KArgs a = make_kargs<C>(p, ws);
-    RACE_TRY((launch_totals<C, 0>(p, a, K, V, nullptr, nullptr, st)));
+    RACE_TRY((launch_hash<C>(p, a, Q, K, 0, 2, st)));
+    RACE_TRY((launch_totals<C, 0>(p, a, a.Mk, V, nullptr, nullptr, st)));
     RACE_TRY(launch_scan(p, a.state, C::STATE, p.causal ? 0 : 2, st));
-    RACE_TRY((launch_stream<C, kForward>(p, a, Q, K, V, nullptr, nullptr, O, den, st)));
+    RACE_TRY((launch_stream<C, kForward>(p, a, a.Mq, a.Mk, V, nullptr, nullptr, O, den, st)));
     return hipSuccess;
 }
 
-// dphi and the chain rule through the soft assignment and W (grad_kernel).  Shapes whose bucket rows are
-// split over several workgroups by tables leave dZ in the workspace and finish with dX = dZ . W for all tables.
+// dphi and the chain rule through the soft assignment and W (grad_kernel).
 template <class C, int SIDE>
 hipError_t launch_grad(const Plan &p, KArgs a, const void *Q, const void *K, const void *V, const void *O,
                        const float *den, const void *dO, void *dX, hipStream_t st)
 {
-    // (the chain rule of the unit-norm option is applied where dX is formed, which a table split moves to dz_matmul_kernel)
-    if (GradCfg<C>::TSPLIT > 1 && p.unit_qk) return hipErrorNotSupported;
-    {
-        auto kern = p.causal ? (p.unit_qk ? grad_kernel<C, SIDE, true, true> : grad_kernel<C, SIDE, false, true>)
-                             : (p.unit_qk ? grad_kernel<C, SIDE, true, false> : grad_kernel<C, SIDE, false, false>);
-        const int lds = p.causal ? (p.unit_qk ? GradLds<C, true, true>::total : GradLds<C, false, true>::total)
-                                 : (p.unit_qk ? GradLds<C, true, false>::total : GradLds<C, false, false>::total);
-        RACE_TRY(allow_lds(kern, lds));
-        ProfileScope prof(SIDE == 0 ? "grad_q" : "grad_k", st);
-        hipLaunchKernelGGL(kern, dim3(p.nseg, p.BH, GradCfg<C>::TSPLIT), dim3(kThreads), lds, st, a,
-                           static_cast<const bf16raw *>(Q), static_cast<const bf16raw *>(K),
-                           static_cast<const bf16raw *>(V), static_cast<const bf16raw *>(O), den,
-                           static_cast<const bf16raw *>(dO), a.dZ, static_cast<bf16raw *>(dX));
-        RACE_TRY(hipGetLastError());
-    }
-    if (GradCfg<C>::TSPLIT > 1) {
-        ProfileScope prof("dz_matmul", st);
-        hipLaunchKernelGGL(dz_matmul_kernel<C>, dim3(static_cast<unsigned>((p.N + kTile * kDzTiles - 1) / (kTile * kDzTiles)), p.BH),
-                           dim3(64 * C::NT), 0, st, a, a.dZ, static_cast<bf16raw *>(dX));
-        RACE_TRY(hipGetLastError());
-    }
-    return hipSuccess;
+    auto kern = p.causal ? (p.unit_qk ? grad_kernel<C, SIDE, true, true> : grad_kernel<C, SIDE, false, true>)
+                         : (p.unit_qk ? grad_kernel<C, SIDE, true, false> : grad_kernel<C, SIDE, false, false>);
+    const int lds = p.causal ? (p.unit_qk ? GradLds<C, true, true>::total : GradLds<C, false, true>::total)
+                             : (p.unit_qk ? GradLds<C, true, false>::total : GradLds<C, false, false>::total);
+    RACE_TRY(allow_lds(kern, lds));
+    ProfileScope prof(SIDE == 0 ? "grad_q" : "grad_k", st);
+    hipLaunchKernelGGL(kern, dim3(p.nseg, p.BH), dim3(kThreads), lds, st, a,
+                       static_cast<const bf16raw *>(Q), static_cast<const bf16raw *>(K),
+                       static_cast<const bf16raw *>(V), static_cast<const bf16raw *>(O), den,
+                       static_cast<const bf16raw *>(dO), static_cast<bf16raw *>(dX));
+    return hipGetLastError();
 }
 
 template <class C>
@@ -680,15 +775,17 @@ hipError_t bwd_t(const Plan &p, const void *Q, const void *K, const void *V, con
     KArgs a = make_kargs<C>(p, ws);
     KArgs b = a;
     b.state = reinterpret_cast<float *>(ws + p.off_stateB);
-    // statistics of (phi_K, [V | 1]) at segment starts (the forward leaves exactly these behind: its scan is in
-    // place and its streaming pass only reads them); of (phi_Q, read-out cotangents) at segment ends
+    // the hashed rows of Q and K and the statistics of (phi_K, [V | 1]) at segment starts (the forward leaves exactly
+    // these behind: its scan is in place and its streaming pass only reads them); then the statistics of
+    // (phi_Q, read-out cotangents) at segment ends
     if (!p.fwd_state_kept) {
-        RACE_TRY((launch_totals<C, 0>(p, a, K, V, nullptr, nullptr, st)));
+        RACE_TRY((launch_hash<C>(p, a, Q, K, 0, 2, st)));
+        RACE_TRY((launch_totals<C, 0>(p, a, a.Mk, V, nullptr, nullptr, st)));
         RACE_TRY(launch_scan(p, a.state, C::STATE, p.causal ? 0 : 2, st));
     }
-    RACE_TRY((launch_totals<C, 1>(p, b, Q, dO, O, den, st)));
+    RACE_TRY((launch_totals<C, 1>(p, b, a.Mq, dO, O, den, st)));
     RACE_TRY(launch_scan(p, b.state, C::STATE, p.causal ? 1 : 2, st));
-    RACE_TRY((launch_stream<C, kGradV>(p, b, K, Q, dO, O, den, dV, nullptr, st)));
+    RACE_TRY((launch_stream<C, kGradV>(p, b, a.Mk, a.Mq, dO, O, den, dV, nullptr, st)));
     RACE_TRY((launch_grad<C, 0>(p, a, Q, K, V, O, den, dO, dQ, st)));
     RACE_TRY((launch_grad<C, 1>(p, b, Q, K, V, O, den, dO, dK, st)));
     if (dbeta) RACE_TRY(reduce_dbeta(p, a.dbeta_part, dbeta, st));
@@ -700,7 +797,8 @@ hipError_t buckets_t(const Plan &p, const void *K, const void *V, float *A, floa
                      char *ws, hipStream_t st)
 {
     KArgs a = make_kargs<C>(p, ws);
-    RACE_TRY((launch_totals<C, 0>(p, a, K, V, nullptr, nullptr, st)));
+    RACE_TRY((launch_hash<C>(p, a, nullptr, K, 1, 1, st)));
+    RACE_TRY((launch_totals<C, 0>(p, a, a.Mk, V, nullptr, nullptr, st)));
     const size_t total = static_cast<size_t>(p.BH) * p.LR * (C::D + 1);
     hipLaunchKernelGGL(bucket_tap_kernel<C>, dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0, st, a.state,
                        p.nseg, p.BH, p.L, p.P, A, Bsum, a_stride, b_stride);
@@ -785,10 +883,10 @@ bool mfma_pick(int d, int L, int P, int *Lc, int *Pc, int *pad)
     return best != 0;
 }
 
-size_t mfma_scratch_bytes(const Plan &p)
+size_t mfma_hashed_bytes(const Plan &p)
 {
 #define X(DD, PP_, LL, PD) if (p.d == DD && p.Pc == PP_ && p.Lc == LL && p.pad == PD) \
-        return GradCfg<Cfg<DD, PP_, LL, PD != 0>>::TSPLIT == 1 ? 0 : static_cast<size_t>(p.BH) * static_cast<size_t>(p.N) * Cfg<DD, PP_, LL, PD != 0>::LPP * 2;
+        return static_cast<size_t>(p.BH) * static_cast<size_t>(p.N) * Cfg<DD, PP_, LL, PD != 0>::LP * sizeof(float);
     RACE_SHAPES(X)
 #undef X
     return 0;
@@ -819,10 +917,7 @@ hipError_t mfma_fwd(const Plan &p, const void *Q, const void *K, const void *V, 
 
 int mfma_dbeta_parts(const Plan &p)
 {
-#define X(DD, PP_, LL, PD) if (p.d == DD && p.Pc == PP_ && p.Lc == LL && p.pad == PD) return p.nseg * GradCfg<Cfg<DD, PP_, LL, PD != 0>>::TSPLIT;
-    RACE_SHAPES(X)
-#undef X
-    return 0;
+    return p.nseg;
 }
 
 hipError_t mfma_bwd(const Plan &p, const void *Q, const void *K, const void *V, const void *O, const float *den,

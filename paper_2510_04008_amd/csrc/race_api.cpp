@@ -229,16 +229,22 @@ race_status_t make_plan(const race_attn_desc_t *desc, Plan *pl)
         p.nseg = static_cast<int>((n + len - 1) / len);
         p.bytes_W = align256(mfma_projection_bytes(p));
         p.bytes_state = align256(static_cast<size_t>(p.BH) * p.nseg * p.LRc * (p.d + 1) * sizeof(float));
-        p.bytes_part = align256(mfma_scratch_bytes(p));
+        p.bytes_part = 0;
+        p.bytes_mass = align256(mfma_hashed_bytes(p));
         p.dbeta_parts = mfma_dbeta_parts(p);
     }
     p.bytes_dbeta = align256(static_cast<size_t>(2) * p.BH * p.dbeta_parts * sizeof(float));
+    // [W | key/value statistics | hashed Q | hashed K] is what the forward pass uses (and leaves behind);
+    // [cotangent statistics | per-table partial results | parts of dbeta] follow
     p.off_W = 0;
     p.off_stateA = p.off_W + p.bytes_W;
-    p.off_stateB = p.off_stateA + p.bytes_state;
+    p.off_massQ = p.off_stateA + p.bytes_state;
+    p.off_massK = p.off_massQ + p.bytes_mass;
+    p.off_stateB = p.off_massK + p.bytes_mass;
     p.off_part = p.off_stateB + p.bytes_state;
     p.off_dbeta = p.off_part + p.bytes_part;
     p.total = p.off_dbeta + p.bytes_dbeta;
+    p.fwd_bytes = (p.family == kFamilyMfma) ? p.off_stateB : p.off_dbeta;
     *pl = p;
     return RACE_OK;
 }
@@ -344,8 +350,7 @@ race_status_t race_attn_fwd_static(const race_attn_desc_t *desc, const void *Q, 
     // smallest segment length tried.
     race_attn_desc_t fit = *desc;
     for (;;) {
-        const size_t need = (p.family == kFamilyMfma) ? p.off_stateB : p.off_dbeta;
-        if (need <= kStaticScratchBytes) break;
+        if (p.fwd_bytes <= kStaticScratchBytes) break;
         if (p.nseg <= 1) {
             g_last_error = "race_attn_fwd_static: the problem needs more than the 32 MiB of built-in scratch; use race_attn_fwd with a workspace";
             return RACE_ERR_WORKSPACE;
