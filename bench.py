@@ -39,38 +39,65 @@ def algorithmic_counts(w):
 
 
 def kernel_shares(w):
-    """Algorithmic flops per token-head credited to each kernel; they add up to 3 Proj + 6 U.
-    The segment-total and scan kernels exist only because the sequence is cut into segments and get 0."""
+    """Algorithmic work per token-head credited to each kernel, (flops, HBM bytes); the flops add up to 3 Proj + 6 U and
+    the bytes to 12 d s + 8.  The segment-total and scan kernels exist only because the sequence is cut into segments
+    and get 0.  Bytes: every tensor of the problem statement is credited once per pass, to the kernel that first
+    needs it (forward: Q, K to the hashing kernel, V, O, den to the streaming pass; backward: dO, O, den, dV to the
+    dV pass, Q, dQ to the dQ pass, K, V, dK to the dK pass)."""
     proj, U, _ = algorithmic_counts(w)
+    s = 2 if w.dtype == "bf16" else 4
+    ds = w.d * s
     return {
-        "stream_forward": proj + 2 * U,      # projections, accumulate, read-out
-        "stream_grad_v": proj + 2 * U,       # projections again, cotangent statistics, dV read-out
-        "grad_q": U + proj / 2,              # dphi_Q, the chain rule through the soft assignment, dQ = dz . W
-        "grad_k": U + proj / 2,              # dphi_K, same
-        "stream_totals_kv": 0.0, "stream_totals_qg": 0.0, "segment_scan": 0.0,
+        "hash_rows": (proj, 2 * ds),                 # projections of Q and K
+        "stream_forward": (2 * U, 2 * ds + 4),       # accumulate, read-out
+        "stream_grad_v": (2 * U, 3 * ds + 4),        # cotangent statistics, dV read-out
+        "grad_q": (U + proj, 2 * ds),                # dphi_Q, projection of Q again (tanh and its derivative), dQ = dz . W
+        "grad_k": (U + proj, 3 * ds),                # dphi_K, same
+        "stream_totals_kv": (0.0, 0.0), "stream_totals_qg": (0.0, 0.0), "segment_scan": (0.0, 0.0),
         # generic family: one replay kernel forward; the key/value kernel forms dV and dK
-        "simple_fwd_replay": proj + 2 * U,
-        "simple_bwd_keyvalue": proj + 2 * U + U + proj / 2,
-        "simple_bwd_query": U + proj / 2,
+        "simple_fwd_replay": (proj + 2 * U, 4 * ds + 4),
+        "simple_bwd_keyvalue": (proj + 2 * U + U + proj / 2, 6 * ds + 4),
+        "simple_bwd_query": (U + proj / 2, 2 * ds),
     }
 
 
-# HBM bytes per token-head and launch, measured with rocprofv3 --pmc FETCH_SIZE and --pmc WRITE_SIZE (two runs of
-# this script at C5, each counter scaled by what it reads for the library's plain copy kernel of 1 GiB: 2.000 and
-# 1.000); valid for the shape they were measured on.
-MEASURED_TRAFFIC = {
-    ("bf16", 128, 8, 6, True): {
-        "stream_totals_kv": 514.7, "segment_scan": 5.4, "stream_forward": 1030.7, "stream_totals_qg": 774.7,
-        "stream_grad_v": 1030.6, "grad_q": 1542.7, "grad_k": 1542.7,
-    },
-}
+def source_hash() -> str:
+    """SHA-256 over the library's sources: what a stored counter measurement is valid for."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2510_04008_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hip", ".h", ".cpp")):
+            h.update(name.encode())
+            h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()
+
+
+def measured_traffic(w):
+    """HBM bytes per token-head and launch, per kernel, from the committed rocprofv3 --pmc summary of this workload
+    (FETCH_SIZE and WRITE_SIZE, each scaled by the same counter's reading for a plain copy of known size), or
+    (None, reason): the summary names the sources it was measured on, and a summary of other sources is not used."""
+    import re
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_%s_pmc.md" % w.name.split("-")[0].lower())
+    if not os.path.exists(path):
+        return None, "no counter summary for this workload under profiles/"
+    text = open(path).read()
+    m = re.search(r"source-sha256:\s*([0-9a-f]{64})", text)
+    t = re.search(r"bytes-per-token-head:\s*(.+)", text)
+    if not m or not t:
+        return None, "%s holds no machine-readable table" % os.path.relpath(path, ROOT)
+    if m.group(1) != source_hash():
+        return None, "%s was measured on other kernel sources (re-run the two --pmc passes it names)" % os.path.relpath(path, ROOT)
+    table = {k: float(v) for k, v in (kv.split("=") for kv in t.group(1).split())}
+    return table, os.path.relpath(path, ROOT)
 
 
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--print-source-hash", action="store_true", help="print the hash a counter summary must carry, and exit")
     ap.add_argument("--workload", default="C5")
     ap.add_argument("--tokens", type=int, default=0, help="override N of the workload")
     ap.add_argument("--chunk", type=int, default=-1, help="override the scan segment length in tokens (0 = let the library choose)")
@@ -84,6 +111,9 @@ def main() -> int:
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="before the warm-up, run one plain copy kernel of this many MiB (scale for byte counters)")
     args = ap.parse_args()
+    if args.print_source_hash:
+        print(source_hash())
+        return 0
     if args.gpus != 1:
         sys.stderr.write("bench.py: this build runs on one GPU; --gpus %d is not supported "
                          "(the path has no collectives: a sequence would shard by batch and heads, or along N with the bucket "
@@ -160,16 +190,23 @@ def main() -> int:
         step()
     torch.cuda.synchronize()
     ra.race_attn_profile_enable(True)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record()
+    for i in range(args.steps):
         step()
+        marks[i + 1].record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     prof = ra.race_attn_profile_read()
     ra.race_attn_profile_enable(False)
 
-    ms_per_step = 1e3 * elapsed / args.steps
-    tokens_per_s = w.B * w.N * args.steps / elapsed
+    # the step time is the median over the timed steps (HIP events between steps on the stream the kernels run on); the
+    # mean over the same steps, from the host clock around the whole region, is reported next to it
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
+    ms_per_step = per_step[len(per_step) // 2] if len(per_step) % 2 else 0.5 * (per_step[len(per_step) // 2 - 1] + per_step[len(per_step) // 2])
+    ms_per_step_mean = 1e3 * elapsed / args.steps
+    tokens_per_s = w.B * w.N / (1e-3 * ms_per_step)
     proj, U, bytes_th = algorithmic_counts(w)
     token_heads = w.B * w.H * w.N
     step_flops = (3 * proj + 6 * U) * token_heads
@@ -179,20 +216,31 @@ def main() -> int:
     kernels = {}
     if prof:
         shares = kernel_shares(w)
+        table, table_note = measured_traffic(w) if family == 2 else (None, "no counter summary for the generic kernels")
+        mfma = family == 2
+        flop_peak = PEAK_BF16_FLOPS if mfma else PEAK_FP32_VECTOR_FLOPS
         for name, (ms, n) in prof.items():
-            kernels[name] = {"avg_ms": ms / n, "launches_per_step": n / args.steps,
-                             "ms_per_step": ms / args.steps}
+            kernels[name] = {"avg_ms": ms / n, "launches_per_step": n / args.steps, "ms_per_step": ms / args.steps}
+            flops, nbytes = shares.get(name, (0.0, 0.0))
+            if flops or nbytes:
+                kernels[name]["frac_of_%s_roof" % ("mfma" if mfma else "alu")] = flops * token_heads / (1e-3 * ms / n) / flop_peak
+                kernels[name]["frac_of_hbm_roof"] = nbytes * token_heads / (1e-3 * ms / n) / PEAK_HBM_BYTES
         name = max(prof, key=lambda k: prof[k][0])
         avg_s = 1e-3 * prof[name][0] / prof[name][1]
-        flops = shares.get(name, 0.0) * token_heads
-        achieved = flops / avg_s / 1e12
-        measured = MEASURED_TRAFFIC.get((w.dtype, w.d, w.L, w.P, bool(w.causal)), {}).get(name)
-        traffic = measured * token_heads if measured is not None else None      # bytes per launch
-        mfma = family == 2
-        peak = (PEAK_BF16_FLOPS if mfma else PEAK_FP32_VECTOR_FLOPS) / 1e12
-        roofline = {"kernel": name, "bound": "mfma" if mfma else "alu", "achieved": achieved, "peak": peak,
-                    "unit": "TFLOP/s", "frac": achieved / peak, "traffic": traffic,
-                    "avg_launch_ms": 1e3 * avg_s, "algorithmic_flops_per_launch": flops}
+        flops, nbytes = (x * token_heads for x in shares.get(name, (0.0, 0.0)))
+        # the binding roof of the kernel's credited work is the one that takes longer at the published peaks
+        t_flop, t_hbm = flops / flop_peak, nbytes / PEAK_HBM_BYTES
+        traffic = table[name] * token_heads if table and name in table else None       # bytes per launch
+        if t_hbm >= t_flop:
+            roofline = {"kernel": name, "bound": "hbm", "achieved": nbytes / avg_s / 1e9, "peak": PEAK_HBM_BYTES / 1e9,
+                        "unit": "GB/s", "frac": nbytes / avg_s / PEAK_HBM_BYTES}
+        else:
+            roofline = {"kernel": name, "bound": "mfma" if mfma else "alu", "achieved": flops / avg_s / 1e12,
+                        "peak": flop_peak / 1e12, "unit": "TFLOP/s", "frac": flops / avg_s / flop_peak}
+        roofline.update({"traffic": traffic, "traffic_source": table_note, "avg_launch_ms": 1e3 * avg_s,
+                         "algorithmic_flops_per_launch": flops, "algorithmic_bytes_per_launch": nbytes,
+                         "frac_of_hbm_roof": nbytes / avg_s / PEAK_HBM_BYTES,
+                         "frac_of_%s_roof" % ("mfma" if mfma else "alu"): flops / avg_s / flop_peak})
 
     cpu_baseline = None
     if not args.no_cpu_baseline:
@@ -226,7 +274,7 @@ def main() -> int:
     out = {
         "metric": "RACE attn fwd+bwd tokens/sec at N=1M-12M (B=1,H=4,d=128); % MFMA/HBM roof",
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": ms_per_step, "ms_per_step_mean": ms_per_step_mean, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "N": w.N, "d": w.d, "L": w.L, "P": w.P,
                    "sharpening": w.sharpening, "causal": w.causal, "unit_qk": w.unit_qk, "kernel_family": family,
@@ -234,8 +282,9 @@ def main() -> int:
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "step_roofline": {"algorithmic_tflop": step_flops / 1e12, "algorithmic_gb": step_bytes / 1e9,
-                          "frac_of_mfma_roof": step_flops / (elapsed / args.steps) / PEAK_BF16_FLOPS,
-                          "frac_of_hbm_roof": step_bytes / (elapsed / args.steps) / PEAK_HBM_BYTES},
+                          "bound": "hbm" if step_bytes / PEAK_HBM_BYTES >= step_flops / (PEAK_BF16_FLOPS if family == 2 else PEAK_FP32_VECTOR_FLOPS) else ("mfma" if family == 2 else "alu"),
+                          "frac_of_%s_roof" % ("mfma" if family == 2 else "alu"): step_flops / (1e-3 * ms_per_step) / (PEAK_BF16_FLOPS if family == 2 else PEAK_FP32_VECTOR_FLOPS),
+                          "frac_of_hbm_roof": step_bytes / (1e-3 * ms_per_step) / PEAK_HBM_BYTES},
         "attainable": attainable,
         "kernels": kernels,
     }
