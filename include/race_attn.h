@@ -216,7 +216,12 @@ const char *race_status_string(race_status_t status);
 const char *race_attn_last_error(void);
 
 /* Which kernel family a descriptor is served by: 0 = invalid/unsupported, 1 = generic fp32-math
- * kernels, 2 = bf16 MFMA kernels.  Informational (benchmarks and tests report it). */
+ * kernels, 2 = bf16 MFMA kernels.  Informational (benchmarks and tests report it).
+ * The generic kernels serve fp32 tensors and every bf16 shape without an MFMA instantiation; they keep per-table
+ * partial results of every token in the workspace (3 * B*H*L*N*d floats for the backward pass), and a descriptor whose
+ * partial results would exceed 16 GiB is RACE_ERR_UNSUPPORTED (e.g. fp32, d = 64, L = 4: B*H*N beyond 5.6 million).
+ * Test switch: with RACE_ATTN_FORCE_GENERIC=1 in the environment every descriptor is planned on the generic kernels
+ * (the tests use it to run one problem on both families; it is read at every call). */
 int race_attn_kernel_family(const race_attn_desc_t *desc);
 
 /* Tokens per scan segment the library uses for this descriptor (desc->chunk rounded to what the kernels take, or

@@ -20,6 +20,9 @@ namespace {
 
 thread_local std::string g_last_error;
 
+// largest per-table partial-result area the generic kernels are offered (their workspace grows like L * N * d)
+constexpr size_t kGenericPartialLimit = static_cast<size_t>(16) << 30;
+
 size_t align256(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
 
 // ---------------------------------------------------------------- Philox-4x32-10 + Box-Muller
@@ -217,6 +220,9 @@ race_status_t make_plan(const race_attn_desc_t *desc, Plan *pl)
         const size_t fwd_part = static_cast<size_t>(p.BH) * p.L * n * (p.d + 1) * sizeof(float);
         const size_t bwd_part = static_cast<size_t>(p.BH) * p.L * n * p.d * sizeof(float) * 3;
         p.bytes_part = align256(fwd_part > bwd_part ? fwd_part : bwd_part);
+        // these kernels keep per-table partial results of every token in the workspace (L * N * d floats): they are
+        // the fp32 reference path, not a long-context path
+        if (p.bytes_part > kGenericPartialLimit) return RACE_ERR_UNSUPPORTED;
         p.dbeta_parts = p.L * p.nseg;
     } else {
         // two workgroups' worth of segments per CU and head-batch; multiples of the 32-token tile

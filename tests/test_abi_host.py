@@ -220,3 +220,30 @@ def test_forward_on_built_in_scratch_checks_everything_on_the_host():
     many = (ctypes.c_uint64 * 200)(*range(200))
     assert lib.race_attn_fwd_static(ctypes.byref(big), p[0], p[1], p[2], many, p[3], p[4], None) == ra.RACE_ERR_WORKSPACE
     assert b"32 MiB" in lib.race_attn_last_error()
+
+
+def test_generic_kernels_refuse_long_contexts():
+    """The generic kernels keep per-table partial results of every token (L * N * d floats per pass): beyond 16 GiB of
+    them the descriptor is unsupported instead of asking for a workspace the design was never meant for."""
+    ok = _desc(N=1 << 20)                                  # fp32, H = 2, d = 64, L = 4: 6 GiB of partial results
+    assert ra.race_attn_kernel_family(ok) == 1 and ra.race_attn_workspace_bytes(ok) > 0
+    big = _desc(N=1 << 22)                                 # 24 GiB
+    assert ra.race_attn_kernel_family(big) == 0 and ra.race_attn_workspace_bytes(big) == 0
+    fake = ctypes.c_void_p(256)
+    seeds = (ctypes.c_uint64 * 2)(1, 2)
+    st = ra.lib().race_attn_fwd(ctypes.byref(big), fake, fake, fake, seeds, fake, fake, fake, 1 << 50, None)
+    assert st == ra.RACE_ERR_UNSUPPORTED
+    # the same shape in bf16 at the MFMA family's headline shape has no such limit
+    long_bf16 = ra.make_desc(1, 4, 1 << 25, 128, 8, 6, 8.0, True, ra.RACE_BF16)
+    assert ra.race_attn_kernel_family(long_bf16) == 2 and ra.race_attn_workspace_bytes(long_bf16) > 0
+
+
+def test_the_force_generic_switch_is_read_at_every_call():
+    d = ra.make_desc(1, 2, 1000, 128, 8, 6, 8.0, True, ra.RACE_BF16)
+    assert ra.race_attn_kernel_family(d) == 2
+    os.environ["RACE_ATTN_FORCE_GENERIC"] = "1"
+    try:
+        assert ra.race_attn_kernel_family(d) == 1
+    finally:
+        del os.environ["RACE_ATTN_FORCE_GENERIC"]
+    assert ra.race_attn_kernel_family(d) == 2
