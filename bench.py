@@ -107,6 +107,9 @@ def main() -> int:
                     help="time race_attn_bwd (derives the key/value statistics again) instead of race_attn_bwd_saved")
     ap.add_argument("--unit-qk", action="store_true",
                     help="descriptor option unit_qk: the layer divides the rows of Q and K by their norms (not the headline workload)")
+    ap.add_argument("--noncausal", action="store_true", help="run the workload's shape without the causal mask (Algorithm 1)")
+    ap.add_argument("--forward-only", action="store_true", help="time race_attn_fwd alone (inference; not the headline metric)")
+    ap.add_argument("--sharpening", type=float, default=None, help="override the temperature (inf = hard hash, forward only)")
     ap.add_argument("--no-attainable", action="store_true", help="skip the copy / MFMA-loop calibration launches")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="before the warm-up, run one plain copy kernel of this many MiB (scale for byte counters)")
@@ -132,6 +135,12 @@ def main() -> int:
         w = dataclasses.replace(w, chunk=args.chunk)
     if args.unit_qk:
         w = dataclasses.replace(w, name=w.name + "+unit_qk", unit_qk=True)
+    if args.noncausal:
+        w = dataclasses.replace(w, name=w.name.replace("causal", "noncausal"), causal=False)
+    if args.sharpening is not None:
+        w = dataclasses.replace(w, name=w.name + "+beta=%g" % args.sharpening, sharpening=args.sharpening)
+        if args.sharpening == float("inf"):
+            args.forward_only = True
     dev = "cuda:0"
     torch.cuda.set_device(0)
     desc = ra.make_desc(w.B, w.H, w.N, w.d, w.L, w.P, w.sharpening, w.causal,
@@ -156,6 +165,8 @@ def main() -> int:
     # --bwd-recompute times race_attn_bwd, which derives them again from K and V.
     def step():
         ra.race_attn_fwd(desc, Q, K, V, seeds, O=O, den=den, workspace=ws)
+        if args.forward_only:
+            return
         if args.bwd_recompute:
             ra.race_attn_bwd(desc, Q, K, V, O, den, dO, seeds, dQ=dQ, dK=dK, dV=dV, workspace=ws)
         else:
@@ -243,7 +254,7 @@ def main() -> int:
                          "frac_of_%s_roof" % ("mfma" if mfma else "alu"): flops / avg_s / flop_peak})
 
     cpu_baseline = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.forward_only:
         from oracle import race_oracle as ro
         from oracle import stream as oracle_stream
         n0 = min(w.N, args.cpu_sample_tokens)
@@ -272,13 +283,14 @@ def main() -> int:
                              % (err(O, Oo), err(den, deno), err(dQ, go[0])))
 
     out = {
-        "metric": "RACE attn fwd+bwd tokens/sec at N=1M-12M (B=1,H=4,d=128); % MFMA/HBM roof",
+        "metric": ("RACE attn forward tokens/sec (not the headline metric)" if args.forward_only else
+                   "RACE attn fwd+bwd tokens/sec at N=1M-12M (B=1,H=4,d=128); % MFMA/HBM roof"),
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "ms_per_step_mean": ms_per_step_mean, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "N": w.N, "d": w.d, "L": w.L, "P": w.P,
                    "sharpening": w.sharpening, "causal": w.causal, "unit_qk": w.unit_qk, "kernel_family": family,
-                   "backward": "race_attn_bwd" if args.bwd_recompute else "race_attn_bwd_saved"},
+                   "backward": None if args.forward_only else ("race_attn_bwd" if args.bwd_recompute else "race_attn_bwd_saved")},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "step_roofline": {"algorithmic_tflop": step_flops / 1e12, "algorithmic_gb": step_bytes / 1e9,

@@ -61,6 +61,12 @@ CASES = [
     Workload("hard-few-keys", 1, 2, 5, 128, 8, 6, INF, False, "bf16"),            # empty buckets: den = 0, O = 0
     Workload("hard-encoder", 2, 2, 900, 64, 16, 4, INF, False, "bf16"),
     Workload("hard-padded-3x3", 1, 2, 1000, 128, 3, 3, INF, True, "bf16", normalize_qk=True, chunk=256),
+    # the paper's grid shapes (padded execution on the small compiled shapes)
+    Workload("hard-counters-4x4", 1, 2, 1500, 128, 4, 4, INF, True, "bf16", normalize_qk=True, chunk=512),
+    Workload("hard-counters-4x4-noncausal", 2, 2, 777, 128, 4, 4, INF, False, "bf16", chunk=256),
+    Workload("hard-counters-2x2", 1, 3, 1000, 128, 2, 2, INF, True, "bf16", chunk=128),
+    Workload("hard-counters-d64", 1, 2, 900, 64, 4, 4, INF, True, "bf16", normalize_qk=True, chunk=160),
+    Workload("hard-counters-one-token", 1, 1, 1, 128, 4, 4, INF, True, "bf16"),
     Workload("hard-generic-f32", 1, 1, 300, 64, 4, 4, INF, True, "f32", chunk=64),
     Workload("hard-generic-f32-noncausal", 1, 2, 200, 64, 4, 4, INF, False, "f32"),
 ]

@@ -191,3 +191,9 @@ def test_headline_shape_1m_tokens_every_token_all_five_tensors():
 def test_paper_grid_1m_tokens(w):
     # the paper's own scaling grid at N = 2^20, on the padded 64-row shape, in the benchmark's launch configuration
     _long_context(w)
+
+
+def test_paper_grid_16m_tokens():
+    # (P, L) = (4, 4) at 2^24 tokens, beyond the 12 M the paper reports for its own runs: 17 GB per tensor, element offsets
+    # up to 8.6e9; O, Den, dQ across the first three segment boundaries, dK, dV across the last
+    _long_context(synth.G44.scaled(1 << 24, "G44-causal-bf16-16M"))
