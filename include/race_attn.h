@@ -143,10 +143,12 @@ race_status_t race_attn_bwd_beta(const race_attn_desc_t *desc, const void *Q, co
                                  void *workspace, size_t workspace_bytes, race_stream_t stream);
 
 /* The backward pass for a caller that kept the forward's workspace.  race_attn_fwd leaves in the workspace what
- * the backward pass would otherwise derive again from K and V: the packed W and the key/value bucket statistics
- * (A, B of Algorithm 1, step 5; in the causal case Algorithm 2's running statistics at the start of every scan
- * segment).  This entry point reads them instead of recomputing them: one pass over K and V fewer.
- * Contract: `workspace` is the buffer that the last race_attn_fwd with the same desc, K, V and proj_seeds wrote,
+ * the backward pass would otherwise derive again from Q, K and V: the packed W, the hashed rows of Q and K (one
+ * float per token, table and hyperplane: all that the soft assignment of Algorithm 1, step 4 depends on) and the
+ * key/value bucket statistics (A, B of Algorithm 1, step 5; in the causal case Algorithm 2's running statistics at
+ * the start of every scan segment).  This entry point reads them instead of recomputing them: one projection pass
+ * over Q and K and one accumulation pass over K and V fewer.
+ * Contract: `workspace` is the buffer that the last race_attn_fwd with the same desc, Q, K, V and proj_seeds wrote,
  * nothing has written to it since, and this call is stream-ordered after that forward.  A workspace that does not
  * hold that forward's data gives wrong gradients, never an out-of-bounds access.  Arguments, outputs, dbeta
  * (may be NULL) and error behaviour are those of race_attn_bwd_beta, whose results it reproduces bit for bit.
