@@ -222,6 +222,9 @@ def main() -> int:
     token_heads = w.B * w.H * w.N
     step_flops = (3 * proj + 6 * U) * token_heads
     step_bytes = bytes_th * token_heads
+    if args.forward_only:       # the forward pass alone: Proj + 2 U, and Q, K, V read, O and den written
+        step_flops = (proj + 2 * U) * token_heads
+        step_bytes = (4 * w.d * (2 if w.dtype == "bf16" else 4) + 4) * token_heads
 
     roofline = None
     kernels = {}
