@@ -185,16 +185,24 @@ def main() -> int:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 256)
         dst = torch.empty_like(src)
         sink = torch.empty(8192 * 256, dtype=torch.float32, device=dev)
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(8)]
         ra.race_attn_calibration_copy(dst, src)
         ra.race_attn_calibration_mfma(8192, 64, sink)
         ev[0].record(); ra.race_attn_calibration_copy(dst, src); ev[1].record()
         ev[2].record(); flop = ra.race_attn_calibration_mfma(8192, 2048, sink); ev[3].record()
+        # the same loop with 8 and 16 independent vector multiplies after every matrix instruction: what is left of the
+        # matrix rate for a kernel that builds its operands with the vector ALU (these kernels issue 11-17 vector
+        # instructions per matrix instruction)
+        ev[4].record(); ra.race_attn_calibration_mfma(8192, 2048, sink, vector_ops=8); ev[5].record()
+        ev[6].record(); ra.race_attn_calibration_mfma(8192, 2048, sink, vector_ops=16); ev[7].record()
         torch.cuda.synchronize()
         attainable = {"hbm_copy_GBps": 2 * src.numel() / (1e-3 * ev[0].elapsed_time(ev[1])) / 1e9,
                       "mfma_bf16_TFLOPs": flop / (1e-3 * ev[2].elapsed_time(ev[3])) / 1e12,
+                      "mfma_bf16_TFLOPs_with_8_vector_ops_each": flop / (1e-3 * ev[4].elapsed_time(ev[5])) / 1e12,
+                      "mfma_bf16_TFLOPs_with_16_vector_ops_each": flop / (1e-3 * ev[6].elapsed_time(ev[7])) / 1e12,
                       "note": "1 GiB copy kernel (read + write counted) and a register-operand "
-                              "v_mfma_f32_32x32x16_bf16 loop, one launch each, HIP events"}
+                              "v_mfma_f32_32x32x16_bf16 loop (alone, and with 8 or 16 independent v_mul_f32 after every "
+                              "matrix instruction), one launch each, HIP events"}
         del src, dst, sink
 
     for _ in range(args.warmup):

@@ -251,9 +251,11 @@ race_status_t race_attn_calibration_copy(void *dst, const void *src, size_t byte
  * published peak).  Launches calibration_mfma_kernel: `workgroups` workgroups of 256 threads, each wavefront
  * issuing `iters` rounds of four independent v_mfma_f32_32x32x16_bf16 on register operands, i.e.
  * workgroups * 4 * iters * 4 * 32768 floating-point operations in all; every lane then stores one float to
- * sink (DEVICE, workgroups * 256 floats) so that the work cannot be optimised away.  workgroups and iters must
- * be in 1 .. 2^20. */
-race_status_t race_attn_calibration_mfma(int workgroups, int iters, float *sink, race_stream_t stream);
+ * sink (DEVICE, workgroups * 256 floats) so that the work cannot be optimised away.  vector_ops (0, 4, 8 or 16):
+ * that many independent v_mul_f32 on registers of the same wavefront follow every matrix instruction, which
+ * measures how much vector work the matrix pipeline hides (the flop count returned by the binding counts the
+ * matrix instructions only).  workgroups and iters must be in 1 .. 2^20. */
+race_status_t race_attn_calibration_mfma(int workgroups, int iters, int vector_ops, float *sink, race_stream_t stream);
 
 #ifdef __cplusplus
 }

@@ -82,7 +82,7 @@ def lib() -> ctypes.CDLL:
         L.race_attn_step_workspace_bytes.restype = ctypes.c_size_t
         L.race_attn_step.argtypes = [dp, vp, vp, vp, u64p, fp, vp, fp, vp, ctypes.c_size_t, vp]
         L.race_attn_step.restype = ctypes.c_int
-        L.race_attn_calibration_mfma.argtypes = [ctypes.c_int, ctypes.c_int, fp, vp]
+        L.race_attn_calibration_mfma.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, fp, vp]
         L.race_attn_calibration_mfma.restype = ctypes.c_int
         L.race_status_string.argtypes = [ctypes.c_int]
         L.race_status_string.restype = ctypes.c_char_p
@@ -356,11 +356,12 @@ def race_attn_calibration_copy(dst, src, stream=None) -> None:
         raise RaceAttnError(st, "race_attn_calibration_copy")
 
 
-def race_attn_calibration_mfma(workgroups: int, iters: int, sink, stream=None) -> int:
-    """Dense bf16 MFMA loop; sink: float32 device tensor of workgroups * 256 elements.  Returns the flop count."""
+def race_attn_calibration_mfma(workgroups: int, iters: int, sink, stream=None, vector_ops: int = 0) -> int:
+    """Dense bf16 MFMA loop, `vector_ops` (0, 4, 8, 16) independent vector multiplies after every matrix instruction;
+    sink: float32 device tensor of workgroups * 256 elements.  Returns the flop count of the matrix instructions."""
     if sink.numel() < workgroups * 256:
         raise ValueError("sink too small")
-    st = lib().race_attn_calibration_mfma(int(workgroups), int(iters), sink.data_ptr(), _stream(stream))
+    st = lib().race_attn_calibration_mfma(int(workgroups), int(iters), int(vector_ops), sink.data_ptr(), _stream(stream))
     if st != RACE_OK:
         raise RaceAttnError(st, "race_attn_calibration_mfma")
     return workgroups * 4 * iters * 4 * 32768

@@ -82,7 +82,7 @@ hipError_t reduce_dbeta(const Plan &p, const float *part, float *dbeta, hipStrea
 // Plain copy of known size (simple_kernels.hip); bytes is a multiple of 16.
 hipError_t calibration_copy(void *dst, const void *src, size_t bytes, hipStream_t st);
 // Dense bf16 MFMA loop on register operands (mfma_kernels.hip).
-hipError_t calibration_mfma(int workgroups, int iters, float *sink, hipStream_t st);
+hipError_t calibration_mfma(int workgroups, int iters, int vector_ops, float *sink, hipStream_t st);
 
 // ---- simple family (simple_kernels.hip)
 hipError_t simple_fwd(const Plan &p, const void *Q, const void *K, const void *V, void *O, float *den,

@@ -641,21 +641,33 @@ __global__ __launch_bounds__(kThreads) void hash_tap_kernel(KArgs a, const bf16r
 }
 
 // Attainable matrix rate: four independent accumulators per wavefront, operands from registers only.
+// NV > 0: every matrix instruction is followed by NV independent vector multiplies on registers of the same
+// wavefront (eight dependency chains), the mix of a kernel that builds its operands with the vector ALU.
+template <int NV>
 __global__ __launch_bounds__(256) void calibration_mfma_kernel(int iters, float *sink)
 {
     const uint32_t seed = 0x3F803F80u ^ (threadIdx.x & 1);          // bf16 values near one
     u32x4 a = {seed, seed, seed, seed}, b = {seed, seed, seed, seed};
-    f32x16 c0 = {0}, c1 = {0}, c2 = {0}, c3 = {0};
+    f32x16 c[4] = {f32x16{0}, f32x16{0}, f32x16{0}, f32x16{0}};
+    float v[8];
+    const float m = 1.0f + 1e-7f * static_cast<float>(threadIdx.x & 3);
+#pragma unroll
+    for (int r = 0; r < 8; ++r) v[r] = 1.0f + static_cast<float>(r);
     for (int i = 0; i < iters; ++i) {
-        c0 = mma(a, b, c0);
-        c1 = mma(a, b, c1);
-        c2 = mma(a, b, c2);
-        c3 = mma(a, b, c3);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            c[k] = mma(a, b, c[k]);
+            // (as instructions: plain C multiplies by a loop-invariant factor would be folded into one per chain)
+#pragma unroll
+            for (int r = 0; r < NV; ++r) asm volatile("v_mul_f32 %0, %0, %1" : "+v"(v[r % 8]) : "v"(m));
+        }
     }
-    const f32x16 c = (c0 + c1) + (c2 + c3);
+    const f32x16 cs = (c[0] + c[1]) + (c[2] + c[3]);
     float s = 0.f;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) s += c[v];
+    for (int e = 0; e < 16; ++e) s += cs[e];
+#pragma unroll
+    for (int r = 0; r < 8; ++r) s += v[r];
     sink[static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x] = s;
 }
 
@@ -857,9 +869,15 @@ void pack_t(const Plan &p, const float *W, void *image)
 
 }  // namespace
 
-hipError_t calibration_mfma(int workgroups, int iters, float *sink, hipStream_t st)
+hipError_t calibration_mfma(int workgroups, int iters, int vector_ops, float *sink, hipStream_t st)
 {
-    hipLaunchKernelGGL(mfma::calibration_mfma_kernel, dim3(workgroups), dim3(256), 0, st, iters, sink);
+    switch (vector_ops) {
+    case 0: hipLaunchKernelGGL(mfma::calibration_mfma_kernel<0>, dim3(workgroups), dim3(256), 0, st, iters, sink); break;
+    case 4: hipLaunchKernelGGL(mfma::calibration_mfma_kernel<4>, dim3(workgroups), dim3(256), 0, st, iters, sink); break;
+    case 8: hipLaunchKernelGGL(mfma::calibration_mfma_kernel<8>, dim3(workgroups), dim3(256), 0, st, iters, sink); break;
+    case 16: hipLaunchKernelGGL(mfma::calibration_mfma_kernel<16>, dim3(workgroups), dim3(256), 0, st, iters, sink); break;
+    default: return hipErrorInvalidValue;
+    }
     return hipGetLastError();
 }
 

@@ -597,10 +597,11 @@ race_status_t race_attn_calibration_copy(void *dst, const void *src, size_t byte
     return RACE_OK;
 }
 
-race_status_t race_attn_calibration_mfma(int workgroups, int iters, float *sink, race_stream_t stream)
+race_status_t race_attn_calibration_mfma(int workgroups, int iters, int vector_ops, float *sink, race_stream_t stream)
 {
     if (!sink || workgroups < 1 || iters < 1 || workgroups > (1 << 20) || iters > (1 << 20)) return RACE_ERR_INVALID_ARG;
-    hipError_t e = calibration_mfma(workgroups, iters, sink, reinterpret_cast<hipStream_t>(stream));
+    if (vector_ops != 0 && vector_ops != 4 && vector_ops != 8 && vector_ops != 16) return RACE_ERR_INVALID_ARG;
+    hipError_t e = calibration_mfma(workgroups, iters, vector_ops, sink, reinterpret_cast<hipStream_t>(stream));
     if (e != hipSuccess) {
         g_last_error = std::string("calibration_mfma: ") + hipGetErrorString(e);
         return RACE_ERR_HIP;

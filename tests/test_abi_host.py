@@ -171,10 +171,11 @@ def test_calibration_copy_rejects_bad_arguments_on_the_host():
 def test_calibration_mfma_rejects_bad_arguments_on_the_host():
     lib = ra.lib()
     fake = ctypes.c_void_p(4096)
-    assert lib.race_attn_calibration_mfma(1, 1, None, None) == ra.RACE_ERR_INVALID_ARG
-    assert lib.race_attn_calibration_mfma(0, 1, fake, None) == ra.RACE_ERR_INVALID_ARG
-    assert lib.race_attn_calibration_mfma(1, 0, fake, None) == ra.RACE_ERR_INVALID_ARG
-    assert lib.race_attn_calibration_mfma((1 << 20) + 1, 1, fake, None) == ra.RACE_ERR_INVALID_ARG
+    assert lib.race_attn_calibration_mfma(1, 1, 0, None, None) == ra.RACE_ERR_INVALID_ARG
+    assert lib.race_attn_calibration_mfma(0, 1, 0, fake, None) == ra.RACE_ERR_INVALID_ARG
+    assert lib.race_attn_calibration_mfma(1, 0, 0, fake, None) == ra.RACE_ERR_INVALID_ARG
+    assert lib.race_attn_calibration_mfma((1 << 20) + 1, 1, 0, fake, None) == ra.RACE_ERR_INVALID_ARG
+    assert lib.race_attn_calibration_mfma(1, 1, 3, fake, None) == ra.RACE_ERR_INVALID_ARG
 
 
 def test_decode_entry_points_check_arguments_on_the_host():

@@ -156,3 +156,8 @@ def test_calibration_mfma_runs_and_fills_the_sink():
     torch.cuda.synchronize()
     assert flop == 16 * 4 * 8 * 4 * 32768
     assert torch.isfinite(sink).all() and (sink > 0).all()
+    for nv in (4, 8, 16):       # the variants with vector multiplies between the matrix instructions
+        sink.fill_(float("nan"))
+        ra.race_attn_calibration_mfma(16, 8, sink, vector_ops=nv)
+        torch.cuda.synchronize()
+        assert torch.isfinite(sink).all() and (sink > 0).all()
