@@ -343,9 +343,10 @@ def backward_streaming(Q, K, V, W, beta, L, P, causal, dO, with_beta: bool = Fal
     return dQ, dK, dV
 
 
-def beta_cotangent_l1(Q, K, V, W, beta, L, P, causal, dO) -> float:
-    """Sum of the absolute values of the terms ds_r (u . v_r) whose sum is d(beta) (N x N form): the scale
-    against which rounding errors of an implementation add up when the terms cancel."""
+def beta_cotangent_terms(Q, K, V, W, beta, L, P, causal, dO):
+    """The terms ds_r (u . v_r), one per (token of Q or K, table, hyperplane), whose sum is d(loss)/d(beta) (N x N
+    form; Algorithm 1, step 4: the logit of corner r is beta * (tanh(W x) . v_r)).  Returns (terms of Q, terms of K),
+    each (N, L, P)."""
     pq = soft_hash(Q, W, beta, L, P)
     pk = soft_hash(K, W, beta, L, P)
     S = np.einsum("ilr,jlr->ij", pq, pk) / L
@@ -354,12 +355,19 @@ def beta_cotangent_l1(Q, K, V, W, beta, L, P, causal, dO) -> float:
     den = S.sum(axis=1)
     O = (S / den[:, None]) @ V
     dS = M * ((dO @ V.T) - (dO * O).sum(axis=1)[:, None]) / den[:, None]
-    total = 0.0
+    out = []
     for X, phi, dphi in ((Q, pq, np.einsum("ij,jlr->ilr", dS, pk) / L), (K, pk, np.einsum("ij,ilr->jlr", dS, pq) / L)):
         u = np.tanh(project(X, W, L, P))
         ds = phi * (dphi - (phi * dphi).sum(axis=2, keepdims=True))
-        total += float(np.abs(np.einsum("nlr,rt->nlt", ds, corners(P)) * u).sum())
-    return total
+        out.append(np.einsum("nlr,rt->nlt", ds, corners(P)) * u)
+    return out[0], out[1]
+
+
+def beta_cotangent_l1(Q, K, V, W, beta, L, P, causal, dO) -> float:
+    """Sum of the absolute values of those terms: the scale against which rounding errors of an implementation add up
+    when the terms cancel."""
+    tq, tk = beta_cotangent_terms(Q, K, V, W, beta, L, P, causal, dO)
+    return float(np.abs(tq).sum() + np.abs(tk).sum())
 
 
 def finite_difference_beta(Q, K, V, W, beta, L, P, causal, dO, h: float = 1e-6) -> float:

@@ -145,12 +145,24 @@ def test_beta_gradient_c_oracle_matches_numpy_and_sums_over_heads():
         assert abs(db.sum() - fd) <= 1e-6 * max(1.0, abs(fd))
 
 
-def test_beta_l1_scale_bounds_the_cotangent():
+def test_beta_l1_scale_is_the_l1_norm_of_terms_that_sum_to_the_finite_difference():
+    # the tolerance scale of the d(beta) comparisons: its terms, summed with their signs, must be the derivative itself
+    # (central differences in beta, independent of the backward code); flipping or scaling dO leaves or scales the norm
     rng = np.random.default_rng(2)
     N, d, L, P, beta = 12, 5, 2, 3, 3.0
     Q, K, V, dO = (rng.standard_normal((N, d)) for _ in range(4))
     W = rng.standard_normal((L * P, d))
     for causal in (False, True):
+        tq, tk = ro.beta_cotangent_terms(Q, K, V, W, beta, L, P, causal, dO)
+        assert tq.shape == (N, L, P) and tk.shape == (N, L, P)
+        fd = ro.finite_difference_beta(Q, K, V, W, beta, L, P, causal, dO)
+        assert abs(tq.sum() + tk.sum() - fd) <= 1e-6 * max(1.0, abs(fd))
         *_, db = ro.backward_quadratic(Q, K, V, W, beta, L, P, causal, dO, with_beta=True)
         l1 = ro.beta_cotangent_l1(Q, K, V, W, beta, L, P, causal, dO)
+        assert abs(l1 - (np.abs(tq).sum() + np.abs(tk).sum())) <= 1e-12 * l1
         assert l1 >= abs(db) and l1 > 0
+        assert abs(ro.beta_cotangent_l1(Q, K, V, W, beta, L, P, causal, -dO) - l1) <= 1e-12 * l1
+        assert abs(ro.beta_cotangent_l1(Q, K, V, W, beta, L, P, causal, 3.0 * dO) - 3.0 * l1) <= 1e-12 * l1
+    # one token (causal): O = V whatever beta is, every term vanishes
+    tq, tk = ro.beta_cotangent_terms(Q[:1], K[:1], V[:1], W, beta, L, P, True, dO[:1])
+    assert np.abs(tq).max() <= 1e-15 and np.abs(tk).max() <= 1e-15
